@@ -1,0 +1,212 @@
+/*
+ * pact.h - C ABI of the MI355X (gfx950) implementation of PACT's token-reduction step:
+ * score and prune visual tokens (EUTI), cluster the survivors' keys (DBDPC), recover
+ * pruned tokens that lie close to a centre, merge each cluster into one token.
+ *
+ * Paper: "PACT: Pruning and Clustering-Based Token Reduction for Faster Visual Language
+ * Models" (arXiv 2504.08966).  Alg. 1 = EUTI, Alg. 2 = DBDPC, Alg. 3 = PACT, Alg. 4 =
+ * recursive centre identification (appendix D); Eq. 1 global query, Eq. 2 score, Eq. 3/4
+ * important / unimportant sets, Eq. 5 distance, Eq. 6 density, Eq. 8/9 recovery, Eq. 10 merge.
+ *
+ * Conventions shared by every entry point
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".  The caller owns all
+ *    buffers.  The library never allocates or frees device memory and never synchronises:
+ *    all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *  - Tensors are row-major and contiguous; every row must start on a 16-byte boundary
+ *    (PACT_ERR_ALIGN otherwise), which for contiguous rows means: base pointer 16-byte
+ *    aligned and row bytes a multiple of 16.
+ *  - Token indices written by the library are int32 and LOCAL to their sample (0..n-1).
+ *  - Data-dependent counts (kept tokens, centres, ...) stay on the device, in pact_report;
+ *    output buffers are sized by the caller for the worst case stated at each argument.
+ *    The host may read the report after synchronising the stream itself.
+ *  - Cluster ids are 0..C-1 in ascending order of the centre's token index, so `merged`
+ *    rows and `center_idx` are in sequence order and the position id of merged row s is
+ *    the caller's P[center_idx[s]] (Alg. 3 step 4).  cluster_id[i] = -1 means token i
+ *    was pruned and not recovered.
+ *  - Return value: PACT_OK, or an error code; on error nothing was enqueued and no output
+ *    was touched.  Data anomalies that cannot be seen without reading device memory
+ *    (zero-norm keys, non-finite values) are not errors: they follow the rules below and
+ *    are flagged in pact_report.
+ *  - `ws` is scratch of at least pact_workspace_bytes(...) bytes, 256-byte aligned.  Calls
+ *    that share a workspace must be ordered on one stream.
+ *
+ * Arithmetic (what "the same result as the definition" means here)
+ *  - Scores (Eq. 2) are evaluated in fp64 and rounded once to fp32; the percentile split
+ *    (Eq. 3/4) compares those fp32 values.
+ *  - Distances (Eq. 5) that decide something (within d_c of a centre or not, nearest centre,
+ *    within alpha*d_c or not) are evaluated in fp64 whenever the fp32 matrix-core value is
+ *    closer to the threshold than its worst-case rounding error, and always for the final
+ *    nearest-centre choice, so those decisions are the fp64 ones.
+ *  - Densities (Eq. 6) are fp64 sums of fp32 terms exp2-evaluated from matrix-core cosines.
+ *  - Ties: equal scores at the percentile are all kept; equal densities are processed in
+ *    ascending token index; equal distances pick the centre with the lower token index.
+ *  - A zero-norm key has cosine 0 (distance 1) to every other token; d_ii = 0.
+ */
+#ifndef PACT_H
+#define PACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PACT_OK = 0,
+    PACT_ERR_NULL = 1,      /* a required pointer is NULL */
+    PACT_ERR_SHAPE = 2,     /* a size is out of range or inconsistent */
+    PACT_ERR_DTYPE = 3,     /* unknown pact_dtype */
+    PACT_ERR_PARAM = 4,     /* lambda, d_c, d_n or alpha out of range */
+    PACT_ERR_WORKSPACE = 5, /* ws is NULL, misaligned or too small */
+    PACT_ERR_ALIGN = 6,     /* a tensor row is not 16-byte aligned */
+    PACT_ERR_HIP = 7,       /* a HIP call failed while enqueueing */
+    PACT_ERR_NOGPU = 8      /* no usable gfx950 device */
+} pact_status;
+
+typedef enum { PACT_F32 = 0, PACT_BF16 = 1 } pact_dtype;
+
+/* Limits.  n: tokens of one sample; batch: samples per varlen call. */
+#define PACT_MAX_TOKENS 32768
+#define PACT_MAX_BATCH 64
+#define PACT_MAX_QHEADS 64
+
+/* Hyper-parameters of Alg. 3 (host memory).  The paper's defaults: d_n = 2, alpha = 1.5,
+ * fallback_T = 10 (appendix D/E).  lambda in [0,1] is the fraction of tokens deemed
+ * unimportant; d_c >= 0; d_n > 0; alpha >= 0.  fallback_T >= 0 is Alg. 4's threshold: once a
+ * parallel round finds fewer than fallback_T new centres the remaining rounds are left to
+ * the single-workgroup finishing kernel.  It changes timing only, never the centres.
+ * flags: bit 0 (PACT_FLAG_NO_MERGE) writes the centre token's hidden state instead of the
+ * cluster mean (the paper's "no merging" ablation). */
+typedef struct {
+    float lambda;
+    float d_c;
+    float d_n;
+    float alpha;
+    int32_t fallback_T;
+    uint32_t flags;
+} pact_params;
+
+#define PACT_FLAG_NO_MERGE 1u
+
+/* Per-sample counters, in DEVICE memory, written by the entry points that produce them. */
+typedef struct {
+    int32_t n_kept;            /* |S_important| = q                         (pact_prune)   */
+    int32_t n_pruned;          /* |S_unimportant|                           (pact_prune)   */
+    int32_t n_centers;         /* C                                         (dbdpc_cluster) */
+    int32_t n_reincorporated;  /* pruned tokens recovered by Eq. 8          (pact_reincorporate) */
+    int32_t n_dropped;         /* pruned tokens not recovered                (pact_reincorporate) */
+    int32_t rounds;            /* parallel centre rounds that found work + finishing rounds */
+    int32_t dc_checked_pairs;  /* ordered kept pairs re-evaluated in fp64 near d_c */
+    int32_t dc_near_ties;      /* of those, pairs with |d - d_c| <= 1e-6 (each pair counted twice) */
+    int32_t refine_overflow;   /* 1 if the near-d_c list overflowed (pairs then keep fp32 decisions) */
+    int32_t zero_norm_seen;    /* kept or pruned tokens with a zero-norm clustering key */
+    int32_t reserved[6];
+} pact_report;
+
+/* Scratch bytes needed for one call on samples of at most n_max tokens each, `batch`
+ * samples, key width dk, n_q query heads of width d_h.  0 if an argument is out of range. */
+size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_q, int32_t d_h);
+
+/* Eq. 1 + Eq. 2 (Alg. 1 steps 1-2): importance score of every token.
+ *   hidden   [n, h]           h_dt   hidden states at the reduction layer
+ *   keys_pre [n, n_kv*d_h]    k_dt   keys before rotary embedding, heads concatenated
+ *   q        [q_rows, n_q*d_h] q_dt  queries before rotary embedding; q_rows == n (Eq. 1 is
+ *                                    applied) or q_rows == 1 (already the global query)
+ *   scores   [n] fp32 out
+ * n_q must be a multiple of n_kv: query head j reads key head j / (n_q / n_kv).  Softmax is
+ * taken across the n tokens inside each head; no 1/sqrt(d_h) factor (Eq. 2 has none). */
+int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+               const void* keys_pre, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+               const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+               float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 3/4 (Alg. 1 step 3): tau = the (m+1)-th smallest score, m = min(floor(lambda*n), n-1);
+ * kept = {s_i >= tau}, pruned = {s_i < tau}.
+ *   kept_idx [n], pruned_idx [n] out, ascending; only the first n_kept / n_pruned are written
+ *   rep      out: n_kept, n_pruned */
+int pact_prune(const float* scores, int32_t n, float lambda,
+               int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 2 on the subset `idx` of the n tokens (Eq. 5, Eq. 6, density order, centre selection
+ * with the bound d_c, nearest-centre assignment).
+ *   keys       [n, dk] k_dt   keys after rotary embedding, heads concatenated (u_i of Sec. 3.2)
+ *   idx        [*n_idx_dev] ascending token indices to cluster, or NULL = all n tokens
+ *   n_idx_dev  device int32 holding the subset size (ignored when idx is NULL)
+ *   center_idx [n] out: token indices of the C centres, ascending (first C written)
+ *   cluster_id [n] out: 0..C-1 for tokens in idx, -1 for the others
+ *   rep        out: n_centers, rounds, dc_* counters, zero_norm_seen; when idx is NULL also
+ *              n_kept = n, n_pruned = 0
+ *   rho_opt    [n] fp64 out or NULL: density of idx[p] at position p
+ *   rank_opt   [n] int32 out or NULL: position of idx[p] in the density order (0 = densest) */
+int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
+                  const int32_t* idx, const int32_t* n_idx_dev,
+                  float d_c, float d_n, int32_t fallback_T,
+                  int32_t* center_idx, int32_t* cluster_id, pact_report* rep,
+                  double* rho_opt, int32_t* rank_opt,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 8/9 (Alg. 3 step 3): each pruned token joins its nearest centre s iff d_is < alpha*d_c.
+ *   pruned_idx [rep->n_pruned], center_idx [rep->n_centers]  (counts are read on the device
+ *   from `rep`, as pact_prune and dbdpc_cluster left them)
+ *   cluster_id [n] in/out: entries of pruned tokens are overwritten (cluster or -1)
+ *   rep        in/out: n_reincorporated, n_dropped written */
+int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
+                       const int32_t* pruned_idx, const int32_t* center_idx,
+                       float d_c, float alpha, int32_t* cluster_id, pact_report* rep,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Eq. 10 (Alg. 3 step 4): merged[s] = mean of hidden[i] over cluster_id[i] == s.
+ *   cluster_id     [n] values in -1..C-1, C = rep->n_centers (read on the device)
+ *   center_idx     [C] needed only with PACT_FLAG_NO_MERGE (may be NULL otherwise)
+ *   merged         [n, h] out_dt, worst case; rows 0..C-1 written
+ *   cluster_counts [n] out: members per cluster (the weights W of Eq. 11) */
+int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+               const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+               uint32_t flags, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 3 end to end for one sample, one enqueue, no host synchronisation.
+ * Inputs as in pact_score (hidden, keys_pre, q) plus `keys` [n, dk = n_kv*d_h] for DBDPC
+ * (may alias keys_pre).  Outputs: scores [n], kept_idx [n], pruned_idx [n], center_idx [n],
+ * cluster_id [n], merged [n, h] out_dt, cluster_counts [n], rep (one record).  p: host. */
+int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+                const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                const pact_params* p,
+                float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                pact_report* rep, void* ws, size_t ws_bytes, void* stream);
+
+/* Alg. 3 for `batch` independent samples whose tokens are concatenated along dim 0.
+ *   cu_seqlens host int32 [batch+1], cu_seqlens[0] = 0, strictly increasing; sample b owns
+ *              rows cu_seqlens[b] .. cu_seqlens[b+1]-1 of every token-indexed tensor
+ *   q_rows     total tokens (per-token queries) or batch (one global query per sample)
+ *   p          host, [batch] parameter records
+ * Token-indexed outputs are laid out like the inputs: sample b's kept_idx / pruned_idx /
+ * center_idx / cluster_counts entries and merged rows start at offset cu_seqlens[b]; the
+ * indices stored are local to the sample.  rep: [batch] records. */
+int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
+                       const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                       const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                       const int32_t* cu_seqlens, int32_t batch, const pact_params* p,
+                       float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                       int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                       pact_report* rep, void* ws, size_t ws_bytes, void* stream);
+
+/* Optional per-kernel timing (for benchmarks; Sec. "Algo. Time" is what it decomposes).
+ * While enabled, every kernel the library enqueues is bracketed by events on its stream.
+ * pact_profile_read synchronises those events and returns the number of records since the
+ * last pact_profile_reset; names[i] points to a static string, ms[i] is the kernel's
+ * duration.  Host pointers.  Not thread-safe; leave disabled in production. */
+int pact_profile_enable(int on);
+int pact_profile_reset(void);
+int pact_profile_read(const char** names, float* ms, int32_t max_records);
+
+const char* pact_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACT_H */

@@ -1,0 +1,256 @@
+// Internal declarations shared by the HIP sources of libpact (gfx950 only).
+// Paper notation: n tokens, q kept tokens ("p-space" = position of a kept token in the
+// ascending kept list), C centres, d_c cutoff, d_n density normaliser, alpha recovery factor.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "pact.h"
+
+namespace pact {
+
+// ---------------------------------------------------------------------------------------
+// Batch descriptor: passed BY VALUE as a kernel argument (no device copy to manage).
+struct Seg {
+    int32_t base;     // first row of this sample in every token-indexed tensor
+    int32_t n;        // tokens in this sample
+    float lambda, d_c, d_n, alpha;
+    int32_t fallback_T;
+    uint32_t flags;
+};
+struct Batch {
+    int32_t B;        // samples in this launch (<= PACT_MAX_BATCH)
+    int32_t n_max;    // max tokens of one sample; pitch of per-sample workspace arrays
+    int32_t W;        // 64-bit words per bitmap row = ceil(n_max / 64)
+    int32_t total;    // tokens over all samples
+    Seg s[PACT_MAX_BATCH];
+};
+
+// ---------------------------------------------------------------------------------------
+// Workspace layout.  Offsets in bytes from the 256-aligned workspace base.
+constexpr int QG_CHUNKS = 128;        // row chunks of the global-query column sum
+constexpr int SCORE_TOK_PER_WG = 16;  // tokens per workgroup in the logits kernel
+constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
+constexpr int MAX_ROUNDS = 8;         // parallel centre rounds launched before the finishing kernel
+constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
+
+struct WsLayout {
+    size_t qg_part, qg, logits, hnorm, sm_part;        // score
+    size_t nn, rinv;                                   // key norms, per token (global row index)
+    size_t ident;                                      // identity index list (idx == NULL)
+    size_t adj;                                        // [B][n_max][W] u64: rows < q adjacency, rows q.. candidates
+    size_t rho_part;                                   // [B][W][n_max] f64
+    size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
+    size_t near_list, near_cnt, round_new;             // refine list, counters
+    size_t cursor, offsets, members;                   // merge CSR (global row index)
+    size_t total;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qcols, int64_t n_q) {
+    WsLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const int64_t W = (n_max + 63) / 64;
+    const int64_t smwg = (n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+    L.qg_part = take(sizeof(double) * B * QG_CHUNKS * qcols);
+    L.qg = take(sizeof(double) * B * qcols);
+    L.logits = take(sizeof(double) * total * n_q);
+    L.hnorm = take(sizeof(double) * total);
+    L.sm_part = take(sizeof(double) * B * smwg * n_q * 2);
+    L.nn = take(sizeof(double) * total);
+    L.rinv = take(sizeof(float) * total);
+    L.ident = take(sizeof(int32_t) * total);
+    L.adj = take(sizeof(uint64_t) * B * n_max * W);
+    L.rho_part = take(sizeof(double) * B * W * n_max);
+    L.rho = take(sizeof(double) * B * n_max);
+    L.rank = take(sizeof(int32_t) * B * n_max);
+    L.status = take(sizeof(uint32_t) * B * n_max);
+    L.cnum = take(sizeof(int32_t) * B * n_max);
+    L.cmask = take(sizeof(uint64_t) * B * W);
+    L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
+    L.near_cnt = take(sizeof(int32_t) * B);
+    L.round_new = take(sizeof(int32_t) * B * MAX_ROUNDS);
+    L.cursor = take(sizeof(int32_t) * total);
+    L.offsets = take(sizeof(int32_t) * (total + B));
+    L.members = take(sizeof(int32_t) * total);
+    L.total = off;
+    return L;
+}
+
+// Resolved device pointers for one call.
+struct Ws {
+    double* qg_part; double* qg; double* logits; double* hnorm; double* sm_part;
+    double* nn; float* rinv; int32_t* ident;
+    uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
+    int32_t* cnum; uint64_t* cmask; uint32_t* near_list; int32_t* near_cnt; int32_t* round_new;
+    int32_t* cursor; int32_t* offsets; int32_t* members;
+};
+
+inline Ws resolve(void* base, const WsLayout& L) {
+    char* p = (char*)base;
+    Ws w;
+    w.qg_part = (double*)(p + L.qg_part); w.qg = (double*)(p + L.qg);
+    w.logits = (double*)(p + L.logits); w.hnorm = (double*)(p + L.hnorm);
+    w.sm_part = (double*)(p + L.sm_part);
+    w.nn = (double*)(p + L.nn); w.rinv = (float*)(p + L.rinv); w.ident = (int32_t*)(p + L.ident);
+    w.adj = (uint64_t*)(p + L.adj); w.rho_part = (double*)(p + L.rho_part);
+    w.rho = (double*)(p + L.rho); w.rank = (int32_t*)(p + L.rank);
+    w.status = (uint32_t*)(p + L.status); w.cnum = (int32_t*)(p + L.cnum);
+    w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
+    w.near_cnt = (int32_t*)(p + L.near_cnt); w.round_new = (int32_t*)(p + L.round_new);
+    w.cursor = (int32_t*)(p + L.cursor); w.offsets = (int32_t*)(p + L.offsets);
+    w.members = (int32_t*)(p + L.members);
+    return w;
+}
+
+// ---------------------------------------------------------------------------------------
+// Kernel launch bookkeeping (optional per-kernel events).
+void prof_begin(const char* name, hipStream_t s);
+void prof_end(hipStream_t s);
+
+#define PACT_LAUNCH(name, kernel, grid, block, stream, ...)                        \
+    do {                                                                           \
+        ::pact::prof_begin(name, stream);                                          \
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);           \
+        ::pact::prof_end(stream);                                                  \
+        if (hipGetLastError() != hipSuccess) return PACT_ERR_HIP;                  \
+    } while (0)
+
+#define PACT_LAUNCH_SHMEM(name, kernel, grid, block, shmem, stream, ...)          \
+    do {                                                                           \
+        ::pact::prof_begin(name, stream);                                          \
+        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);       \
+        ::pact::prof_end(stream);                                                  \
+        if (hipGetLastError() != hipSuccess) return PACT_ERR_HIP;                  \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------
+// Stage launchers (host).  Each enqueues on `st` and returns a pact_status.
+struct ScoreIn {
+    const void* hidden; pact_dtype h_dt; int32_t h;
+    const void* keys_pre; pact_dtype k_dt; int32_t n_kv, d_h;
+    const void* q; pact_dtype q_dt; int32_t q_per_token; int32_t n_q;   // q_per_token: 1 = [total, ..], 0 = [B, ..]
+};
+
+int launch_init(const Batch& bt, const Ws& w, pact_report* rep, int32_t* cluster_id,
+                int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st);
+int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, float* scores, hipStream_t st);
+int launch_prune(const Batch& bt, const float* scores, int32_t* kept_idx, int32_t* pruned_idx,
+                 pact_report* rep, hipStream_t st);
+int launch_key_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                    pact_report* rep, hipStream_t st);
+int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                        const int32_t* idx, pact_report* rep, hipStream_t st);
+int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                   const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
+                   int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
+                   hipStream_t st);
+int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                         const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
+                         int32_t* cluster_counts, pact_report* rep, hipStream_t st);
+int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
+                 const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+                 void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
+                 hipStream_t st);
+
+// init modes
+enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_MERGE = 4 };
+
+// Worst-case rounding error of an fp32 matrix-core cosine of two dk-long rows, plus slack for
+// the scaling multiplies; decisions closer than this to a threshold are re-made in fp64.
+inline double cos_margin(int dk) { return (double)(dk + 16) * (1.0 / 8388608.0) + 2e-6; }
+
+}  // namespace pact
+
+// ---------------------------------------------------------------------------------------
+// Device helpers
+#ifdef __HIPCC__
+namespace pact {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+
+// Counts read back from a device-side report are clamped to the sample size, so that a report
+// the caller never initialised cannot send a kernel out of bounds.
+__device__ __forceinline__ int clamp_count(int v, int n) { return v < 0 ? 0 : (v > n ? n : v); }
+
+// 16 bytes of a row -> up to 8 doubles.  EPL = elements per 16-byte load.
+template <int DT> struct Elem;
+template <> struct Elem<PACT_BF16> {
+    static constexpr int EPL = 8;
+    static constexpr int BYTES = 2;
+    __device__ static __forceinline__ void widen(const uint4& v, double* out) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = (double)__uint_as_float(w[i] << 16);
+            out[2 * i + 1] = (double)__uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ void widenf(const uint4& v, float* out) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+template <> struct Elem<PACT_F32> {
+    static constexpr int EPL = 4;
+    static constexpr int BYTES = 4;
+    __device__ static __forceinline__ void widen(const uint4& v, double* out) {
+        out[0] = (double)__uint_as_float(v.x); out[1] = (double)__uint_as_float(v.y);
+        out[2] = (double)__uint_as_float(v.z); out[3] = (double)__uint_as_float(v.w);
+    }
+    __device__ static __forceinline__ void widenf(const uint4& v, float* out) {
+        out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y);
+        out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
+    }
+};
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
+    return v;   // butterfly: every lane ends with the bit-identical total
+}
+__device__ __forceinline__ double wave_max_f64(double v) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) v = fmax(v, __shfl_xor(v, s, 64));
+    return v;
+}
+
+// fp64 dot product of two rows of dk elements, computed by one full wavefront; the partition
+// of elements over lanes and the reduction tree are fixed, so dot(a,b) of bit-identical rows
+// equals dot(a,a) bit for bit.
+template <int DT>
+__device__ __forceinline__ double wave_dot64(const char* ra, const char* rb, int dk, int lane) {
+    constexpr int EPL = Elem<DT>::EPL;
+    double acc = 0.0;
+    for (int e = lane * EPL; e < dk; e += 64 * EPL) {
+        const uint4 va = *(const uint4*)(ra + (size_t)e * Elem<DT>::BYTES);
+        const uint4 vb = *(const uint4*)(rb + (size_t)e * Elem<DT>::BYTES);
+        double a[8], b[8];
+        Elem<DT>::widen(va, a);
+        Elem<DT>::widen(vb, b);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
+    }
+    return wave_sum_f64(acc);
+}
+
+// Eq. 5 in fp64 from a dot product and the two squared norms; zero vector -> cosine 0.
+__device__ __forceinline__ double cos_dist64(double dot, double nna, double nnb) {
+    const double den = sqrt(nna * nnb);
+    const double c = den > 0.0 ? dot / den : 0.0;
+    return fmin(fmax(1.0 - c, 0.0), 2.0);
+}
+
+}  // namespace pact
+#endif

@@ -1,0 +1,207 @@
+// Merge (Eq. 10, Alg. 3 step 4): h'_s = mean of the hidden states of cluster s.
+// Member lists are built with integer atomics (their order inside a cluster is then sorted,
+// so the fp64 accumulation order - ascending token index - and hence every output bit is
+// the same on every run).  The stage is bound by reading the member rows of H once and
+// writing C rows.
+#include "pact_internal.h"
+
+namespace pact {
+
+// Recount members (stand-alone pact_merge).  grid (ceil(n_max/256), B), block 256.
+__global__ __launch_bounds__(256) void count_members_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
+                                                            const pact_report* __restrict__ rep,
+                                                            int32_t* cluster_counts) {
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sg.n) return;
+    const int cid = cluster_id[sg.base + i];
+    if (cid >= 0 && cid < clamp_count(rep[b].n_centers, sg.n)) atomicAdd(&cluster_counts[sg.base + cid], 1);
+}
+
+// Exclusive scan of the cluster sizes -> CSR offsets; clears the fill cursors.
+// grid (B), block 1024.  offsets of sample b live at [base + b, base + b + C].
+__global__ __launch_bounds__(1024) void scan_offsets_kernel(Batch bt, const pact_report* __restrict__ rep,
+                                                            const int32_t* __restrict__ cluster_counts,
+                                                            int32_t* offsets, int32_t* cursor) {
+    __shared__ int s_wtot[16];
+    const int b = blockIdx.x;
+    const Seg sg = bt.s[b];
+    const int C = clamp_count(rep[b].n_centers, sg.n);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t* cnt = cluster_counts + sg.base;
+    int32_t* off = offsets + sg.base + b;
+    int32_t* cur = cursor + sg.base;
+    const int chunk = (C + 1023) / 1024;
+    const int c0 = min(C, tid * chunk), c1 = min(C, c0 + chunk);
+    int loc = 0;
+    for (int c = c0; c < c1; ++c) loc += cnt[c];
+    int inc = loc;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int v = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += v;
+    }
+    if (lane == 63) s_wtot[wave] = inc;
+    __syncthreads();
+    int run = inc - loc;
+    for (int w = 0; w < wave; ++w) run += s_wtot[w];
+    for (int c = c0; c < c1; ++c) {
+        off[c] = run;
+        cur[c] = 0;
+        run += cnt[c];
+    }
+    if (c1 == C && c0 < C) off[C] = run;
+    if (C == 0 && tid == 0) off[0] = 0;
+}
+
+// grid (ceil(n_max/256), B), block 256.
+__global__ __launch_bounds__(256) void fill_members_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
+                                                           const pact_report* __restrict__ rep,
+                                                           const int32_t* __restrict__ offsets,
+                                                           int32_t* cursor, int32_t* members) {
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= sg.n) return;
+    const int cid = cluster_id[sg.base + i];
+    if (cid < 0 || cid >= clamp_count(rep[b].n_centers, sg.n)) return;
+    const int pos = atomicAdd(&cursor[sg.base + cid], 1);
+    members[sg.base + offsets[sg.base + b + cid] + pos] = i;
+}
+
+constexpr int MERGE_LDS_MEMBERS = 1024;
+
+template <int ODT> struct StoreOut;
+template <> struct StoreOut<PACT_F32> {
+    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v) {
+        float* o = (float*)out + e;
+#pragma unroll
+        for (int i = 0; i < N; i += 4) *(float4*)(o + i) = make_float4((float)v[i], (float)v[i + 1], (float)v[i + 2], (float)v[i + 3]);
+    }
+};
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+template <> struct StoreOut<PACT_BF16> {
+    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v) {
+        uint16_t* o = (uint16_t*)out + e;
+        uint32_t w[N / 2];
+#pragma unroll
+        for (int i = 0; i < N; i += 2)
+            w[i / 2] = f32_to_bf16_rne((float)v[i]) | (f32_to_bf16_rne((float)v[i + 1]) << 16);
+        if (N == 8) *(uint4*)o = make_uint4(w[0], w[1], w[2], w[3]);
+        else *(uint2*)o = make_uint2(w[0], w[1]);
+    }
+};
+
+// One workgroup per cluster (persistent over clusters).  grid (min(n_max, 4096), B), block 256.
+template <int HDT, int ODT>
+__global__ __launch_bounds__(256) void merge_kernel(Batch bt, const char* __restrict__ hidden, int h,
+                                                     const int32_t* __restrict__ cluster_id,
+                                                     const int32_t* __restrict__ center_idx,
+                                                     const pact_report* __restrict__ rep,
+                                                     const int32_t* __restrict__ cluster_counts,
+                                                     const int32_t* __restrict__ offsets,
+                                                     const int32_t* __restrict__ members,
+                                                     char* __restrict__ merged) {
+    __shared__ int s_raw[MERGE_LDS_MEMBERS];
+    __shared__ int s_sorted[MERGE_LDS_MEMBERS];
+    constexpr int EPL = Elem<HDT>::EPL;
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int C = clamp_count(rep[b].n_centers, sg.n);
+    const int tid = threadIdx.x;
+    const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
+    const char* hb = hidden + (size_t)sg.base * hrow;
+    const bool no_merge = (sg.flags & PACT_FLAG_NO_MERGE) != 0;
+
+    for (int c = blockIdx.x; c < C; c += gridDim.x) {
+        int m = cluster_counts[sg.base + c];
+        bool in_lds = true;
+        __syncthreads();                       // previous cluster's readers are done with the LDS lists
+        if (no_merge) {
+            if (tid == 0) s_sorted[0] = center_idx[sg.base + c];
+        } else if (m <= MERGE_LDS_MEMBERS) {
+            const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
+            for (int k = tid; k < m; k += 256) s_raw[k] = mem[k];
+            __syncthreads();
+            for (int k = tid; k < m; k += 256) {
+                const int v = s_raw[k];
+                int pos = 0;
+                for (int u = 0; u < m; ++u) pos += (s_raw[u] < v);
+                s_sorted[pos] = v;
+            }
+        } else {
+            in_lds = false;
+        }
+        __syncthreads();
+        const int m_eff = no_merge ? 1 : m;
+        for (int e = tid * EPL; e < h; e += 256 * EPL) {
+            double acc[EPL];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = 0.0;
+            if (in_lds) {
+                for (int k = 0; k < m_eff; ++k) {
+                    const uint4 v = *(const uint4*)(hb + (size_t)s_sorted[k] * hrow + (size_t)e * Elem<HDT>::BYTES);
+                    double x[8];
+                    Elem<HDT>::widen(v, x);
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) acc[i] += x[i];
+                }
+            } else {
+                // very large cluster: walk the tokens in index order (no list to sort)
+                for (int t = 0; t < sg.n; ++t) {
+                    if (cluster_id[sg.base + t] != c) continue;
+                    const uint4 v = *(const uint4*)(hb + (size_t)t * hrow + (size_t)e * Elem<HDT>::BYTES);
+                    double x[8];
+                    Elem<HDT>::widen(v, x);
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) acc[i] += x[i];
+                }
+            }
+            double outv[EPL];
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : acc[i] / (double)m_eff;
+            StoreOut<ODT>::template put<EPL>(merged + ((size_t)sg.base + c) * (size_t)h * (ODT == PACT_BF16 ? 2 : 4),
+                                             (size_t)e, outv);
+        }
+    }
+}
+
+template <int HDT>
+static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int32_t h,
+                          const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+                          void* merged, pact_dtype out_dt, const int32_t* cluster_counts, hipStream_t st) {
+    dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
+    if (out_dt == PACT_BF16)
+        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(256), st, bt, (const char*)hidden,
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
+    else
+        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(256), st, bt, (const char*)hidden,
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
+    return PACT_OK;
+}
+
+int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
+                 const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+                 void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
+                 hipStream_t st) {
+    dim3 gtok((bt.n_max + 255) / 256, bt.B);
+    if (recount)
+        PACT_LAUNCH("count_members", count_members_kernel, gtok, dim3(256), st, bt, cluster_id, rep,
+                    cluster_counts);
+    PACT_LAUNCH("scan_offsets", scan_offsets_kernel, dim3(bt.B), dim3(1024), st, bt, rep, cluster_counts,
+                w.offsets, w.cursor);
+    PACT_LAUNCH("fill_members", fill_members_kernel, gtok, dim3(256), st, bt, cluster_id, rep, w.offsets,
+                w.cursor, w.members);
+    if (h_dt == PACT_BF16)
+        return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
+                                         cluster_counts, st);
+    return launch_merge_k<PACT_F32>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
+                                    cluster_counts, st);
+}
+
+}  // namespace pact

@@ -1,0 +1,110 @@
+"""The C-ABI library loads and exports every symbol include/pact.h declares; argument
+validation answers before anything touches a GPU.  CPU only (no compute calls)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2504_08966_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pact.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:pact|dbdpc)_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load_library()
+    names = declared_functions()
+    assert {"pact_score", "pact_prune", "dbdpc_cluster", "pact_reincorporate", "pact_merge",
+            "pact_reduce", "pact_reduce_varlen", "pact_workspace_bytes", "pact_strerror"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None, name
+
+
+def test_workspace_size_is_monotone_and_bounded():
+    a = P.pact_workspace_bytes(729, 1, 128, 2, 64)
+    b = P.pact_workspace_bytes(7290, 1, 512, 4, 128)
+    c = P.pact_workspace_bytes(7290, 8, 512, 4, 128)
+    assert 0 < a < b < c and b < 64 << 20
+    assert P.pact_workspace_bytes(0, 1, 128, 2, 64) == 0
+    assert P.pact_workspace_bytes(1 << 20, 1, 128, 2, 64) == 0
+    assert P.pact_workspace_bytes(729, 65, 128, 2, 64) == 0
+    assert P.pact_workspace_bytes(729, 1, 128, 65, 64) == 0
+
+
+def test_strerror_covers_all_codes():
+    msgs = [P.pact_strerror(i) for i in range(9)]
+    assert msgs[0] == "ok" and len(set(msgs)) == 9
+    assert P.pact_strerror(99) == "unknown status"
+
+
+def test_argument_validation_is_host_side():
+    """Bad arguments are rejected before any GPU call: NULL pointers, sizes, parameters,
+    alignment, workspace.  Fake non-NULL addresses are never dereferenced on these paths."""
+    lib = P.load_library()
+    fake = C.c_void_p(0x1000)          # 16-byte and 256-byte aligned, never touched
+    odd = C.c_void_p(0x1008)
+    ws_bytes = 1 << 30
+    NULL, SHAPE, DTYPE, PARAM, WS, ALIGN = 1, 2, 3, 4, 5, 6
+    # pact_prune
+    assert lib.pact_prune(None, 10, 0.5, fake, fake, fake, None, 0, None) == NULL
+    assert lib.pact_prune(fake, 0, 0.5, fake, fake, fake, None, 0, None) == SHAPE
+    assert lib.pact_prune(fake, 10, 1.5, fake, fake, fake, None, 0, None) == PARAM
+    assert lib.pact_prune(fake, 10, float("nan"), fake, fake, fake, None, 0, None) == PARAM
+    # pact_score
+    sc = lambda **k: lib.pact_score(k.get("hidden", fake), k.get("h_dt", 0), k.get("n", 16), k.get("h", 64),
+                                    fake, k.get("k_dt", 0), k.get("n_kv", 2), k.get("d_h", 8), fake, 0,
+                                    k.get("q_rows", 16), k.get("n_q", 2), k.get("scores", fake),
+                                    k.get("ws", fake), k.get("ws_bytes", ws_bytes), None)
+    assert sc(hidden=None) == NULL and sc(scores=None) == NULL
+    assert sc(n=0) == SHAPE and sc(n_q=3) == SHAPE and sc(q_rows=5) == SHAPE and sc(n=1 << 20) == SHAPE
+    assert sc(h_dt=7) == DTYPE
+    assert sc(h=3) == ALIGN and sc(hidden=odd) == ALIGN and sc(d_h=2) == ALIGN
+    assert sc(ws=None) == WS and sc(ws_bytes=16) == WS and sc(ws=C.c_void_p(0x1010)) == WS
+    # dbdpc_cluster
+    db = lambda **k: lib.dbdpc_cluster(k.get("keys", fake), k.get("dt", 1), k.get("n", 16), k.get("dk", 64),
+                                       k.get("idx", None), k.get("n_idx", None), k.get("d_c", 0.1),
+                                       k.get("d_n", 2.0), k.get("T", 10), fake, fake, fake, None, None,
+                                       fake, k.get("ws_bytes", ws_bytes), None)
+    assert db(keys=None) == NULL and db(idx=fake) == NULL
+    assert db(d_c=-0.1) == PARAM and db(d_n=0.0) == PARAM and db(T=-1) == PARAM
+    assert db(d_c=float("inf")) == PARAM
+    assert db(dk=4) == ALIGN and db(dt=5) == DTYPE and db(n=-3) == SHAPE and db(ws_bytes=1000) == WS
+    # pact_reincorporate / pact_merge
+    assert lib.pact_reincorporate(fake, 1, 16, 64, None, fake, 0.1, 1.5, fake, fake, fake, ws_bytes, None) == NULL
+    assert lib.pact_reincorporate(fake, 1, 16, 64, fake, fake, 0.1, -1.0, fake, fake, fake, ws_bytes, None) == PARAM
+    assert lib.pact_merge(fake, 1, 16, 64, fake, None, fake, 1, fake, 0, fake, fake, ws_bytes, None) == NULL
+    assert lib.pact_merge(fake, 1, 16, 64, fake, None, fake, 0, fake, 9, fake, fake, ws_bytes, None) == DTYPE
+    assert lib.pact_merge(fake, 1, 16, 60, fake, None, fake, 0, fake, 0, fake, fake, ws_bytes, None) == ALIGN
+    # pact_reduce / pact_reduce_varlen
+    prm = P.PactParams(0.45, 0.02).c()
+    rd = lambda p, **k: lib.pact_reduce(fake, 1, k.get("n", 16), 64, fake, k.get("keys", fake), 1, 2, 8, fake,
+                                        1, k.get("q_rows", 16), 2, p, fake, fake, fake, fake, fake,
+                                        k.get("merged", fake), 0, fake, fake, fake, k.get("ws_bytes", ws_bytes), None)
+    assert rd(None) == NULL and rd(C.byref(prm), keys=None) == NULL and rd(C.byref(prm), merged=None) == NULL
+    assert rd(C.byref(prm), n=0) == SHAPE and rd(C.byref(prm), q_rows=3) == SHAPE
+    assert rd(C.byref(prm), ws_bytes=64) == WS
+    bad = P.PactParams(0.45, 0.02, d_n=-1.0).c()
+    assert rd(C.byref(bad)) == PARAM
+    cu_bad = (C.c_int32 * 3)(0, 8, 8)          # empty second sample
+    cu_ok = (C.c_int32 * 3)(0, 8, 16)
+    pa = (type(prm) * 2)(prm, prm)
+    vl = lambda cu, batch=2, wsb=ws_bytes: lib.pact_reduce_varlen(
+        fake, 1, 64, fake, fake, 1, 2, 8, fake, 1, 16, 2, cu, batch, pa, fake, fake, fake, fake, fake, fake,
+        0, fake, fake, fake, wsb, None)
+    assert vl(cu_bad) == SHAPE and vl(cu_ok, batch=0) == SHAPE and vl(cu_ok, wsb=10) == WS
+    assert vl(None) == NULL
+
+
+def test_valid_call_without_gpu_reports_no_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("this check is for boxes without a GPU")
+    lib = P.load_library()
+    fake = C.c_void_p(0x1000)
+    assert lib.pact_prune(fake, 10, 0.5, fake, fake, fake, None, 0, None) == 8
