@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the PACT token-reduction hot path on one MI355X.
+
+One "step" = one pact_reduce (score -> prune -> DBDPC -> recovery -> merge) over one
+synthetic LLaVA-OneVision-7B-shaped anyres image: N = 7290 tokens, hidden 3584, keys 512
+(4 KV heads x 128), bf16, lambda = 0.45, d_c calibrated for ~71% total reduction.  Inputs,
+outputs and workspace are resident in HBM before the timed region; the timed region is K
+back-to-back calls bracketed by device synchronisation.
+
+Prints ONE JSON line (see README): whole-job images/s, ms per step, the roofline
+record of the dominant kernel (per-kernel durations measured with HIP events recorded by the
+library on the launch stream, in a separate pass right after the timed one) and the CPU
+oracle timed on this machine's host cores on the same input.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def algorithmic_work(kernel: str, n, h, dk, q, C, n_reinc, key_bytes, hid_bytes, out_bytes, n_q, d_h):
+    """(bound, work, unit) of one launch of `kernel`: algorithmic flops or HBM bytes."""
+    if kernel == "gram_density":          # unique pairs: q^2/2 dot products of length dk, 2 flops each
+        return "mfma", float(q) * q * dk, "flop"
+    if kernel == "gram_candidates":
+        return "mfma", 2.0 * (n - q) * C * dk, "flop"
+    if kernel == "score_logits":          # read H and K_pre once, write logits and norms
+        return "hbm", n * h * hid_bytes + n * dk * key_bytes + n * (n_q + 1) * 8, "B"
+    if kernel == "qglobal_partial":
+        return "hbm", n * n_q * d_h * key_bytes, "B"
+    if kernel == "merge_mean":            # read member rows once, write C merged rows
+        return "hbm", (q + n_reinc) * h * hid_bytes + C * h * out_bytes, "B"
+    if kernel == "key_prep":
+        return "hbm", n * dk * key_bytes + n * ((n + 63) // 64) * 8, "B"
+    return None, 0.0, ""
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-table", action="store_true", help="print per-kernel averages to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (samples are independent; "
+              "see DESIGN.md, 'How it would shard'). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2504_08966_amd as P
+    from pact_synth import gen
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    P.load_library()
+
+    cfg = gen.CONFIGS["img_7b"]
+    s = gen.make_sample(cfg, args.seed)
+    with open(os.path.join(ROOT, "pact_synth", "manifest.json")) as f:
+        man = json.load(f)[f"img_7b:s{args.seed}:g{cfg.grids}:l{cfg.lam:.2f}"]
+    d_c = man["d_c"]
+    n, h, dk = s.n, cfg.hidden, cfg.dk
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda().to(torch.bfloat16)
+
+    hidden, keys, q = dev(s.hidden), dev(s.keys.reshape(n, -1)), dev(s.queries.reshape(n, -1))
+    prm = P.PactParams(s.lam, d_c, 2.0, 1.5)
+    ws = P.alloc_workspace(n, 1, dk, cfg.n_kv, cfg.d_h)
+    out = P.pact_reduce(hidden, keys, keys, q, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws)
+
+    def step():
+        P.pact_reduce(hidden, keys, keys, q, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    rep = P.read_report(out["rep"])
+    assert rep["n_kept"] == man["q"] and rep["n_centers"] == man["C"], (rep, man)
+
+    # per-kernel durations: library-side HIP events on the launch stream, separate pass
+    P.pact_profile_enable(True)
+    P.pact_profile_reset()
+    prof_steps = min(args.steps, 50)
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    recs = P.pact_profile_read(prof_steps * 64)
+    P.pact_profile_enable(False)
+    tot, cnt = {}, {}
+    for name, ms in recs:
+        tot[name] = tot.get(name, 0.0) + ms
+        cnt[name] = cnt.get(name, 0) + 1
+    per_step = {k: v / prof_steps for k, v in tot.items()}          # ms per step, all launches of k
+    per_launch = {k: tot[k] / cnt[k] for k in tot}
+    if args.kernel_table:
+        for k in sorted(per_step, key=per_step.get, reverse=True):
+            print(f"  {k:18s} {per_step[k] * 1e3:9.2f} us/step  {cnt[k] // prof_steps} launch(es)  "
+                  f"{per_launch[k] * 1e3:9.2f} us/launch", file=sys.stderr)
+        print(f"  sum of kernels      {sum(per_step.values()) * 1e3:9.2f} us/step; wall {ms_per_step * 1e3:.2f} us/step",
+              file=sys.stderr)
+
+    q_kept, C, n_re = rep["n_kept"], rep["n_centers"], rep["n_reincorporated"]
+    roof = None
+    for k in sorted(per_step, key=per_step.get, reverse=True):
+        bound, work, unit = algorithmic_work(k, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
+        if bound is None:
+            continue
+        sec = per_launch[k] * 1e-3
+        if bound == "mfma":
+            ach, peak, u = work / sec / 1e12, PEAK_MFMA_TFLOPS["bf16"], "TFLOP/s"
+        else:
+            ach, peak, u = work / sec / 1e9, PEAK_HBM_GBS, "GB/s"
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(k)
+        roof = {"kernel": k, "bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": u,
+                "frac": round(ach / peak, 4), "traffic": traffic, "us_per_launch": round(sec * 1e6, 2),
+                "work_per_launch": work, "work_unit": unit,
+                "share_of_step": round(per_step[k] / sum(per_step.values()), 3)}
+        break
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import pact_oracle as po
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            cores = 1
+        reps, t_cpu = 0, 0.0
+        while reps < 3 or (t_cpu < 10.0 and reps < 8):
+            t1 = time.perf_counter()
+            po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        cpu = {"value": round(reps / t_cpu, 4), "unit": "images/s", "cores": cores, "kind": "oracle",
+               "sample": f"{reps} runs of the fp64 numpy oracle's pact_reduce on the same image "
+                         f"(matmuls on {cores} BLAS threads, the rest on one thread)",
+               "ms_per_step": round(t_cpu / reps * 1e3, 1)}
+
+    line = {
+        "metric": "images/sec per pact_reduce at N=7290, Dk=512", "value": round(args.steps / dt, 2),
+        "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "us_per_pact_reduce": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "LLaVA-OV-7B-shaped anyres image, N=7290 (10x729), H=3584, Dk=512 (4x128) bf16, "
+                               "lambda=0.45, d_n=2, alpha=1.5, d_c=%.6f (71%% reduction), batch 1" % d_c,
+                   "seed": args.seed, "q": q_kept, "C": C, "n_reincorporated": n_re,
+                   "rounds": rep["rounds"], "dc_checked_pairs": rep["dc_checked_pairs"]},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernels_us_per_step": {k: round(v * 1e3, 2) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
