@@ -90,13 +90,14 @@ struct ReduceIO {
 
 static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStream_t st) {
     const int32_t dk = io.n_kv * io.d_h;
-    int rc = launch_init(bt, w, io.rep, io.cluster_id, io.cluster_counts, INIT_REDUCE, nullptr, st);
+    int rc = launch_prep(bt, w, io.keys, io.k_dt, dk, io.q_per_token ? io.q : nullptr, io.q_dt,
+                         io.n_q * io.d_h, io.rep, io.cluster_id, io.cluster_counts, INIT_REDUCE, nullptr, st);
     if (rc) return rc;
     ScoreIn si{io.hidden, io.h_dt, io.h, io.keys_pre, io.k_dt, io.n_kv, io.d_h, io.q, io.q_dt,
                io.q_per_token, io.n_q};
-    if ((rc = launch_score(bt, w, si, io.scores, st))) return rc;
-    if ((rc = launch_prune(bt, io.scores, io.kept_idx, io.pruned_idx, io.rep, st))) return rc;
-    if ((rc = launch_key_prep(bt, w, io.keys, io.k_dt, dk, io.rep, st))) return rc;
+    if ((rc = launch_score(bt, w, si, st))) return rc;
+    if ((rc = launch_score_prune(bt, w, io.n_q, false, io.scores, io.kept_idx, io.pruned_idx, io.rep, st)))
+        return rc;
     if ((rc = launch_gram_density(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.rep, st))) return rc;
     if ((rc = launch_centres(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.center_idx, io.cluster_id,
                              io.cluster_counts, io.rep, nullptr, nullptr, st))) return rc;
@@ -139,14 +140,20 @@ int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     Batch bt;
     fill_single(bt, n, default_params());
     const Ws w = resolve(ws, L);
+    hipStream_t st = (hipStream_t)stream;
     ScoreIn si{hidden, h_dt, h, keys_pre, k_dt, n_kv, d_h, q, q_dt, q_rows == n ? 1 : 0, n_q};
-    return launch_score(bt, w, si, scores, (hipStream_t)stream);
+    if (si.q_per_token &&
+        (rc = launch_prep(bt, w, nullptr, k_dt, 0, q, q_dt, n_q * d_h, nullptr, nullptr, nullptr, INIT_SCORE,
+                          nullptr, st)))
+        return rc;
+    if ((rc = launch_score(bt, w, si, st))) return rc;
+    return launch_score_only(bt, w, n_q, scores, st);
 }
 
 int pact_prune(const float* scores, int32_t n, float lambda,
                int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep,
                void* ws, size_t ws_bytes, void* stream) {
-    (void)ws; (void)ws_bytes;
+    (void)ws; (void)ws_bytes;       // the split needs no scratch
     if (!scores || !kept_idx || !pruned_idx || !rep) return PACT_ERR_NULL;
     if (n < 1 || n > PACT_MAX_TOKENS) return PACT_ERR_SHAPE;
     if (!(lambda >= 0.0f && lambda <= 1.0f)) return PACT_ERR_PARAM;
@@ -156,7 +163,10 @@ int pact_prune(const float* scores, int32_t n, float lambda,
     p.lambda = lambda;
     Batch bt;
     fill_single(bt, n, p);
-    return launch_prune(bt, scores, kept_idx, pruned_idx, rep, (hipStream_t)stream);
+    Ws none;
+    std::memset(&none, 0, sizeof(none));
+    return launch_score_prune(bt, none, 1, true, const_cast<float*>(scores), kept_idx, pruned_idx, rep,
+                              (hipStream_t)stream);
 }
 
 int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
@@ -181,10 +191,9 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     fill_single(bt, n, p);
     const Ws w = resolve(ws, L);
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_init(bt, w, rep, cluster_id, nullptr, idx ? INIT_DBDPC_SUBSET : INIT_DBDPC_ALL,
-                          n_idx_dev, st))) return rc;
+    if ((rc = launch_prep(bt, w, keys, k_dt, dk, nullptr, PACT_F32, 0, rep, cluster_id, nullptr,
+                          idx ? INIT_DBDPC_SUBSET : INIT_DBDPC_ALL, n_idx_dev, st))) return rc;
     const int32_t* use_idx = idx ? idx : w.ident;
-    if ((rc = launch_key_prep(bt, w, keys, k_dt, dk, rep, st))) return rc;
     if ((rc = launch_gram_density(bt, w, keys, k_dt, dk, use_idx, rep, st))) return rc;
     return launch_centres(bt, w, keys, k_dt, dk, use_idx, center_idx, cluster_id, nullptr, rep, rho_opt,
                           rank_opt, st);
@@ -208,8 +217,8 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     fill_single(bt, n, p);
     const Ws w = resolve(ws, L);
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_init(bt, w, rep, cluster_id, nullptr, INIT_REINC, nullptr, st))) return rc;
-    if ((rc = launch_key_prep(bt, w, keys, k_dt, dk, rep, st))) return rc;
+    if ((rc = launch_prep(bt, w, keys, k_dt, dk, nullptr, PACT_F32, 0, rep, cluster_id, nullptr, INIT_REINC,
+                          nullptr, st))) return rc;
     return launch_reincorporate(bt, w, keys, k_dt, dk, pruned_idx, center_idx, cluster_id, nullptr, rep, st);
 }
 
@@ -233,8 +242,6 @@ int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     fill_single(bt, n, p);
     const Ws w = resolve(ws, L);
     hipStream_t st = (hipStream_t)stream;
-    if ((rc = launch_init(bt, w, const_cast<pact_report*>(rep), nullptr, cluster_counts, INIT_MERGE, nullptr, st)))
-        return rc;
     return launch_merge(bt, w, hidden, h_dt, h, cluster_id, center_idx, rep, merged, out_dt, cluster_counts,
                         true, st);
 }

@@ -2,150 +2,162 @@
 // done in parallel rounds (same centres as the sequential loop; cf. the recursive scheme of
 // appendix D), nearest-centre assignment; and the recovery of pruned tokens (Eq. 8/9).
 //
-// Centre selection.  Token i "precedes" j when rho_i > rho_j, or rho_i == rho_j and i < j.
-// Alg. 2 makes i a centre iff no centre that precedes it lies within d_c.  With the bitmap
-// adj[i][j] = (d_ij <= d_c) this is a fixed point every token can evaluate on its own:
+// Centre selection.  Token j "precedes" i when rho_j > rho_i, or rho_j == rho_i and j < i
+// (the stable descending density order of Alg. 2).  Alg. 2 makes i a centre iff no centre
+// that precedes it lies within d_c.  With adj[i][j] = (d_ij <= d_c) this is a fixed point
+// every token can evaluate on its own from its list of preceding neighbours:
 //     a preceding neighbour is a centre            -> i is not a centre
 //     every preceding neighbour is known not to be -> i is a centre
-// A round evaluates this for all undecided tokens at once (one wavefront per token); the
-// densest undecided token is always decided, so the rounds terminate, and the result does
-// not depend on how stale the statuses read within a round are.
+// A round evaluates this for all undecided tokens at once; the densest undecided token is
+// always decided, so the rounds terminate, and the result does not depend on how stale the
+// statuses read within a round are.
 #include "pact_internal.h"
 
 namespace pact {
 
-// ------------------------------------------------------------------------------------------
-// Start-of-call initialisation of everything the later kernels accumulate into.
-// grid (ceil(n_max/256), B), block 256.
-__global__ __launch_bounds__(256) void init_kernel(Batch bt, Ws w, pact_report* rep, int32_t* cluster_id,
-                                                   int32_t* cluster_counts, int mode,
-                                                   const int32_t* n_idx_dev) {
-    const int b = blockIdx.y;
-    const Seg sg = bt.s[b];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        w.near_cnt[b] = 0;
-        for (int r = 0; r < MAX_ROUNDS; ++r) w.round_new[b * MAX_ROUNDS + r] = 0;
-        pact_report* rp = rep + b;
-        if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {
-            if (mode != INIT_REDUCE) {
-                rp->n_kept = (mode == INIT_DBDPC_ALL) ? sg.n : min(max(*n_idx_dev, 0), sg.n);
-                rp->n_pruned = (mode == INIT_DBDPC_ALL) ? 0 : sg.n - rp->n_kept;
-            }
-            rp->n_centers = 0; rp->rounds = 0; rp->dc_checked_pairs = 0; rp->dc_near_ties = 0;
-            rp->refine_overflow = 0; rp->zero_norm_seen = 0;
-            rp->n_reincorporated = 0; rp->n_dropped = 0;
-            for (int k = 0; k < 6; ++k) rp->reserved[k] = 0;
-        }
-        if (mode == INIT_REINC) { rp->n_reincorporated = 0; rp->n_dropped = 0; rp->zero_norm_seen = 0; }
-    }
-    if (i >= sg.n) return;
-    const size_t g = (size_t)sg.base + i;
-    const size_t l = (size_t)b * bt.n_max + i;
-    if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {
-        w.status[l] = ST_UNKNOWN;
-        w.ident[g] = i;
-        cluster_id[g] = -1;
-        if (cluster_counts) cluster_counts[g] = 0;
-    }
-    if (mode == INIT_MERGE && cluster_counts) cluster_counts[g] = 0;
+constexpr int KP = PRED_CAP;   // preceding neighbours kept per token; more -> bitmap fallback
+
+__device__ __forceinline__ bool precedes(double rho_j, int j, double rho_i, int i) {
+    return rho_j > rho_i || (rho_j == rho_i && j < i);
 }
 
-// ------------------------------------------------------------------------------------------
-// Squared norm (fp64), reciprocal norm (fp32) of every token's clustering key, and a cleared
-// bitmap row per token.  One wavefront per token; grid (ceil(n_max/4), B), block 256.
+// fp64 dot product of two rows by a group of 8 lanes (sub = lane & 7); every lane of the
+// group returns the bit-identical total.
 template <int DT>
-__global__ __launch_bounds__(256) void key_prep_kernel(Batch bt, const char* __restrict__ keys, int dk,
-                                                        double* __restrict__ nn, float* __restrict__ rinv,
-                                                        uint64_t* __restrict__ adj, pact_report* rep) {
-    const int b = blockIdx.y;
-    const Seg sg = bt.s[b];
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (i >= sg.n) return;
-    const size_t g = (size_t)sg.base + i;
-    const char* row = keys + g * (size_t)dk * Elem<DT>::BYTES;
-    const double v = wave_dot64<DT>(row, row, dk, lane);
-    if (lane == 0) {
-        nn[g] = v;
-        rinv[g] = v > 0.0 ? (float)(1.0 / sqrt(v)) : 0.0f;
-        if (!(v > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
-    }
-    uint64_t* arow = adj + ((size_t)b * bt.n_max + i) * bt.W;
-    const int Wn = (sg.n + 63) >> 6;
-    for (int k = lane; k < Wn; k += 64) arow[k] = 0ull;
-}
-
-// ------------------------------------------------------------------------------------------
-// Pairs the Gram epilogue could not decide in fp32: evaluate Eq. 5 in fp64 and clear the bit
-// if the distance exceeds d_c.  One wavefront per pair, grid (64, B), block 256.
-template <int DT>
-__global__ __launch_bounds__(256) void refine_kernel(Batch bt, const char* __restrict__ keys, int dk,
-                                                      const int32_t* __restrict__ idx,
-                                                      const double* __restrict__ nn,
-                                                      const uint32_t* __restrict__ near_list,
-                                                      const int32_t* __restrict__ near_cnt,
-                                                      uint64_t* __restrict__ adj, pact_report* rep) {
-    const int b = blockIdx.y;
-    const Seg sg = bt.s[b];
-    const int lane = threadIdx.x & 63;
-    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int nw = gridDim.x * 4;
-    const int raw = near_cnt[b];
-    const int cnt = min(raw, NEAR_CAP);
-    if (gw == 0 && lane == 0) {
-        rep[b].dc_checked_pairs = cnt;
-        rep[b].refine_overflow = raw > NEAR_CAP;
-    }
-    const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
-    const char* kb = keys + (size_t)sg.base * row_bytes;
-    const int32_t* ix = idx + sg.base;
-    const double* nnb = nn + sg.base;
-    const double d_c = (double)sg.d_c;
-    int ties = 0;
-    for (int e = gw; e < cnt; e += nw) {
-        const uint32_t pi = near_list[((size_t)b * NEAR_CAP + e) * 2];
-        const uint32_t pj = near_list[((size_t)b * NEAR_CAP + e) * 2 + 1];
-        const int ti = ix[pi], tj = ix[pj];
-        double d = 0.0;
-        if (pi != pj) {
-            const double dot = wave_dot64<DT>(kb + (size_t)ti * row_bytes, kb + (size_t)tj * row_bytes, dk, lane);
-            d = cos_dist64(dot, nnb[ti], nnb[tj]);
-        }
-        if (lane == 0) {
-            if (d > d_c)
-                atomicAnd((unsigned long long*)&adj[((size_t)b * bt.n_max + pi) * bt.W + (pj >> 6)],
-                          ~(1ull << (pj & 63)));
-            if (fabs(d - d_c) <= 1e-6) ++ties;
-        }
-    }
-    if (lane == 0 && ties) atomicAdd(&rep[b].dc_near_ties, ties);
-}
-
-// ------------------------------------------------------------------------------------------
-// Eq. 6 completed: rho_p = sum over the 64-row blocks of the column partials.  With d_n = 2
-// every term is an fp32 value in [e^-1, 1], so these fp64 additions are exact and the result
-// does not depend on the order.  grid (ceil(n_max/256), B), block 256.
-__global__ __launch_bounds__(256) void rho_finalize_kernel(Batch bt, const pact_report* __restrict__ rep,
-                                                           const double* __restrict__ rho_part,
-                                                           double* __restrict__ rho, double* rho_opt) {
-    const int b = blockIdx.y;
-    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
-    const int p = blockIdx.x * 256 + threadIdx.x;
-    if (p >= q) return;
-    const int nrt = (q + 63) >> 6;
-    const double* in = rho_part + (size_t)b * bt.W * bt.n_max + p;
+__device__ __forceinline__ double group8_dot64(const char* ra, const char* rb, int dk, int sub) {
+    constexpr int EPL = Elem<DT>::EPL;
     double acc = 0.0;
-    for (int r = 0; r < nrt; ++r) acc += in[(size_t)r * bt.n_max];
-    rho[(size_t)b * bt.n_max + p] = acc;
-    if (rho_opt) rho_opt[bt.s[b].base + p] = acc;
+    for (int e = sub * EPL; e < dk; e += 8 * EPL) {
+        const uint4 va = *(const uint4*)(ra + (size_t)e * Elem<DT>::BYTES);
+        const uint4 vb = *(const uint4*)(rb + (size_t)e * Elem<DT>::BYTES);
+        double a[8], b[8];
+        Elem<DT>::widen(va, a);
+        Elem<DT>::widen(vb, b);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
+    }
+#pragma unroll
+    for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
+    return acc;
 }
 
-// Density order by enumeration: rank_p = #{j : rho_j > rho_p, or rho_j == rho_p and j < p}.
+// Nearest of `ncand` candidates (ids in LDS), evaluated 8 at a time by 8-lane groups.
+// tok_of(c) maps a candidate id to its token; only distances < thr compete; ties go to the
+// lower candidate id.  Updates (best, bestc), identical in every lane.
+template <int DT, typename TokOf>
+__device__ __forceinline__ void nearest_candidate(const int* cand, int ncand, const char* mine, double nnp,
+                                                  const char* kb, size_t row_bytes, const double* nnb,
+                                                  int dk, int lane, double thr, TokOf tok_of,
+                                                  double& best, int& bestc) {
+    const int grp = lane >> 3, sub = lane & 7;
+    for (int c0 = 0; c0 < ncand; c0 += 8) {
+        const int ci = c0 + grp;
+        const bool valid = ci < ncand;
+        const int c = cand[valid ? ci : c0];
+        const int tok = tok_of(c);
+        const double dot = group8_dot64<DT>(mine, kb + (size_t)tok * row_bytes, dk, sub);
+        double d = cos_dist64(dot, nnp, nnb[tok]);
+        int cc = c;
+        if (!valid || !(d < thr)) { d = INFINITY; cc = 0x7FFFFFFF; }
+#pragma unroll
+        for (int s = 8; s <= 32; s <<= 1) {
+            const double od = __shfl_xor(d, s, 64);
+            const int oc = __shfl_xor(cc, s, 64);
+            if (od < d || (od == d && oc < cc)) { d = od; cc = oc; }
+        }
+        if (cc != 0x7FFFFFFF && (d < best || (d == best && cc < bestc))) { best = d; bestc = cc; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// After the density Gram pass, two independent jobs in one launch:
+//   blocks [0, REFINE_BLOCKS): the pairs the epilogue could not decide in fp32 - evaluate
+//       Eq. 5 in fp64 and clear the bit if the distance exceeds d_c (one wavefront per pair);
+//   the other blocks: Eq. 6 completed, rho_p = sum over the 64-row blocks of the column
+//       partials (64 tokens x 4 slices per block).  With d_n = 2 every term is an fp32 value
+//       in [e^-1, 1], so these fp64 additions are exact whatever their order.
+constexpr int REFINE_BLOCKS = 64;
+
+template <int DT>
+__global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __restrict__ keys, int dk,
+                                                         const int32_t* __restrict__ idx,
+                                                         const double* __restrict__ nn,
+                                                         const uint32_t* __restrict__ near_list,
+                                                         const int32_t* __restrict__ near_cnt,
+                                                         uint64_t* adj, pact_report* rep,
+                                                         const double* __restrict__ rho_part,
+                                                         double* __restrict__ rho, double* rho_opt) {
+    __shared__ double s_p[4][64];
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int q = clamp_count(rep[b].n_kept, sg.n);
+    if (blockIdx.x < REFINE_BLOCKS) {
+        const int gw = blockIdx.x * 4 + wave;
+        const int nw = REFINE_BLOCKS * 4;
+        const int raw = near_cnt[b];
+        const int cnt = min(raw, NEAR_CAP);
+        if (gw == 0 && lane == 0) {
+            rep[b].dc_checked_pairs = cnt;
+            rep[b].refine_overflow = raw > NEAR_CAP;
+        }
+        const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
+        const char* kb = keys + (size_t)sg.base * row_bytes;
+        const int32_t* ix = idx + sg.base;
+        const double* nnb = nn + sg.base;
+        const double d_c = (double)sg.d_c;
+        int ties = 0;
+        for (int e = gw; e < cnt; e += nw) {
+            const uint32_t pi = near_list[((size_t)b * NEAR_CAP + e) * 2];
+            const uint32_t pj = near_list[((size_t)b * NEAR_CAP + e) * 2 + 1];
+            const int ti = ix[pi], tj = ix[pj];
+            double d = 0.0;
+            if (pi != pj) {
+                const double dot = wave_dot64<DT>(kb + (size_t)ti * row_bytes, kb + (size_t)tj * row_bytes, dk, lane);
+                d = cos_dist64(dot, nnb[ti], nnb[tj]);
+            }
+            if (lane == 0) {
+                if (d > d_c)
+                    atomicAnd((unsigned long long*)&adj[((size_t)b * bt.n_max + pi) * bt.W + (pj >> 6)],
+                              ~(1ull << (pj & 63)));
+                if (fabs(d - d_c) <= 1e-6) ++ties;
+            }
+        }
+        if (lane == 0 && ties) atomicAdd(&rep[b].dc_near_ties, ties);
+        return;
+    }
+    const int p0 = (blockIdx.x - REFINE_BLOCKS) * 64;
+    if (p0 >= q) return;
+    const int p = p0 + lane;
+    const int nrt = (q + 63) >> 6;
+    double acc = 0.0;
+    if (p < q) {
+        const double* in = rho_part + (size_t)b * bt.W * bt.n_max + p;
+        for (int r0 = wave; r0 < nrt; r0 += 32) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + 4 * u;
+                v[u] = (r < nrt) ? in[(size_t)r * bt.n_max] : 0.0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+    }
+    s_p[wave][lane] = acc;
+    __syncthreads();
+    if (wave == 0 && p < q) {
+        const double t = (s_p[0][lane] + s_p[1][lane]) + (s_p[2][lane] + s_p[3][lane]);
+        rho[(size_t)b * bt.n_max + p] = t;
+        if (rho_opt) rho_opt[sg.base + p] = t;
+    }
+}
+
+// Optional output: position of every kept token in the density order, by enumeration.
 // grid (ceil(n_max/64), B), block 1024 = 64 tokens x 16 slices of the j range.
 __global__ __launch_bounds__(1024) void rank_kernel(Batch bt, const pact_report* __restrict__ rep,
-                                                    const double* __restrict__ rho,
-                                                    int32_t* __restrict__ rank, int32_t* rank_opt) {
+                                                    const double* __restrict__ rho, int32_t* rank_opt) {
     __shared__ int s_cnt[16][64];
     const int b = blockIdx.y;
     const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
@@ -158,97 +170,139 @@ __global__ __launch_bounds__(1024) void rank_kernel(Batch bt, const pact_report*
     const int per = (q + 15) / 16;
     const int j0 = slice * per, j1 = min(q, j0 + per);
     int cnt = 0;
-    for (int j = j0; j < j1; ++j) {
-        const double v = r[j];
-        cnt += (v > mine) || (v == mine && j < p);
-    }
+    for (int j = j0; j < j1; ++j) cnt += precedes(r[j], j, mine, p);
     s_cnt[slice][lane] = cnt;
     __syncthreads();
     if (threadIdx.x < 64 && p < q) {
         int tot = 0;
 #pragma unroll
         for (int s = 0; s < 16; ++s) tot += s_cnt[s][lane];
-        rank[(size_t)b * bt.n_max + p] = tot;
-        if (rank_opt) rank_opt[bt.s[b].base + p] = tot;
+        rank_opt[bt.s[b].base + p] = tot;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// One parallel round of centre selection.  One wavefront per kept token;
-// grid (ceil(n_max/4), B), block 256.
-__global__ __launch_bounds__(256) void centre_round_kernel(Batch bt, const pact_report* __restrict__ rep,
-                                                           const uint64_t* __restrict__ adj,
-                                                           const int32_t* __restrict__ rank,
-                                                           uint32_t* status, int32_t* round_new, int round) {
+// Lock-step extraction of the set bits of one 64-bit word per lane: each call of `step`
+// pops at most one bit per lane and reports, wave-wide, how many lanes popped one.
+struct BitPop {
+    uint64_t word;
+    __device__ __forceinline__ bool any() const { return __any(word != 0ull); }
+    // returns true if this lane popped bit `bit`
+    __device__ __forceinline__ bool pop(int& bit) {
+        const bool has = word != 0ull;
+        bit = has ? __builtin_ctzll(word) : 0;
+        if (has) word &= word - 1;
+        return has;
+    }
+};
+__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
+    return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// For every kept token: the list of its neighbours (bitmap row) that precede it in the
+// density order, as 16-bit positions; pcnt = list length, or KP+1 if it did not fit.
+// One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+__global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
+                                                          const uint64_t* __restrict__ adj,
+                                                          const double* __restrict__ rho,
+                                                          uint16_t* __restrict__ preds,
+                                                          int32_t* __restrict__ pcnt) {
     const int b = blockIdx.y;
     const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
     const int lane = threadIdx.x & 63;
     const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (p >= q) return;
-    const int T = bt.s[b].fallback_T;
-    if (round > 0 && round_new[b * MAX_ROUNDS + round - 1] < T) return;   // leave the rest to the finisher
-    uint32_t* st = status + (size_t)b * bt.n_max;
-    if (st[p] != ST_UNKNOWN) return;
-    const int32_t* rk = rank + (size_t)b * bt.n_max;
-    const int myrank = rk[p];
+    const double* r = rho + (size_t)b * bt.n_max;
+    const double rp = r[p];
     const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
+    uint16_t* out = preds + ((size_t)b * bt.n_max + p) * KP;
     const int Wq = (q + 63) >> 6;
-    bool blocked = false, pending = false;
+    int total = 0;
     for (int w0 = 0; w0 < Wq; w0 += 64) {
         const int w = w0 + lane;
-        uint64_t word = (w < Wq) ? row[w] : 0ull;
-        while (word) {
-            const int bit = __builtin_ctzll(word);
-            word &= word - 1;
+        BitPop bp{(w < Wq) ? row[w] : 0ull};
+        while (bp.any()) {
+            int bit;
+            const bool has = bp.pop(bit);
             const int j = (w << 6) + bit;
-            if (j < q && rk[j] < myrank) {
-                const uint32_t sj = st[j];
-                blocked |= (sj == ST_CENTER);
-                pending |= (sj == ST_UNKNOWN);
-            }
+            const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
+            const uint64_t m = __ballot(pre);
+            const int slot = total + lanes_below(m, lane);
+            if (pre && slot < KP) out[slot] = (uint16_t)j;
+            total += __popcll(m);
         }
     }
-    blocked = __any(blocked);
-    pending = __any(pending);
-    if (lane == 0) {
-        if (blocked) st[p] = ST_NOT;
-        else if (!pending) { st[p] = ST_CENTER; atomicAdd(&round_new[b * MAX_ROUNDS + round], 1); }
-    }
+    if (lane == 0) pcnt[(size_t)b * bt.n_max + p] = total > KP ? KP + 1 : total;
 }
 
-// Finishing kernel: one workgroup per sample repeats the round on the statuses held in LDS
-// until nothing is undecided (at least the densest undecided token is decided per round, so
-// at most q rounds), then numbers the centres in ascending token order and publishes them.
-// grid (B), block 1024.
-__global__ __launch_bounds__(1024) void centre_finish_kernel(Batch bt, pact_report* rep,
-                                                             const uint64_t* __restrict__ adj,
-                                                             const int32_t* __restrict__ rank,
-                                                             const int32_t* __restrict__ idx,
-                                                             uint32_t* status, const int32_t* round_new,
-                                                             int32_t* cnum, uint64_t* cmask,
-                                                             int32_t* center_idx) {
-    extern __shared__ unsigned char s_st[];        // q bytes
-    __shared__ int s_unknown;
+// All rounds of the centre selection in one workgroup per sample, statuses in LDS; then the
+// centres are numbered in ascending token order and published.  Tokens whose list overflowed
+// are evaluated from their bitmap row by a whole wavefront.  grid (B), block 1024,
+// dynamic LDS: n_max bytes (status) + n_max * 2 bytes (overflow token list).
+__global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_report* rep,
+                                                              const uint64_t* __restrict__ adj,
+                                                              const double* __restrict__ rho,
+                                                              const uint16_t* __restrict__ preds,
+                                                              const int32_t* __restrict__ pcnt,
+                                                              const int32_t* __restrict__ idx,
+                                                              uint32_t* status, int32_t* cnum,
+                                                              uint64_t* cmask, int32_t* center_idx) {
+    extern __shared__ unsigned char s_raw[];
+    __shared__ int s_unknown, s_nover;
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
-    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
+    const int q = clamp_count(rep[b].n_kept, sg.n);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    uint32_t* st = status + (size_t)b * bt.n_max;
-    const int32_t* rk = rank + (size_t)b * bt.n_max;
+    const int qpad = (bt.n_max + 63) / 64 * 64;
+    volatile unsigned char* s_st = s_raw;                       // [qpad]
+    uint16_t* s_over = (uint16_t*)(s_raw + qpad);                // [n_max]
+    const double* r = rho + (size_t)b * bt.n_max;
+    const int32_t* pc = pcnt + (size_t)b * bt.n_max;
     const int Wq = (q + 63) >> 6;
-    for (int p = tid; p < q; p += 1024) s_st[p] = (unsigned char)st[p];
+
+    if (tid == 0) s_nover = 0;
+    __syncthreads();
+    for (int p = tid; p < q; p += 1024) {
+        s_st[p] = ST_UNKNOWN;
+        if (pc[p] > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    }
+    __syncthreads();
+    const int nover = s_nover;
     int rounds = 0;
-    for (int r = 0; r < MAX_ROUNDS; ++r) rounds += (round_new[b * MAX_ROUNDS + r] > 0);
     while (true) {
         if (tid == 0) s_unknown = 0;
         __syncthreads();
-        bool any_unknown = false;
-        for (int p = wave; p < q; p += 16) {
+        bool still = false;
+        for (int p = tid; p < q; p += 1024) {
             if (s_st[p] != ST_UNKNOWN) continue;
-            const int myrank = rk[p];
+            const int c = pc[p];
+            if (c > KP) continue;
+            const uint4* pl = (const uint4*)(preds + ((size_t)b * bt.n_max + p) * KP);
+            bool blocked = false, pending = false;
+            for (int k = 0; k < c; k += 8) {
+                const uint4 v = pl[k >> 3];
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    if (k + t < c) {
+                        const int j = (wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF;
+                        const unsigned char sj = s_st[j];
+                        blocked |= (sj == ST_CENTER);
+                        pending |= (sj == ST_UNKNOWN);
+                    }
+                }
+            }
+            if (blocked) s_st[p] = ST_NOT;
+            else if (!pending) s_st[p] = ST_CENTER;
+            else still = true;
+        }
+        for (int o = wave; o < nover; o += 16) {                 // wave-uniform trip count
+            const int p = s_over[o];
+            if (s_st[p] != ST_UNKNOWN) continue;
+            const double rp = r[p];
             const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
             bool blocked = false, pending = false;
             for (int w0 = 0; w0 < Wq; w0 += 64) {
@@ -258,8 +312,8 @@ __global__ __launch_bounds__(1024) void centre_finish_kernel(Batch bt, pact_repo
                     const int bit = __builtin_ctzll(word);
                     word &= word - 1;
                     const int j = (w << 6) + bit;
-                    if (j < q && rk[j] < myrank) {
-                        const unsigned char sj = ((volatile unsigned char*)s_st)[j];
+                    if (j < q && precedes(r[j], j, rp, p)) {
+                        const unsigned char sj = s_st[j];
                         blocked |= (sj == ST_CENTER);
                         pending |= (sj == ST_UNKNOWN);
                     }
@@ -269,14 +323,14 @@ __global__ __launch_bounds__(1024) void centre_finish_kernel(Batch bt, pact_repo
             pending = __any(pending);
             if (blocked) { if (lane == 0) s_st[p] = ST_NOT; }
             else if (!pending) { if (lane == 0) s_st[p] = ST_CENTER; }
-            else any_unknown = true;
+            else still = true;
         }
-        if (any_unknown && lane == 0) s_unknown = 1;
+        if (still) s_unknown = 1;
+        ++rounds;
         __syncthreads();
         const int more = s_unknown;
         __syncthreads();
         if (!more) break;
-        ++rounds;
     }
     // number the centres in ascending p (= ascending token index)
     const int chunk = (q + 1023) / 1024;
@@ -297,6 +351,7 @@ __global__ __launch_bounds__(1024) void centre_finish_kernel(Batch bt, pact_repo
         total += s_wtot[w];
     }
     int c = woff + inc - cnt;
+    uint32_t* st = status + (size_t)b * bt.n_max;
     int32_t* cn = cnum + (size_t)b * bt.n_max;
     const int32_t* ix = idx + sg.base;
     int32_t* co = center_idx + sg.base;
@@ -320,36 +375,15 @@ __global__ __launch_bounds__(1024) void centre_finish_kernel(Batch bt, pact_repo
 }
 
 // ------------------------------------------------------------------------------------------
-// Iterate, in ascending order, over the set bits of (row[w] & mask[w]) for w < nWords, calling
-// f(bitIndex) with a wave-uniform index.  All 64 lanes must call it together.
-template <typename F>
-__device__ __forceinline__ void for_each_bit_uniform(const uint64_t* row, const uint64_t* mask, int nWords,
-                                                     int lane, F f) {
-    for (int w0 = 0; w0 < nWords; w0 += 64) {
-        const int w = w0 + lane;
-        uint64_t word = 0ull;
-        if (w < nWords) word = mask ? (row[w] & mask[w]) : row[w];
-        uint64_t have = __ballot(word != 0ull);
-        while (have) {
-            const int src = __builtin_ctzll(have);
-            const uint32_t lo = __shfl((uint32_t)word, src, 64);
-            const uint32_t hi = __shfl((uint32_t)(word >> 32), src, 64);
-            uint64_t wv = ((uint64_t)hi << 32) | lo;
-            while (wv) {
-                const int bit = __builtin_ctzll(wv);
-                wv &= wv - 1;
-                f(((w0 + src) << 6) + bit);
-            }
-            have &= have - 1;
-        }
-    }
-}
+constexpr int CAND_BUF = 128;
 
-// Alg. 2 last loop: every kept token joins the nearest centre, distances in fp64 over the
-// centres its bitmap row allows (the nearest centre is within d_c, hence among them).
+// Alg. 2 last loop: every kept token joins the nearest centre.  Candidates are the centres
+// its bitmap row reaches (the nearest centre is within d_c, hence one of them; it need not
+// precede the token); with one candidate no distance is needed, otherwise Eq. 5 is
+// evaluated in fp64.
 // One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
 template <int DT>
-__global__ __launch_bounds__(256) void assign_kernel(Batch bt, const pact_report* __restrict__ rep,
+__global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
                                                       const char* __restrict__ keys, int dk,
                                                       const int32_t* __restrict__ idx,
                                                       const double* __restrict__ nn,
@@ -358,39 +392,63 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, const pact_report
                                                       const uint32_t* __restrict__ status,
                                                       const int32_t* __restrict__ cnum,
                                                       int32_t* cluster_id, int32_t* cluster_counts) {
+    __shared__ int s_cand[4][CAND_BUF];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
+    const int q = clamp_count(rep[b].n_kept, sg.n);
     const int lane = threadIdx.x & 63;
-    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int wave = threadIdx.x >> 6;
+    const int p = blockIdx.x * 4 + wave;
     if (p >= q) return;
     const int32_t* ix = idx + sg.base;
     const int32_t* cn = cnum + (size_t)b * bt.n_max;
+    const uint32_t* st = status + (size_t)b * bt.n_max;
+    const double* nnb = nn + sg.base;
     const int tok = ix[p];
     int cid;
-    if (status[(size_t)b * bt.n_max + p] == ST_CENTER) {
+    if (st[p] == ST_CENTER) {
         cid = cn[p];
     } else {
         const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
         const char* kb = keys + (size_t)sg.base * row_bytes;
-        const double* nnb = nn + sg.base;
         const char* mine = kb + (size_t)tok * row_bytes;
         const double nnp = nnb[tok];
+        int* cand = s_cand[wave];
         double best = INFINITY;
-        int bestj = -1;
-        for_each_bit_uniform(adj + ((size_t)b * bt.n_max + p) * bt.W, cmask + (size_t)b * bt.W,
-                             (q + 63) >> 6, lane, [&](int j) {
-            if (j >= q) return;
-            const int tj = ix[j];
-            const double dot = wave_dot64<DT>(mine, kb + (size_t)tj * row_bytes, dk, lane);
-            const double d = cos_dist64(dot, nnp, nnb[tj]);
-            if (d < best) { best = d; bestj = j; }
-        });
-        cid = bestj >= 0 ? cn[bestj] : -1;
+        int bestj = 0x7FFFFFFF;
+        auto tok_of = [&](int j) { return ix[j]; };
+        const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
+        const uint64_t* cm = cmask + (size_t)b * bt.W;
+        const int Wq = (q + 63) >> 6;
+        int nbuf = 0, ntot = 0;
+        for (int w0 = 0; w0 < Wq; w0 += 64) {
+            const int w = w0 + lane;
+            BitPop bp{(w < Wq) ? (row[w] & cm[w]) : 0ull};
+            while (bp.any()) {
+                int bit;
+                const bool has = bp.pop(bit);
+                const int j = (w << 6) + bit;
+                const bool ok = has && j < q;
+                const uint64_t m = __ballot(ok);
+                if (ok) cand[nbuf + lanes_below(m, lane)] = j;
+                nbuf += __popcll(m);
+                ntot += __popcll(m);
+                if (nbuf > CAND_BUF - 64) {
+                    nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
+                                          tok_of, best, bestj);
+                    nbuf = 0;
+                }
+            }
+        }
+        if (ntot == 1) bestj = cand[0];                 // a single centre in reach: no distance needed
+        else if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
+                                             tok_of, best, bestj);
+        cid = bestj != 0x7FFFFFFF ? cn[bestj] : -1;
     }
     if (lane == 0) {
         cluster_id[sg.base + tok] = cid;
         if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
+        if (!(nnb[tok] > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
     }
 }
 
@@ -405,12 +463,14 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
                                                             const double* __restrict__ nn,
                                                             const uint64_t* __restrict__ adj,
                                                             int32_t* cluster_id, int32_t* cluster_counts) {
+    __shared__ int s_cand[4][CAND_BUF];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
               C = clamp_count(rep[b].n_centers, q);
     const int lane = threadIdx.x & 63;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 4 + wave;
     if (t >= np) return;
     const int tok = pruned_idx[sg.base + t];
     const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
@@ -421,76 +481,81 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     const double nnp = nnb[tok];
     const double thr = (double)sg.alpha * (double)sg.d_c;
     double best = INFINITY;
-    int bestc = -1;
+    int bestc = 0x7FFFFFFF;
     if (thr > 0.0 && C > 0) {
-        for_each_bit_uniform(adj + ((size_t)b * bt.n_max + q + t) * bt.W, nullptr, (C + 63) >> 6, lane,
-                             [&](int c) {
-            if (c >= C) return;
-            const int tc = co[c];
-            const double dot = wave_dot64<DT>(mine, kb + (size_t)tc * row_bytes, dk, lane);
-            const double d = cos_dist64(dot, nnp, nnb[tc]);
-            if (d < thr && d < best) { best = d; bestc = c; }
-        });
+        int* cand = s_cand[wave];
+        auto tok_of = [&](int c) { return co[c]; };
+        const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
+        const int Wc = (C + 63) >> 6;
+        int nbuf = 0;
+        for (int w0 = 0; w0 < Wc; w0 += 64) {
+            const int w = w0 + lane;
+            BitPop bp{(w < Wc) ? row[w] : 0ull};
+            while (bp.any()) {
+                int bit;
+                const bool has = bp.pop(bit);
+                const int c = (w << 6) + bit;
+                const bool ok = has && c < C;
+                const uint64_t m = __ballot(ok);
+                if (ok) cand[nbuf + lanes_below(m, lane)] = c;
+                nbuf += __popcll(m);
+                if (nbuf > CAND_BUF - 64) {
+                    nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
+                                          best, bestc);
+                    nbuf = 0;
+                }
+            }
+        }
+        if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
+                                        best, bestc);
     }
     if (lane == 0) {
-        cluster_id[sg.base + tok] = bestc;
-        if (bestc >= 0) {
-            if (cluster_counts) atomicAdd(&cluster_counts[sg.base + bestc], 1);
+        const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
+        cluster_id[sg.base + tok] = cid;
+        if (cid >= 0) {
+            if (cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
             atomicAdd(&rep[b].n_reincorporated, 1);
         } else {
             atomicAdd(&rep[b].n_dropped, 1);
         }
+        if (!(nnp > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
     }
 }
 
 // ------------------------------------------------------------------------------------------
-int launch_init(const Batch& bt, const Ws& w, pact_report* rep, int32_t* cluster_id,
-                int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st) {
-    PACT_LAUNCH("init", init_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt, w, rep,
-                cluster_id, cluster_counts, mode, n_idx_dev);
-    return PACT_OK;
-}
-
-int launch_key_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
-                    pact_report* rep, hipStream_t st) {
-    dim3 grid((bt.n_max + 3) / 4, bt.B);
-    if (k_dt == PACT_BF16)
-        PACT_LAUNCH("key_prep", key_prep_kernel<PACT_BF16>, grid, dim3(256), st, bt, (const char*)keys, dk,
-                    w.nn, w.rinv, w.adj, rep);
-    else
-        PACT_LAUNCH("key_prep", key_prep_kernel<PACT_F32>, grid, dim3(256), st, bt, (const char*)keys, dk,
-                    w.nn, w.rinv, w.adj, rep);
-    return PACT_OK;
-}
-
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
                    hipStream_t st) {
     const char* k = (const char*)keys;
+    dim3 gpost(REFINE_BLOCKS + (bt.n_max + 63) / 64, bt.B);
     if (k_dt == PACT_BF16)
-        PACT_LAUNCH("refine_pairs", refine_kernel<PACT_BF16>, dim3(64, bt.B), dim3(256), st, bt, k, dk, idx,
-                    w.nn, w.near_list, w.near_cnt, w.adj, rep);
+        PACT_LAUNCH("post_gram", post_gram_kernel<PACT_BF16>, gpost, dim3(256), st, bt, k, dk, idx, w.nn,
+                    w.near_list, w.near_cnt, w.adj, rep, w.rho_part, w.rho, rho_opt);
     else
-        PACT_LAUNCH("refine_pairs", refine_kernel<PACT_F32>, dim3(64, bt.B), dim3(256), st, bt, k, dk, idx,
-                    w.nn, w.near_list, w.near_cnt, w.adj, rep);
-    PACT_LAUNCH("rho_finalize", rho_finalize_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt,
-                rep, w.rho_part, w.rho, rho_opt);
-    PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
-                w.rho, w.rank, rank_opt);
-    const int n_par = 4;
-    for (int r = 0; r < n_par; ++r)
-        PACT_LAUNCH("centre_round", centre_round_kernel, dim3((bt.n_max + 3) / 4, bt.B), dim3(256), st, bt,
-                    rep, w.adj, w.rank, w.status, w.round_new, r);
-    PACT_LAUNCH_SHMEM("centre_finish", centre_finish_kernel, dim3(bt.B), dim3(1024),
-                      (size_t)((bt.n_max + 255) / 256 * 256), st, bt, rep, w.adj, w.rank, idx, w.status,
-                      w.round_new, w.cnum, w.cmask, center_idx);
-    dim3 grid((bt.n_max + 3) / 4, bt.B);
+        PACT_LAUNCH("post_gram", post_gram_kernel<PACT_F32>, gpost, dim3(256), st, bt, k, dk, idx, w.nn,
+                    w.near_list, w.near_cnt, w.adj, rep, w.rho_part, w.rho, rho_opt);
+    if (rank_opt)
+        PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
+                    w.rho, rank_opt);
+    dim3 gtok((bt.n_max + 3) / 4, bt.B);
+    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
+                w.pcnt);
+    const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) + (size_t)bt.n_max * 2;
+    static size_t raised = 0;
+    if (lds > 48 * 1024 && lds > raised) {
+        if (hipFuncSetAttribute((const void*)centre_resolve_kernel,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return PACT_ERR_HIP;
+        raised = lds;
+    }
+    PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
+                      w.adj, w.rho, w.preds, w.pcnt, idx, w.status, w.cnum, w.cmask, center_idx);
     if (k_dt == PACT_BF16)
-        PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, grid, dim3(256), st, bt, rep, k, dk, idx, w.nn,
+        PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
                     w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);
     else
-        PACT_LAUNCH("assign", assign_kernel<PACT_F32>, grid, dim3(256), st, bt, rep, k, dk, idx, w.nn,
+        PACT_LAUNCH("assign", assign_kernel<PACT_F32>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
                     w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);
     return PACT_OK;
 }

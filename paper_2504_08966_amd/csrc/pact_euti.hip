@@ -1,4 +1,5 @@
-// EUTI (Alg. 1): global query (Eq. 1), importance score (Eq. 2), percentile split (Eq. 3/4).
+// EUTI (Alg. 1): global query (Eq. 1), importance score (Eq. 2), percentile split (Eq. 3/4),
+// plus the per-token preparation of the clustering keys (norms, cleared bitmap rows).
 // All arithmetic of the score is fp64 (the stage is bound by reading H from HBM, the ALU work
 // is free), rounded once to fp32; the split then compares fp32 bit patterns exactly.
 #include "pact_internal.h"
@@ -6,51 +7,129 @@
 namespace pact {
 
 // ------------------------------------------------------------------------------------------
-// Eq. 1, pass 1: column sums of the queries of one row chunk.  grid (QG_CHUNKS, B), block 256.
-// Each thread owns groups of 4 consecutive columns; partial sums go to qg_part[b][chunk][col].
-template <int DT>
-__global__ __launch_bounds__(256) void qglobal_partial_kernel(Batch bt, const char* __restrict__ q,
-                                                               int qcols, double* __restrict__ qg_part) {
+// First kernel of a call.  Three independent jobs share one launch:
+//   blocks [0, nKeyBlocks)            : one wavefront per token: squared key norm (fp64),
+//                                       reciprocal norm (fp32), cleared bitmap row, and the
+//                                       per-token initial state (status, cluster id, counts);
+//   blocks [nKeyBlocks, +QG_CHUNKS)   : Eq. 1 pass 1, column sums of one row chunk of Q.
+// grid (nKeyBlocks + (do_q ? QG_CHUNKS : 0), B), block 256.
+struct PrepArgs {
+    const char* keys; int32_t dk; int32_t key_dt_unused;
+    const char* q; int32_t qcols;            // q == nullptr: no query pass
+    double* nn; float* rinv; uint64_t* adj; double* qg_part;
+    uint32_t* status; int32_t* ident; int32_t* near_cnt; int32_t* round_new;
+    pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
+    const int32_t* n_idx_dev;
+    int32_t mode; int32_t n_key_blocks;
+};
+
+template <int KDT, int QDT>
+__global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    const int chunk = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    if ((int)blockIdx.x < a.n_key_blocks) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            a.near_cnt[b] = 0;
+            for (int r = 0; r < MAX_ROUNDS; ++r) a.round_new[b * MAX_ROUNDS + r] = 0;
+            pact_report* rp = a.rep + b;
+            const int mode = a.mode;
+            if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {
+                if (mode != INIT_REDUCE) {
+                    const int k = (mode == INIT_DBDPC_ALL) ? sg.n : min(max(*a.n_idx_dev, 0), sg.n);
+                    rp->n_kept = k;
+                    rp->n_pruned = (mode == INIT_DBDPC_ALL) ? 0 : sg.n - k;
+                }
+                rp->n_centers = 0; rp->rounds = 0; rp->dc_checked_pairs = 0; rp->dc_near_ties = 0;
+                rp->refine_overflow = 0; rp->n_reincorporated = 0; rp->n_dropped = 0;
+                rp->zero_norm_seen = 0;     // counted by the assignment kernels, which run later
+                for (int k = 0; k < 6; ++k) rp->reserved[k] = 0;
+            }
+            if (mode == INIT_REINC) { rp->n_reincorporated = 0; rp->n_dropped = 0; }
+        }
+        const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+        if (i >= sg.n) return;
+        const size_t g = (size_t)sg.base + i;
+        const char* row = a.keys + g * (size_t)a.dk * Elem<KDT>::BYTES;
+        const double v = wave_dot64<KDT>(row, row, a.dk, lane);
+        uint64_t* arow = a.adj + ((size_t)b * bt.n_max + i) * bt.W;
+        const int Wn = (sg.n + 63) >> 6;
+        for (int k = lane; k < Wn; k += 64) arow[k] = 0ull;
+        if (lane == 0) {
+            a.nn[g] = v;
+            a.rinv[g] = v > 0.0 ? (float)(1.0 / sqrt(v)) : 0.0f;
+            if (a.mode == INIT_REDUCE || a.mode == INIT_DBDPC_ALL || a.mode == INIT_DBDPC_SUBSET) {
+                a.status[(size_t)b * bt.n_max + i] = ST_UNKNOWN;
+                a.ident[g] = i;
+                a.cluster_id[g] = -1;
+                if (a.cluster_counts) a.cluster_counts[g] = 0;
+            }
+        }
+        return;
+    }
+    // ---- Eq. 1, pass 1
+    const int chunk = blockIdx.x - a.n_key_blocks;
     const int rows_per = (sg.n + QG_CHUNKS - 1) / QG_CHUNKS;
     const int r0 = chunk * rows_per;
     const int r1 = min(sg.n, r0 + rows_per);
-    const size_t row_bytes = (size_t)qcols * Elem<DT>::BYTES;
-    double* out = qg_part + ((size_t)b * QG_CHUNKS + chunk) * qcols;
-    for (int c = threadIdx.x * 4; c < qcols; c += 256 * 4) {
+    const size_t row_bytes = (size_t)a.qcols * Elem<QDT>::BYTES;
+    double* out = a.qg_part + ((size_t)b * QG_CHUNKS + chunk) * a.qcols;
+    for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int r = r0; r < r1; ++r) {
-            const char* p = q + (size_t)(sg.base + r) * row_bytes + (size_t)c * Elem<DT>::BYTES;
-            float f[4];
-            if (DT == PACT_BF16) {
-                const uint2 v = *(const uint2*)p;
-                f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-                f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-            } else {
-                const float4 v = *(const float4*)p;
-                f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+        const char* base = a.q + (size_t)sg.base * row_bytes + (size_t)c * Elem<QDT>::BYTES;
+        for (int r = r0; r < r1; r += 8) {
+            float f[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool ok = r + u < r1;
+                const char* p = base + (size_t)(ok ? r + u : r0) * row_bytes;
+                if (QDT == PACT_BF16) {
+                    const uint2 v = *(const uint2*)p;
+                    f[u][0] = __uint_as_float(v.x << 16); f[u][1] = __uint_as_float(v.x & 0xFFFF0000u);
+                    f[u][2] = __uint_as_float(v.y << 16); f[u][3] = __uint_as_float(v.y & 0xFFFF0000u);
+                } else {
+                    const float4 v = *(const float4*)p;
+                    f[u][0] = v.x; f[u][1] = v.y; f[u][2] = v.z; f[u][3] = v.w;
+                }
+                if (!ok) { f[u][0] = f[u][1] = f[u][2] = f[u][3] = 0.0f; }
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] += (double)f[i];
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] += (double)f[u][i];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) out[c + i] = acc[i];
     }
 }
 
-// Eq. 1, pass 2: sum the chunk partials in chunk order and divide by n.  grid (ceil(qcols/256), B).
-__global__ __launch_bounds__(256) void qglobal_final_kernel(Batch bt, int qcols,
-                                                            const double* __restrict__ qg_part,
-                                                            double* __restrict__ qg) {
+// Eq. 1, pass 2: sum the chunk partials in a fixed order and divide by n.
+// grid (ceil(qcols/64), B), block 1024 = 64 columns x 16 slices of the chunk range.
+__global__ __launch_bounds__(1024) void qglobal_final_kernel(Batch bt, int qcols,
+                                                             const double* __restrict__ qg_part,
+                                                             double* __restrict__ qg) {
+    __shared__ double s_p[16][64];
     const int b = blockIdx.y;
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= qcols) return;
-    const double* in = qg_part + (size_t)b * QG_CHUNKS * qcols + c;
+    const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl;
+    constexpr int PER = QG_CHUNKS / 16;
     double acc = 0.0;
-    for (int k = 0; k < QG_CHUNKS; ++k) acc += in[(size_t)k * qcols];
-    qg[(size_t)b * qcols + c] = acc / (double)bt.s[b].n;
+    if (c < qcols) {
+        const double* in = qg_part + ((size_t)b * QG_CHUNKS + slice * PER) * qcols + c;
+        double v[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) v[k] = in[(size_t)k * qcols];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) acc += v[k];
+    }
+    s_p[slice][cl] = acc;
+    __syncthreads();
+    if (slice == 0 && c < qcols) {
+        double t = 0.0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) t += s_p[k][cl];
+        qg[(size_t)b * qcols + c] = t / (double)bt.s[b].n;
+    }
 }
 
 // Caller supplied the global query ([B, qcols]): widen it to fp64.
@@ -69,10 +148,10 @@ __global__ __launch_bounds__(256) void qglobal_copy_kernel(Batch bt, const char*
 
 // ------------------------------------------------------------------------------------------
 // Eq. 2, pass 1: one wavefront per token computes |h_i|_2 and the n_q logits
-// k_i^(g(j)) . Qg^(j); the workgroup (16 tokens) then leaves one online-softmax partial
-// (max, sum of exp) per head.  grid (ceil(n_max/16), B), block 256.
+// k_i^(g(j)) . Qg^(j); the workgroup (SCORE_TOK_PER_WG tokens) then leaves one online-softmax
+// partial (max, sum of exp) per head.  grid (ceil(n_max/8), B), block 512.
 template <int HDT, int KDT>
-__global__ __launch_bounds__(256) void score_logits_kernel(Batch bt, const char* __restrict__ hidden, int h,
+__global__ __launch_bounds__(512) void score_logits_kernel(Batch bt, const char* __restrict__ hidden, int h,
                                                             const char* __restrict__ keys, int n_kv, int d_h,
                                                             int n_q, const double* __restrict__ qg,
                                                             double* __restrict__ logits,
@@ -90,22 +169,30 @@ __global__ __launch_bounds__(256) void score_logits_kernel(Batch bt, const char*
     const double* qgb = qg + (size_t)b * qcols;
     const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
     const size_t krow = (size_t)n_kv * d_h * Elem<KDT>::BYTES;
+    constexpr int HE = Elem<HDT>::EPL;
 
-    for (int tt = wave; tt < SCORE_TOK_PER_WG; tt += 4) {
-        const int i = t0 + tt;
-        if (i >= sg.n) break;
+    const int i = t0 + wave;
+    if (i < sg.n) {
         const size_t g = (size_t)sg.base + i;
-        // hidden-state norm
+        // hidden-state norm: 4 independent 16-byte loads in flight per lane
         const char* hp = hidden + g * hrow;
-        double ss = 0.0;
-        for (int e = lane * Elem<HDT>::EPL; e < h; e += 64 * Elem<HDT>::EPL) {
-            const uint4 v = *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES);
-            double x[8];
-            Elem<HDT>::widen(v, x);
+        double ss[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int e0 = lane * HE; e0 < h; e0 += 4 * 64 * HE) {
+            uint4 v[4];
 #pragma unroll
-            for (int k = 0; k < Elem<HDT>::EPL; ++k) ss = fma(x[k], x[k], ss);
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * 64 * HE;
+                v[u] = (e < h) ? *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                double x[8];
+                Elem<HDT>::widen(v[u], x);
+#pragma unroll
+                for (int k = 0; k < HE; ++k) ss[u] = fma(x[k], x[k], ss[u]);
+            }
         }
-        ss = wave_sum_f64(ss);
+        const double sst = wave_sum_f64((ss[0] + ss[1]) + (ss[2] + ss[3]));
         // per-head logits
         const char* kp = keys + g * krow;
         for (int j = 0; j < n_q; ++j) {
@@ -122,10 +209,10 @@ __global__ __launch_bounds__(256) void score_logits_kernel(Batch bt, const char*
             acc = wave_sum_f64(acc);
             if (lane == 0) {
                 logits[g * n_q + j] = acc;
-                s_l[tt][j] = acc;
+                s_l[wave][j] = acc;
             }
         }
-        if (lane == 0) hnorm[g] = sqrt(ss);
+        if (lane == 0) hnorm[g] = sqrt(sst);
     }
     __syncthreads();
     if (threadIdx.x < n_q) {
@@ -142,8 +229,10 @@ __global__ __launch_bounds__(256) void score_logits_kernel(Batch bt, const char*
     }
 }
 
-// Eq. 2, pass 2: combine the partials into (max, normaliser) per head, then
-// s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.  grid (ceil(n_max/256), B), block 256.
+// ------------------------------------------------------------------------------------------
+// Eq. 2, pass 2 on its own (stand-alone pact_score): combine the partials into (max,
+// normaliser) per head, then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
+// grid (ceil(n_max/256), B), block 256.
 __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
                                                           const double* __restrict__ logits,
                                                           const double* __restrict__ hnorm,
@@ -178,17 +267,28 @@ __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 3/4: exact radix select of the (m+1)-th smallest fp32 score, then an ordered
-// compaction into kept / pruned index lists.  One workgroup of 1024 per sample.
+// Eq. 2 pass 2 + Eq. 3/4, one workgroup of 1024 per sample:
+//   (a) combine the softmax partials into (max, normaliser) per head;
+//   (b) s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j, rounded to fp32, written out and
+//       kept in LDS as order-preserving integer keys;          [skipped when scores are given]
+//   (c) exact radix select of the (m+1)-th smallest key, m = min(floor(lambda n), n-1);
+//   (d) ordered compaction into the kept / pruned index lists.
+// Dynamic LDS: n_max * 4 bytes.
 __device__ __forceinline__ uint32_t ordered_key(float f) {
     const uint32_t u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __restrict__ scores,
-                                                     int32_t* __restrict__ kept_idx,
-                                                     int32_t* __restrict__ pruned_idx,
-                                                     pact_report* __restrict__ rep) {
+__global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, int have_scores,
+                                                           const double* __restrict__ logits,
+                                                           const double* __restrict__ hnorm,
+                                                           const double* __restrict__ sm_part,
+                                                           float* scores,
+                                                           int32_t* __restrict__ kept_idx,
+                                                           int32_t* __restrict__ pruned_idx,
+                                                           pact_report* __restrict__ rep) {
+    extern __shared__ uint32_t s_key[];
+    __shared__ double s_M[PACT_MAX_QHEADS], s_Z[PACT_MAX_QHEADS];
     __shared__ int s_hist[256];
     __shared__ int s_digit, s_newk;
     __shared__ int s_wtot[16];
@@ -198,7 +298,35 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const float* s = scores + sg.base;
+    float* s = scores + sg.base;
+
+    if (!have_scores) {
+        const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+        const int nwg = (n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+        for (int j = wave; j < n_q; j += 16) {
+            const double* part = sm_part + ((size_t)b * smwg * n_q + j) * 2;
+            double m = -INFINITY;
+            for (int w = lane; w < nwg; w += 64) m = fmax(m, part[(size_t)w * n_q * 2]);
+            m = wave_max_f64(m);
+            double z = 0.0;
+            for (int w = lane; w < nwg; w += 64)
+                z += part[(size_t)w * n_q * 2 + 1] * exp(part[(size_t)w * n_q * 2] - m);
+            z = wave_sum_f64(z);
+            if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
+        }
+        __syncthreads();
+        for (int i = tid; i < n; i += 1024) {
+            const size_t g = (size_t)sg.base + i;
+            double acc = 0.0;
+            for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
+            const float v = (float)(hnorm[g] * (acc / (double)n_q));
+            s[i] = v;
+            s_key[i] = ordered_key(v);
+        }
+    } else {
+        for (int i = tid; i < n; i += 1024) s_key[i] = ordered_key(s[i]);
+    }
+    __syncthreads();
 
     int k = (int)floor((double)sg.lambda * (double)n);
     if (k > n - 1) k = n - 1;
@@ -209,7 +337,7 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
         if (tid < 256) s_hist[tid] = 0;
         __syncthreads();
         for (int i = tid; i < n; i += 1024) {
-            const uint32_t u = ordered_key(s[i]);
+            const uint32_t u = s_key[i];
             if ((u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255], 1);
         }
         __syncthreads();
@@ -223,7 +351,7 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
                 const int v = __shfl_up(inc, d, 64);
                 if (lane >= d) inc += v;
             }
-            int e = inc - loc;   // scores with a smaller digit in earlier bins
+            int e = inc - loc;   // keys with a smaller digit
             const int c[4] = {c0, c1, c2, c3};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -243,7 +371,7 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
     const int i0 = min(n, tid * chunk);
     const int i1 = min(n, i0 + chunk);
     int cnt = 0;
-    for (int i = i0; i < i1; ++i) cnt += ordered_key(s[i]) >= tau;
+    for (int i = i0; i < i1; ++i) cnt += s_key[i] >= tau;
     int inc = cnt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -262,7 +390,7 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
     int32_t* ko = kept_idx + sg.base;
     int32_t* po = pruned_idx + sg.base;
     for (int i = i0; i < i1; ++i) {
-        if (ordered_key(s[i]) >= tau) ko[kp++] = i;
+        if (s_key[i] >= tau) ko[kp++] = i;
         else po[pp++] = i;
     }
     if (tid == 0) {
@@ -272,31 +400,55 @@ __global__ __launch_bounds__(1024) void prune_kernel(Batch bt, const float* __re
 }
 
 // ------------------------------------------------------------------------------------------
+static hipError_t raise_lds_limit(const void* fn, size_t bytes) {
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int KDT>
+static int launch_prep_q(const Batch& bt, const PrepArgs& a, pact_dtype q_dt, dim3 grid, hipStream_t st) {
+    if (q_dt == PACT_BF16)
+        PACT_LAUNCH("prep", (prep_kernel<KDT, PACT_BF16>), grid, dim3(256), st, bt, a);
+    else
+        PACT_LAUNCH("prep", (prep_kernel<KDT, PACT_F32>), grid, dim3(256), st, bt, a);
+    return PACT_OK;
+}
+
+int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                const void* q, pact_dtype q_dt, int32_t qcols, pact_report* rep, int32_t* cluster_id,
+                int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st) {
+    PrepArgs a;
+    a.keys = (const char*)keys; a.dk = dk; a.key_dt_unused = 0;
+    a.q = (const char*)q; a.qcols = qcols;
+    a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
+    a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt; a.round_new = w.round_new;
+    a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
+    a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;
+    dim3 grid(a.n_key_blocks + (q ? QG_CHUNKS : 0), bt.B);
+    return (k_dt == PACT_BF16) ? launch_prep_q<PACT_BF16>(bt, a, q_dt, grid, st)
+                               : launch_prep_q<PACT_F32>(bt, a, q_dt, grid, st);
+}
+
 template <int HDT>
 static int launch_logits_k(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
     dim3 grid((bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
     if (in.k_dt == PACT_BF16)
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_BF16>), grid, dim3(256), st, bt,
+        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt,
                     (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
                     w.qg, w.logits, w.hnorm, w.sm_part);
     else
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_F32>), grid, dim3(256), st, bt,
+        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt,
                     (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
                     w.qg, w.logits, w.hnorm, w.sm_part);
     return PACT_OK;
 }
 
-int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, float* scores, hipStream_t st) {
+// Scores for every sample.  The per-token query pass (Eq. 1 pass 1) must already have run
+// (launch_prep with q != nullptr) when in.q_per_token is set.
+int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
     const int qcols = in.n_q * in.d_h;
     if (in.q_per_token) {
-        if (in.q_dt == PACT_BF16)
-            PACT_LAUNCH("qglobal_partial", qglobal_partial_kernel<PACT_BF16>, dim3(QG_CHUNKS, bt.B),
-                        dim3(256), st, bt, (const char*)in.q, qcols, w.qg_part);
-        else
-            PACT_LAUNCH("qglobal_partial", qglobal_partial_kernel<PACT_F32>, dim3(QG_CHUNKS, bt.B),
-                        dim3(256), st, bt, (const char*)in.q, qcols, w.qg_part);
-        PACT_LAUNCH("qglobal_final", qglobal_final_kernel, dim3((qcols + 255) / 256, bt.B), dim3(256),
-                    st, bt, qcols, w.qg_part, w.qg);
+        PACT_LAUNCH("qglobal_final", qglobal_final_kernel, dim3((qcols + 63) / 64, bt.B), dim3(1024), st,
+                    bt, qcols, w.qg_part, w.qg);
     } else {
         if (in.q_dt == PACT_BF16)
             PACT_LAUNCH("qglobal_copy", qglobal_copy_kernel<PACT_BF16>, dim3((qcols + 255) / 256, bt.B),
@@ -305,18 +457,27 @@ int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, float* scores,
             PACT_LAUNCH("qglobal_copy", qglobal_copy_kernel<PACT_F32>, dim3((qcols + 255) / 256, bt.B),
                         dim3(256), st, bt, (const char*)in.q, qcols, w.qg);
     }
-    int rc = (in.h_dt == PACT_BF16) ? launch_logits_k<PACT_BF16>(bt, w, in, st)
-                                    : launch_logits_k<PACT_F32>(bt, w, in, st);
-    if (rc != PACT_OK) return rc;
-    PACT_LAUNCH("score_final", score_final_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st,
-                bt, in.n_q, w.logits, w.hnorm, w.sm_part, scores);
+    return (in.h_dt == PACT_BF16) ? launch_logits_k<PACT_BF16>(bt, w, in, st)
+                                  : launch_logits_k<PACT_F32>(bt, w, in, st);
+}
+
+int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st) {
+    PACT_LAUNCH("score_final", score_final_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt,
+                n_q, w.logits, w.hnorm, w.sm_part, scores);
     return PACT_OK;
 }
 
-int launch_prune(const Batch& bt, const float* scores, int32_t* kept_idx, int32_t* pruned_idx,
-                 pact_report* rep, hipStream_t st) {
-    PACT_LAUNCH("prune_select", prune_kernel, dim3(bt.B), dim3(1024), st, bt, scores, kept_idx,
-                pruned_idx, rep);
+// Finishes the scores (unless have_scores) and splits them.
+int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, float* scores,
+                       int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep, hipStream_t st) {
+    const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(uint32_t);
+    static size_t raised = 0;
+    if (lds > 48 * 1024 && lds > raised) {
+        if (raise_lds_limit((const void*)score_prune_kernel, lds) != hipSuccess) return PACT_ERR_HIP;
+        raised = lds;
+    }
+    PACT_LAUNCH_SHMEM("score_prune", score_prune_kernel, dim3(bt.B), dim3(1024), lds, st, bt, n_q,
+                      have_scores ? 1 : 0, w.logits, w.hnorm, w.sm_part, scores, kept_idx, pruned_idx, rep);
     return PACT_OK;
 }
 

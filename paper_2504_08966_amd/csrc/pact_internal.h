@@ -31,7 +31,8 @@ struct Batch {
 // ---------------------------------------------------------------------------------------
 // Workspace layout.  Offsets in bytes from the 256-aligned workspace base.
 constexpr int QG_CHUNKS = 128;        // row chunks of the global-query column sum
-constexpr int SCORE_TOK_PER_WG = 16;  // tokens per workgroup in the logits kernel
+constexpr int SCORE_TOK_PER_WG = 8;   // tokens (= wavefronts) per workgroup in the logits kernel
+constexpr int PRED_CAP = 64;          // preceding neighbours listed per kept token (16-bit positions)
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
 constexpr int MAX_ROUNDS = 8;         // parallel centre rounds launched before the finishing kernel
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
@@ -43,6 +44,7 @@ struct WsLayout {
     size_t adj;                                        // [B][n_max][W] u64: rows < q adjacency, rows q.. candidates
     size_t rho_part;                                   // [B][W][n_max] f64
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
+    size_t preds, pcnt;                                // [B][n_max][PRED_CAP] u16, [B][n_max] i32
     size_t near_list, near_cnt, round_new;             // refine list, counters
     size_t cursor, offsets, members;                   // merge CSR (global row index)
     size_t total;
@@ -71,6 +73,8 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.status = take(sizeof(uint32_t) * B * n_max);
     L.cnum = take(sizeof(int32_t) * B * n_max);
     L.cmask = take(sizeof(uint64_t) * B * W);
+    L.preds = take(sizeof(uint16_t) * B * n_max * PRED_CAP);
+    L.pcnt = take(sizeof(int32_t) * B * n_max);
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
     L.near_cnt = take(sizeof(int32_t) * B);
     L.round_new = take(sizeof(int32_t) * B * MAX_ROUNDS);
@@ -86,7 +90,7 @@ struct Ws {
     double* qg_part; double* qg; double* logits; double* hnorm; double* sm_part;
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
-    int32_t* cnum; uint64_t* cmask; uint32_t* near_list; int32_t* near_cnt; int32_t* round_new;
+    int32_t* cnum; uint64_t* cmask; uint16_t* preds; int32_t* pcnt; uint32_t* near_list; int32_t* near_cnt; int32_t* round_new;
     int32_t* cursor; int32_t* offsets; int32_t* members;
 };
 
@@ -100,6 +104,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.adj = (uint64_t*)(p + L.adj); w.rho_part = (double*)(p + L.rho_part);
     w.rho = (double*)(p + L.rho); w.rank = (int32_t*)(p + L.rank);
     w.status = (uint32_t*)(p + L.status); w.cnum = (int32_t*)(p + L.cnum);
+    w.preds = (uint16_t*)(p + L.preds); w.pcnt = (int32_t*)(p + L.pcnt);
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
     w.near_cnt = (int32_t*)(p + L.near_cnt); w.round_new = (int32_t*)(p + L.round_new);
     w.cursor = (int32_t*)(p + L.cursor); w.offsets = (int32_t*)(p + L.offsets);
@@ -136,13 +141,15 @@ struct ScoreIn {
     const void* q; pact_dtype q_dt; int32_t q_per_token; int32_t n_q;   // q_per_token: 1 = [total, ..], 0 = [B, ..]
 };
 
-int launch_init(const Batch& bt, const Ws& w, pact_report* rep, int32_t* cluster_id,
+// First kernel of every call: key norms, cleared bitmap rows, per-token initial state and
+// (q != nullptr) the first pass of Eq. 1.
+int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
+                const void* q, pact_dtype q_dt, int32_t qcols, pact_report* rep, int32_t* cluster_id,
                 int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st);
-int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, float* scores, hipStream_t st);
-int launch_prune(const Batch& bt, const float* scores, int32_t* kept_idx, int32_t* pruned_idx,
-                 pact_report* rep, hipStream_t st);
-int launch_key_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
-                    pact_report* rep, hipStream_t st);
+int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st);
+int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st);
+int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, float* scores,
+                       int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep, hipStream_t st);
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                         const int32_t* idx, pact_report* rep, hipStream_t st);
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -158,7 +165,7 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
                  hipStream_t st);
 
 // init modes
-enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_MERGE = 4 };
+enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_SCORE = 4 };
 
 // Worst-case rounding error of an fp32 matrix-core cosine of two dk-long rows, plus slack for
 // the scaling multiplies; decisions closer than this to a threshold are re-made in fp64.

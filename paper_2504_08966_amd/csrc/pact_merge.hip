@@ -7,35 +7,40 @@
 
 namespace pact {
 
-// Recount members (stand-alone pact_merge).  grid (ceil(n_max/256), B), block 256.
-__global__ __launch_bounds__(256) void count_members_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
-                                                            const pact_report* __restrict__ rep,
-                                                            int32_t* cluster_counts) {
-    const int b = blockIdx.y;
-    const Seg sg = bt.s[b];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sg.n) return;
-    const int cid = cluster_id[sg.base + i];
-    if (cid >= 0 && cid < clamp_count(rep[b].n_centers, sg.n)) atomicAdd(&cluster_counts[sg.base + cid], 1);
-}
-
-// Exclusive scan of the cluster sizes -> CSR offsets; clears the fill cursors.
-// grid (B), block 1024.  offsets of sample b live at [base + b, base + b + C].
-__global__ __launch_bounds__(1024) void scan_offsets_kernel(Batch bt, const pact_report* __restrict__ rep,
-                                                            const int32_t* __restrict__ cluster_counts,
-                                                            int32_t* offsets, int32_t* cursor) {
+// Member lists (CSR) of all clusters of a sample, by one workgroup: cluster sizes (taken from
+// cluster_counts, or recounted from cluster_id for a stand-alone merge), their exclusive scan,
+// and the fill with LDS cursors.  grid (B), block 1024, dynamic LDS n_max * 4 bytes.
+// offsets of sample b live at [base + b, base + b + C].
+__global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
+                                                         const pact_report* __restrict__ rep,
+                                                         int32_t* cluster_counts, int recount,
+                                                         int32_t* offsets, int32_t* members) {
+    extern __shared__ int s_cur[];          // [C]: sizes, then running fill cursors
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int C = clamp_count(rep[b].n_centers, sg.n);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t* cnt = cluster_counts + sg.base;
+    int32_t* cnt = cluster_counts + sg.base;
     int32_t* off = offsets + sg.base + b;
-    int32_t* cur = cursor + sg.base;
+    const int32_t* cid = cluster_id + sg.base;
+    if (recount) {
+        for (int c = tid; c < C; c += 1024) s_cur[c] = 0;
+        __syncthreads();
+        for (int i = tid; i < sg.n; i += 1024) {
+            const int c = cid[i];
+            if (c >= 0 && c < C) atomicAdd(&s_cur[c], 1);
+        }
+        __syncthreads();
+        for (int c = tid; c < C; c += 1024) cnt[c] = s_cur[c];
+    } else {
+        for (int c = tid; c < C; c += 1024) s_cur[c] = cnt[c];
+    }
+    __syncthreads();
     const int chunk = (C + 1023) / 1024;
     const int c0 = min(C, tid * chunk), c1 = min(C, c0 + chunk);
     int loc = 0;
-    for (int c = c0; c < c1; ++c) loc += cnt[c];
+    for (int c = c0; c < c1; ++c) loc += s_cur[c];
     int inc = loc;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -47,27 +52,19 @@ __global__ __launch_bounds__(1024) void scan_offsets_kernel(Batch bt, const pact
     int run = inc - loc;
     for (int w = 0; w < wave; ++w) run += s_wtot[w];
     for (int c = c0; c < c1; ++c) {
+        const int sz = s_cur[c];
         off[c] = run;
-        cur[c] = 0;
-        run += cnt[c];
+        s_cur[c] = run;                     // cursor starts at the segment's offset
+        run += sz;
     }
     if (c1 == C && c0 < C) off[C] = run;
     if (C == 0 && tid == 0) off[0] = 0;
-}
-
-// grid (ceil(n_max/256), B), block 256.
-__global__ __launch_bounds__(256) void fill_members_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
-                                                           const pact_report* __restrict__ rep,
-                                                           const int32_t* __restrict__ offsets,
-                                                           int32_t* cursor, int32_t* members) {
-    const int b = blockIdx.y;
-    const Seg sg = bt.s[b];
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= sg.n) return;
-    const int cid = cluster_id[sg.base + i];
-    if (cid < 0 || cid >= clamp_count(rep[b].n_centers, sg.n)) return;
-    const int pos = atomicAdd(&cursor[sg.base + cid], 1);
-    members[sg.base + offsets[sg.base + b + cid] + pos] = i;
+    __syncthreads();
+    int32_t* mem = members + sg.base;
+    for (int i = tid; i < sg.n; i += 1024) {
+        const int c = cid[i];
+        if (c >= 0 && c < C) mem[atomicAdd(&s_cur[c], 1)] = i;
+    }
 }
 
 constexpr int MERGE_LDS_MEMBERS = 1024;
@@ -97,9 +94,9 @@ template <> struct StoreOut<PACT_BF16> {
     }
 };
 
-// One workgroup per cluster (persistent over clusters).  grid (min(n_max, 4096), B), block 256.
+// One workgroup per cluster (persistent over clusters).  grid (min(n_max, 4096), B), block 512.
 template <int HDT, int ODT>
-__global__ __launch_bounds__(256) void merge_kernel(Batch bt, const char* __restrict__ hidden, int h,
+__global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __restrict__ hidden, int h,
                                                      const int32_t* __restrict__ cluster_id,
                                                      const int32_t* __restrict__ center_idx,
                                                      const pact_report* __restrict__ rep,
@@ -126,9 +123,9 @@ __global__ __launch_bounds__(256) void merge_kernel(Batch bt, const char* __rest
             if (tid == 0) s_sorted[0] = center_idx[sg.base + c];
         } else if (m <= MERGE_LDS_MEMBERS) {
             const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
-            for (int k = tid; k < m; k += 256) s_raw[k] = mem[k];
+            for (int k = tid; k < m; k += 512) s_raw[k] = mem[k];
             __syncthreads();
-            for (int k = tid; k < m; k += 256) {
+            for (int k = tid; k < m; k += 512) {
                 const int v = s_raw[k];
                 int pos = 0;
                 for (int u = 0; u < m; ++u) pos += (s_raw[u] < v);
@@ -139,17 +136,27 @@ __global__ __launch_bounds__(256) void merge_kernel(Batch bt, const char* __rest
         }
         __syncthreads();
         const int m_eff = no_merge ? 1 : m;
-        for (int e = tid * EPL; e < h; e += 256 * EPL) {
+        for (int e = tid * EPL; e < h; e += 512 * EPL) {
             double acc[EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[i] = 0.0;
+            for (int i = 0; i < EPL; ++i) acc[i] = -0.0;   // additive identity that keeps the sign of -0.0
             if (in_lds) {
-                for (int k = 0; k < m_eff; ++k) {
-                    const uint4 v = *(const uint4*)(hb + (size_t)s_sorted[k] * hrow + (size_t)e * Elem<HDT>::BYTES);
-                    double x[8];
-                    Elem<HDT>::widen(v, x);
+                const char* hcol = hb + (size_t)e * Elem<HDT>::BYTES;
+                for (int k = 0; k < m_eff; k += 4) {
+                    uint4 v[4];
 #pragma unroll
-                    for (int i = 0; i < EPL; ++i) acc[i] += x[i];
+                    for (int u = 0; u < 4; ++u)
+                        v[u] = (k + u < m_eff) ? *(const uint4*)(hcol + (size_t)s_sorted[k + u] * hrow)
+                                               : make_uint4(0, 0, 0, 0);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (k + u < m_eff) {          // (skipping keeps -0.0 rows exact)
+                            double x[8];
+                            Elem<HDT>::widen(v[u], x);
+#pragma unroll
+                            for (int i = 0; i < EPL; ++i) acc[i] += x[i];
+                        }
+                    }
                 }
             } else {
                 // very large cluster: walk the tokens in index order (no list to sort)
@@ -177,10 +184,10 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
                           void* merged, pact_dtype out_dt, const int32_t* cluster_counts, hipStream_t st) {
     dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
     if (out_dt == PACT_BF16)
-        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(256), st, bt, (const char*)hidden,
+        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt, (const char*)hidden,
                     h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
     else
-        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(256), st, bt, (const char*)hidden,
+        PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt, (const char*)hidden,
                     h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
     return PACT_OK;
 }
@@ -189,14 +196,16 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
                  const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
                  hipStream_t st) {
-    dim3 gtok((bt.n_max + 255) / 256, bt.B);
-    if (recount)
-        PACT_LAUNCH("count_members", count_members_kernel, gtok, dim3(256), st, bt, cluster_id, rep,
-                    cluster_counts);
-    PACT_LAUNCH("scan_offsets", scan_offsets_kernel, dim3(bt.B), dim3(1024), st, bt, rep, cluster_counts,
-                w.offsets, w.cursor);
-    PACT_LAUNCH("fill_members", fill_members_kernel, gtok, dim3(256), st, bt, cluster_id, rep, w.offsets,
-                w.cursor, w.members);
+    const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(int);
+    static size_t raised = 0;
+    if (lds > 48 * 1024 && lds > raised) {
+        if (hipFuncSetAttribute((const void*)scan_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PACT_ERR_HIP;
+        raised = lds;
+    }
+    PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id, rep,
+                      cluster_counts, recount ? 1 : 0, w.offsets, w.members);
     if (h_dt == PACT_BF16)
         return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
                                          cluster_counts, st);
