@@ -96,13 +96,14 @@ static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStrea
     ScoreIn si{io.hidden, io.h_dt, io.h, io.keys_pre, io.k_dt, io.n_kv, io.d_h, io.q, io.q_dt,
                io.q_per_token, io.n_q};
     if ((rc = launch_score(bt, w, si, st))) return rc;
-    if ((rc = launch_score_prune(bt, w, io.n_q, false, io.scores, io.kept_idx, io.pruned_idx, io.rep, st)))
+    if ((rc = launch_score_only(bt, w, io.n_q, io.scores, st))) return rc;
+    if ((rc = launch_score_prune(bt, w, io.n_q, true, io.scores, io.kept_idx, io.pruned_idx, io.rep, st)))
         return rc;
     if ((rc = launch_gram_density(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.rep, st))) return rc;
     if ((rc = launch_centres(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.center_idx, io.cluster_id,
                              io.cluster_counts, io.rep, nullptr, nullptr, st))) return rc;
     if ((rc = launch_reincorporate(bt, w, io.keys, io.k_dt, dk, io.pruned_idx, io.center_idx,
-                                   io.cluster_id, io.cluster_counts, io.rep, st))) return rc;
+                                   io.cluster_id, io.cluster_counts, io.rep, false, st))) return rc;
     return launch_merge(bt, w, io.hidden, io.h_dt, io.h, io.cluster_id, io.center_idx, io.rep, io.merged,
                         io.out_dt, io.cluster_counts, false, st);
 }
@@ -219,7 +220,7 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     hipStream_t st = (hipStream_t)stream;
     if ((rc = launch_prep(bt, w, keys, k_dt, dk, nullptr, PACT_F32, 0, rep, cluster_id, nullptr, INIT_REINC,
                           nullptr, st))) return rc;
-    return launch_reincorporate(bt, w, keys, k_dt, dk, pruned_idx, center_idx, cluster_id, nullptr, rep, st);
+    return launch_reincorporate(bt, w, keys, k_dt, dk, pruned_idx, center_idx, cluster_id, nullptr, rep, true, st);
 }
 
 int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,

@@ -15,7 +15,7 @@
 
 namespace pact {
 
-constexpr int KP = PRED_CAP;   // preceding neighbours kept per token; more -> bitmap fallback
+constexpr int KP = PRED_CAP - 1;   // preceding neighbours kept per token (slot 0 holds the count); more -> bitmap fallback
 
 __device__ __forceinline__ bool precedes(double rho_j, int j, double rho_i, int i) {
     return rho_j > rho_i || (rho_j == rho_i && j < i);
@@ -27,14 +27,25 @@ template <int DT>
 __device__ __forceinline__ double group8_dot64(const char* ra, const char* rb, int dk, int sub) {
     constexpr int EPL = Elem<DT>::EPL;
     double acc = 0.0;
-    for (int e = sub * EPL; e < dk; e += 8 * EPL) {
-        const uint4 va = *(const uint4*)(ra + (size_t)e * Elem<DT>::BYTES);
-        const uint4 vb = *(const uint4*)(rb + (size_t)e * Elem<DT>::BYTES);
-        double a[8], b[8];
-        Elem<DT>::widen(va, a);
-        Elem<DT>::widen(vb, b);
+    for (int e0 = sub * EPL; e0 < dk; e0 += 4 * 8 * EPL) {       // 4 independent load pairs in flight
+        uint4 va[4], vb[4];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * 8 * EPL;
+            const size_t o = (size_t)(e < dk ? e : e0) * Elem<DT>::BYTES;
+            va[u] = *(const uint4*)(ra + o);
+            vb[u] = *(const uint4*)(rb + o);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (e0 + u * 8 * EPL < dk) {
+                double a[8], b[8];
+                Elem<DT>::widen(va[u], a);
+                Elem<DT>::widen(vb[u], b);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
+            }
+        }
     }
 #pragma unroll
     for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
@@ -45,7 +56,7 @@ __device__ __forceinline__ double group8_dot64(const char* ra, const char* rb, i
 // tok_of(c) maps a candidate id to its token; only distances < thr compete; ties go to the
 // lower candidate id.  Updates (best, bestc), identical in every lane.
 template <int DT, typename TokOf>
-__device__ __forceinline__ void nearest_candidate(const int* cand, int ncand, const char* mine, double nnp,
+__device__ __forceinline__ void nearest_candidate(const lds_i32* cand, int ncand, const char* mine, double nnp,
                                                   const char* kb, size_t row_bytes, const double* nnb,
                                                   int dk, int lane, double thr, TokOf tok_of,
                                                   double& best, int& bestc) {
@@ -76,7 +87,7 @@ __device__ __forceinline__ void nearest_candidate(const int* cand, int ncand, co
 //   the other blocks: Eq. 6 completed, rho_p = sum over the 64-row blocks of the column
 //       partials (64 tokens x 4 slices per block).  With d_n = 2 every term is an fp32 value
 //       in [e^-1, 1], so these fp64 additions are exact whatever their order.
-constexpr int REFINE_BLOCKS = 64;
+constexpr int REFINE_BLOCKS = 256;
 
 template <int DT>
 __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __restrict__ keys, int dk,
@@ -200,13 +211,13 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 }
 
 // For every kept token: the list of its neighbours (bitmap row) that precede it in the
-// density order, as 16-bit positions; pcnt = list length, or KP+1 if it did not fit.
-// One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+// density order, as 16-bit positions in slots 1..KP of its PRED_CAP-slot record; slot 0 holds
+// the list length, or KP+1 if the list did not fit (the token is then evaluated from its
+// bitmap row).  One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
 __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
                                                           const uint64_t* __restrict__ adj,
                                                           const double* __restrict__ rho,
-                                                          uint16_t* __restrict__ preds,
-                                                          int32_t* __restrict__ pcnt) {
+                                                          uint16_t* __restrict__ preds) {
     const int b = blockIdx.y;
     const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
     const int lane = threadIdx.x & 63;
@@ -215,7 +226,7 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
     const double* r = rho + (size_t)b * bt.n_max;
     const double rp = r[p];
     const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
-    uint16_t* out = preds + ((size_t)b * bt.n_max + p) * KP;
+    uint16_t* out = preds + ((size_t)b * bt.n_max + p) * PRED_CAP;
     const int Wq = (q + 63) >> 6;
     int total = 0;
     for (int w0 = 0; w0 < Wq; w0 += 64) {
@@ -228,28 +239,49 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
             const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
             const uint64_t m = __ballot(pre);
             const int slot = total + lanes_below(m, lane);
-            if (pre && slot < KP) out[slot] = (uint16_t)j;
+            if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
             total += __popcll(m);
         }
     }
-    if (lane == 0) pcnt[(size_t)b * bt.n_max + p] = total > KP ? KP + 1 : total;
+    if (lane == 0) out[0] = (uint16_t)(total > KP ? KP + 1 : total);
+}
+
+// Status checks of the 8 slots of one 16-byte piece of a predecessor record; slot s of the
+// piece is list position pos0 + s, valid for 1 <= position <= c.
+__device__ __forceinline__ void check_preds8(const uint4& v, int pos0, int c, lds_vu8* st,
+                                             int dummy, bool& blocked, bool& pending) {
+    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+    unsigned char sj[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {          // eight independent LDS reads; st[dummy] == ST_NOT
+        const int pos = pos0 + t;
+        const int j = (wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF;
+        sj[t] = st[(pos >= 1 && pos <= c) ? j : dummy];
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        blocked |= (sj[t] == ST_CENTER);
+        pending |= (sj[t] == ST_UNKNOWN);
+    }
 }
 
 // All rounds of the centre selection in one workgroup per sample, statuses in LDS; then the
-// centres are numbered in ascending token order and published.  Tokens whose list overflowed
-// are evaluated from their bitmap row by a whole wavefront.  grid (B), block 1024,
-// dynamic LDS: n_max bytes (status) + n_max * 2 bytes (overflow token list).
+// centres are numbered in ascending token order and published.  Each thread owns the tokens
+// tid, tid + 1024, ... and keeps the first 32 bytes of their records (count + 15
+// predecessors) in registers across the rounds, so most tokens never touch memory again.
+// Tokens whose list overflowed are evaluated from their bitmap row by a whole wavefront.
+// grid (B), block 1024, dynamic LDS: (n_max + 64) bytes (status) + n_max * 2 bytes (overflow
+// token list) + W * 4 bytes (centres per 64 tokens).
+constexpr int RESOLVE_CACHED = 4;     // 4 tokens x 32 bytes: what fits beside the rest in 128 VGPRs
 __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_report* rep,
                                                               const uint64_t* __restrict__ adj,
                                                               const double* __restrict__ rho,
                                                               const uint16_t* __restrict__ preds,
-                                                              const int32_t* __restrict__ pcnt,
                                                               const int32_t* __restrict__ idx,
                                                               uint32_t* status, int32_t* cnum,
                                                               uint64_t* cmask, int32_t* center_idx) {
     extern __shared__ unsigned char s_raw[];
     __shared__ int s_unknown, s_nover;
-    __shared__ int s_wtot[16];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
@@ -257,18 +289,31 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int qpad = (bt.n_max + 63) / 64 * 64;
-    volatile unsigned char* s_st = s_raw;                       // [qpad]
-    uint16_t* s_over = (uint16_t*)(s_raw + qpad);                // [n_max]
+    lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64], s_st[qpad] = ST_NOT
+    lds_u16* s_over = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
+    lds_i32* s_wcnt = (lds_i32*)(s_raw + qpad + 64 + (size_t)qpad * 2);   // [W + 1]
+    const int dummy = qpad;
     const double* r = rho + (size_t)b * bt.n_max;
-    const int32_t* pc = pcnt + (size_t)b * bt.n_max;
+    const uint4* rec = (const uint4*)(preds + (size_t)b * bt.n_max * PRED_CAP);   // 8 pieces per token
     const int Wq = (q + 63) >> 6;
 
-    if (tid == 0) s_nover = 0;
+    if (tid == 0) { s_nover = 0; s_st[dummy] = ST_NOT; }
     __syncthreads();
-    for (int p = tid; p < q; p += 1024) {
-        s_st[p] = ST_UNKNOWN;
-        if (pc[p] > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    uint4 rc0[RESOLVE_CACHED], rc1[RESOLVE_CACHED];
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) {
+        const int p = tid + 1024 * k;
+        rc0[k] = (p < q) ? rec[(size_t)p * 8] : make_uint4(0, 0, 0, 0);
+        rc1[k] = (p < q) ? rec[(size_t)p * 8 + 1] : make_uint4(0, 0, 0, 0);
     }
+    for (int p = tid; p < q; p += 1024) s_st[p] = ST_UNKNOWN;
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) {
+        const int p = tid + 1024 * k;
+        if (p < q && (int)(rc0[k].x & 0xFFFF) > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    }
+    for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024)
+        if ((int)(rec[(size_t)p * 8].x & 0xFFFF) > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
     __syncthreads();
     const int nover = s_nover;
     int rounds = 0;
@@ -276,25 +321,32 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         if (tid == 0) s_unknown = 0;
         __syncthreads();
         bool still = false;
-        for (int p = tid; p < q; p += 1024) {
-            if (s_st[p] != ST_UNKNOWN) continue;
-            const int c = pc[p];
-            if (c > KP) continue;
-            const uint4* pl = (const uint4*)(preds + ((size_t)b * bt.n_max + p) * KP);
-            bool blocked = false, pending = false;
-            for (int k = 0; k < c; k += 8) {
-                const uint4 v = pl[k >> 3];
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    if (k + t < c) {
-                        const int j = (wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF;
-                        const unsigned char sj = s_st[j];
-                        blocked |= (sj == ST_CENTER);
-                        pending |= (sj == ST_UNKNOWN);
-                    }
+        for (int k = 0; k < RESOLVE_CACHED; ++k) {
+            const int p = tid + 1024 * k;
+            if (p < q && s_st[p] == ST_UNKNOWN) {
+                const int c = rc0[k].x & 0xFFFF;
+                if (c <= KP) {
+                    bool blocked = false, pending = false;
+                    check_preds8(rc0[k], 0, c, s_st, dummy, blocked, pending);
+                    if (c >= 8) check_preds8(rc1[k], 8, c, s_st, dummy, blocked, pending);
+                    for (int piece = 2; piece * 8 <= c && !blocked; ++piece)
+                        check_preds8(rec[(size_t)p * 8 + piece], piece * 8, c, s_st, dummy, blocked, pending);
+                    if (blocked) s_st[p] = ST_NOT;
+                    else if (!pending) s_st[p] = ST_CENTER;
+                    else still = true;
                 }
             }
+        }
+        for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {
+            if (s_st[p] != ST_UNKNOWN) continue;
+            const uint4 f = rec[(size_t)p * 8];
+            const int c = f.x & 0xFFFF;
+            if (c > KP) continue;
+            bool blocked = false, pending = false;
+            check_preds8(f, 0, c, s_st, dummy, blocked, pending);
+            for (int piece = 1; piece * 8 <= c && !blocked; ++piece)
+                check_preds8(rec[(size_t)p * 8 + piece], piece * 8, c, s_st, dummy, blocked, pending);
             if (blocked) s_st[p] = ST_NOT;
             else if (!pending) s_st[p] = ST_CENTER;
             else still = true;
@@ -332,44 +384,50 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         __syncthreads();
         if (!more) break;
     }
-    // number the centres in ascending p (= ascending token index)
-    const int chunk = (q + 1023) / 1024;
-    const int p0 = min(q, tid * chunk), p1 = min(q, p0 + chunk);
-    int cnt = 0;
-    for (int p = p0; p < p1; ++p) cnt += (s_st[p] == ST_CENTER);
-    int inc = cnt;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int v = __shfl_up(inc, d, 64);
-        if (lane >= d) inc += v;
+    // Publish: one ballot per 64 tokens gives the centre mask word; the centres are numbered in
+    // ascending p (= ascending token index) from the running sum of the words' popcounts.
+    uint64_t* cm = cmask + (size_t)b * bt.W;
+    for (int w = wave; w < Wq; w += 16) {
+        const int p = (w << 6) + lane;
+        const uint64_t m = __ballot(p < q && s_st[p] == ST_CENTER);
+        if (lane == 0) { cm[w] = m; s_wcnt[w] = __popcll(m); }
     }
-    if (lane == 63) s_wtot[wave] = inc;
     __syncthreads();
-    int woff = 0, total = 0;
-    for (int w = 0; w < 16; ++w) {
-        if (w < wave) woff += s_wtot[w];
-        total += s_wtot[w];
+    if (wave == 0) {                                          // exclusive scan over the words
+        int run = 0;
+        for (int w0 = 0; w0 < Wq; w0 += 64) {
+            const int w = w0 + lane;
+            const int v = (w < Wq) ? s_wcnt[w] : 0;
+            int inc = v;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(inc, d, 64);
+                if (lane >= d) inc += t;
+            }
+            if (w < Wq) s_wcnt[w] = run + inc - v;
+            run += __shfl(inc, 63, 64);
+        }
+        if (lane == 0) s_wcnt[Wq] = run;
     }
-    int c = woff + inc - cnt;
+    __syncthreads();
     uint32_t* st = status + (size_t)b * bt.n_max;
     int32_t* cn = cnum + (size_t)b * bt.n_max;
     const int32_t* ix = idx + sg.base;
     int32_t* co = center_idx + sg.base;
-    for (int p = p0; p < p1; ++p) {
-        const bool isc = s_st[p] == ST_CENTER;
-        st[p] = s_st[p];
-        cn[p] = isc ? c : -1;
-        if (isc) co[c++] = ix[p];
-    }
-    uint64_t* cm = cmask + (size_t)b * bt.W;
-    for (int w = tid; w < Wq; w += 1024) {
-        uint64_t m = 0;
-        const int pe = min(q, (w + 1) << 6);
-        for (int p = w << 6; p < pe; ++p) m |= (uint64_t)(s_st[p] == ST_CENTER) << (p & 63);
-        cm[w] = m;
+    for (int w = wave; w < Wq; w += 16) {
+        const int p = (w << 6) + lane;
+        const unsigned char sv = (p < q) ? s_st[p] : (unsigned char)ST_NOT;
+        const bool isc = sv == ST_CENTER;
+        const uint64_t m = __ballot(isc);
+        const int c = s_wcnt[w] + lanes_below(m, lane);
+        if (p < q) {
+            st[p] = sv;
+            cn[p] = isc ? c : -1;
+            if (isc) co[c] = ix[p];
+        }
     }
     if (tid == 0) {
-        rep[b].n_centers = total;
+        rep[b].n_centers = s_wcnt[Wq];
         rep[b].rounds = rounds;
     }
 }
@@ -413,7 +471,7 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
         const char* kb = keys + (size_t)sg.base * row_bytes;
         const char* mine = kb + (size_t)tok * row_bytes;
         const double nnp = nnb[tok];
-        int* cand = s_cand[wave];
+        lds_i32* cand = (lds_i32*)s_cand[wave];
         double best = INFINITY;
         int bestj = 0x7FFFFFFF;
         auto tok_of = [&](int j) { return ix[j]; };
@@ -483,7 +541,7 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     double best = INFINITY;
     int bestc = 0x7FFFFFFF;
     if (thr > 0.0 && C > 0) {
-        int* cand = s_cand[wave];
+        lds_i32* cand = (lds_i32*)s_cand[wave];
         auto tok_of = [&](int c) { return co[c]; };
         const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
         const int Wc = (C + 63) >> 6;
@@ -512,14 +570,30 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     if (lane == 0) {
         const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
         cluster_id[sg.base + tok] = cid;
-        if (cid >= 0) {
-            if (cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
-            atomicAdd(&rep[b].n_reincorporated, 1);
-        } else {
-            atomicAdd(&rep[b].n_dropped, 1);
-        }
+        // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
+        //  counter that every wavefront hits would serialise at one L2 address)
+        if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
         if (!(nnp > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
     }
+}
+
+// Stand-alone pact_reincorporate: totals of recovered / dropped tokens (the fused path gets
+// them from the cluster sizes).  grid (B), block 1024.
+__global__ __launch_bounds__(1024) void count_recovered_kernel(Batch bt, pact_report* rep,
+                                                               const int32_t* __restrict__ pruned_idx,
+                                                               const int32_t* __restrict__ cluster_id) {
+    __shared__ int s_tot;
+    const int b = blockIdx.x;
+    const Seg sg = bt.s[b];
+    const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q);
+    if (threadIdx.x == 0) s_tot = 0;
+    __syncthreads();
+    int loc = 0;
+    for (int t = threadIdx.x; t < np; t += 1024) loc += cluster_id[sg.base + pruned_idx[sg.base + t]] >= 0;
+    loc = (int)wave_sum_f64((double)loc);
+    if ((threadIdx.x & 63) == 0 && loc) atomicAdd(&s_tot, loc);
+    __syncthreads();
+    if (threadIdx.x == 0) { rep[b].n_reincorporated = s_tot; rep[b].n_dropped = np - s_tot; }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -539,9 +613,9 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
                     w.rho, rank_opt);
     dim3 gtok((bt.n_max + 3) / 4, bt.B);
-    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
-                w.pcnt);
-    const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) + (size_t)bt.n_max * 2;
+    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds);
+    const size_t qpad = (size_t)((bt.n_max + 63) / 64 * 64);
+    const size_t lds = qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4;
     static size_t raised = 0;
     if (lds > 48 * 1024 && lds > raised) {
         if (hipFuncSetAttribute((const void*)centre_resolve_kernel,
@@ -550,7 +624,7 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         raised = lds;
     }
     PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
-                      w.adj, w.rho, w.preds, w.pcnt, idx, w.status, w.cnum, w.cmask, center_idx);
+                      w.adj, w.rho, w.preds, idx, w.status, w.cnum, w.cmask, center_idx);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
                     w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);
@@ -566,7 +640,7 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
 
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
-                         int32_t* cluster_counts, pact_report* rep, hipStream_t st) {
+                         int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st) {
     int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, st);
     if (rc != PACT_OK) return rc;
     dim3 grid((bt.n_max + 3) / 4, bt.B);
@@ -576,6 +650,9 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
     else
         PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_F32>, grid, dim3(256), st, bt, rep,
                     (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, cluster_id, cluster_counts);
+    if (count_totals)
+        PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
+                    pruned_idx, cluster_id);
     return PACT_OK;
 }
 

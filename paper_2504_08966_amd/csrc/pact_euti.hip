@@ -8,10 +8,10 @@ namespace pact {
 
 // ------------------------------------------------------------------------------------------
 // First kernel of a call.  Three independent jobs share one launch:
-//   blocks [0, nKeyBlocks)            : one wavefront per token: squared key norm (fp64),
+//   blocks [nQ, nQ + nKeyBlocks)      : one wavefront per token: squared key norm (fp64),
 //                                       reciprocal norm (fp32), cleared bitmap row, and the
 //                                       per-token initial state (status, cluster id, counts);
-//   blocks [nKeyBlocks, +QG_CHUNKS)   : Eq. 1 pass 1, column sums of one row chunk of Q.
+//   blocks [0, nQ = QG_CHUNKS or 0)   : Eq. 1 pass 1, column sums of one row chunk of Q.
 // grid (nKeyBlocks + (do_q ? QG_CHUNKS : 0), B), block 256.
 struct PrepArgs {
     const char* keys; int32_t dk; int32_t key_dt_unused;
@@ -28,8 +28,10 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int lane = threadIdx.x & 63;
-    if ((int)blockIdx.x < a.n_key_blocks) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const int n_q_blocks = a.q ? QG_CHUNKS : 0;      // the query chunks come first: they are the longer job
+    if ((int)blockIdx.x >= n_q_blocks) {
+        const int kblk = blockIdx.x - n_q_blocks;
+        if (kblk == 0 && threadIdx.x == 0) {
             a.near_cnt[b] = 0;
             for (int r = 0; r < MAX_ROUNDS; ++r) a.round_new[b * MAX_ROUNDS + r] = 0;
             pact_report* rp = a.rep + b;
@@ -47,7 +49,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
             }
             if (mode == INIT_REINC) { rp->n_reincorporated = 0; rp->n_dropped = 0; }
         }
-        const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+        const int i = kblk * 4 + (threadIdx.x >> 6);
         if (i >= sg.n) return;
         const size_t g = (size_t)sg.base + i;
         const char* row = a.keys + g * (size_t)a.dk * Elem<KDT>::BYTES;
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         return;
     }
     // ---- Eq. 1, pass 1
-    const int chunk = blockIdx.x - a.n_key_blocks;
+    const int chunk = blockIdx.x;
     const int rows_per = (sg.n + QG_CHUNKS - 1) / QG_CHUNKS;
     const int r0 = chunk * rows_per;
     const int r1 = min(sg.n, r0 + rows_per);
@@ -149,9 +151,9 @@ __global__ __launch_bounds__(256) void qglobal_copy_kernel(Batch bt, const char*
 // ------------------------------------------------------------------------------------------
 // Eq. 2, pass 1: one wavefront per token computes |h_i|_2 and the n_q logits
 // k_i^(g(j)) . Qg^(j); the workgroup (SCORE_TOK_PER_WG tokens) then leaves one online-softmax
-// partial (max, sum of exp) per head.  grid (ceil(n_max/8), B), block 512.
+// partial (max, sum of exp) per head.  grid (ceil(n_max/16), B), block 1024.
 template <int HDT, int KDT>
-__global__ __launch_bounds__(512) void score_logits_kernel(Batch bt, const char* __restrict__ hidden, int h,
+__global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char* __restrict__ hidden, int h,
                                                             const char* __restrict__ keys, int n_kv, int d_h,
                                                             int n_q, const double* __restrict__ qg,
                                                             double* __restrict__ logits,
@@ -229,6 +231,37 @@ __global__ __launch_bounds__(512) void score_logits_kernel(Batch bt, const char*
     }
 }
 
+// (max, normaliser) of one head from the workgroup partials, by one wavefront: every lane
+// loads its (max, sum) pairs 8 at a time, then the usual two-step combine.
+__device__ __forceinline__ void combine_softmax_partials(const double* part, int nwg, int stride, int lane,
+                                                         double& M, double& Z) {
+    double m = -INFINITY;
+    for (int w0 = lane; w0 < nwg; w0 += 512) {
+        double2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int w = w0 + 64 * u;
+            v[u] = (w < nwg) ? *(const double2*)(part + (size_t)w * stride) : make_double2(-INFINITY, 0.0);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m = fmax(m, v[u].x);
+    }
+    m = wave_max_f64(m);
+    double z = 0.0;
+    for (int w0 = lane; w0 < nwg; w0 += 512) {
+        double2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int w = w0 + 64 * u;
+            v[u] = (w < nwg) ? *(const double2*)(part + (size_t)w * stride) : make_double2(-INFINITY, 0.0);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) z += (v[u].y != 0.0) ? v[u].y * exp(v[u].x - m) : 0.0;
+    }
+    M = m;
+    Z = wave_sum_f64(z);
+}
+
 // ------------------------------------------------------------------------------------------
 // Eq. 2, pass 2 on its own (stand-alone pact_score): combine the partials into (max,
 // normaliser) per head, then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
@@ -247,14 +280,8 @@ __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
     const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     const int nwg = (sg.n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     for (int j = wave; j < n_q; j += 4) {
-        const double* part = sm_part + ((size_t)b * smwg * n_q + j) * 2;
-        double m = -INFINITY;
-        for (int w = lane; w < nwg; w += 64) m = fmax(m, part[(size_t)w * n_q * 2]);
-        m = wave_max_f64(m);
-        double z = 0.0;
-        for (int w = lane; w < nwg; w += 64)
-            z += part[(size_t)w * n_q * 2 + 1] * exp(part[(size_t)w * n_q * 2] - m);
-        z = wave_sum_f64(z);
+        double m, z;
+        combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
         if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
     }
     __syncthreads();
@@ -304,14 +331,8 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
         const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
         const int nwg = (n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
         for (int j = wave; j < n_q; j += 16) {
-            const double* part = sm_part + ((size_t)b * smwg * n_q + j) * 2;
-            double m = -INFINITY;
-            for (int w = lane; w < nwg; w += 64) m = fmax(m, part[(size_t)w * n_q * 2]);
-            m = wave_max_f64(m);
-            double z = 0.0;
-            for (int w = lane; w < nwg; w += 64)
-                z += part[(size_t)w * n_q * 2 + 1] * exp(part[(size_t)w * n_q * 2] - m);
-            z = wave_sum_f64(z);
+            double m, z;
+            combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
             if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
         }
         __syncthreads();
@@ -432,11 +453,11 @@ template <int HDT>
 static int launch_logits_k(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
     dim3 grid((bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
     if (in.k_dt == PACT_BF16)
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt,
+        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_BF16>), grid, dim3(1024), st, bt,
                     (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
                     w.qg, w.logits, w.hnorm, w.sm_part);
     else
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt,
+        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_F32>), grid, dim3(1024), st, bt,
                     (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
                     w.qg, w.logits, w.hnorm, w.sm_part);
     return PACT_OK;

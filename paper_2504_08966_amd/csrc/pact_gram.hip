@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const size_t row_bytes = (size_t)ga.dk * Elem<DT>::BYTES;
     const int nSlices = (int)((row_bytes + KSLICE_BYTES - 1) / KSLICE_BYTES);
     const int row_bytes_i = (int)row_bytes;                   // a row's tail slice is zero-filled
-    const char* keys = ga.keys + (size_t)sg.base * row_bytes;
+    const char* __restrict__ keys = ga.keys + (size_t)sg.base * row_bytes;
     const int32_t* idxR = ga.idx_rows + sg.base;
     const int32_t* idxC = ga.idx_cols + sg.base;
     const float* rinv = ga.rinv + sg.base;
@@ -97,18 +97,32 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int ld_row = tid >> 3;
     const int ld_chunk = tid & 7;
 
-    for (int tile = blockIdx.x; tile < nTiles; tile += gridDim.x) {
-        const int tr = tile / tilesC, tc = tile % tilesC;
+    // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (XCD = workgroup id mod 8) and
+    // every XCD has its own L2, so each XCD works on its own band of tile columns: its key rows
+    // for those columns stay in its L2 while the row tiles stream through.
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int nslot = (gridDim.x + 7 - xcd) >> 3;      // workgroups of this launch on this XCD
+    const bool banded = tilesC >= 8 && (gridDim.x & 7) == 0;
+    const int c_lo = banded ? (int)((long)xcd * tilesC / 8) : 0;
+    const int bw = banded ? (int)((long)(xcd + 1) * tilesC / 8) - c_lo : tilesC;
+    const int myTiles = banded ? tilesR * bw : nTiles;
+    const int t_first = banded ? slot : (int)blockIdx.x;
+    const int t_step = banded ? nslot : (int)gridDim.x;
+
+    for (int tl = t_first; tl < myTiles; tl += t_step) {
+        const int tr = tl / bw, tc = c_lo + tl % bw;
         const int rowBase = tr * TILE, colBase = tc * TILE;
 
-        const char* pa[4];
-        const char* pb[4];
+        // Rows past the end are clamped to the last valid row: their products are discarded in
+        // the epilogue (row terms via sRow, columns via the column mask), so no zero fill.
+        uint32_t oa[4], ob[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int r = ld_row + 32 * u;
-            const int ra = rowBase + r, rb = colBase + r;
-            pa[u] = (ra < nA) ? keys + (size_t)idxR[ra] * row_bytes + ld_chunk * 16 : nullptr;
-            pb[u] = (rb < nB) ? keys + (size_t)idxC[rb] * row_bytes + ld_chunk * 16 : nullptr;
+            const int ra = min(rowBase + r, nA - 1), rb = min(colBase + r, nB - 1);
+            oa[u] = (uint32_t)idxR[ra] * (uint32_t)row_bytes_i + ld_chunk * 16;
+            ob[u] = (uint32_t)idxC[rb] * (uint32_t)row_bytes_i + ld_chunk * 16;
         }
         if (tid < TILE) {
             const int ra = rowBase + tid;
@@ -132,12 +146,16 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
         uint4 ra_[4], rb_[4];
-        const uint4 zero4 = make_uint4(0, 0, 0, 0);
-        const bool in0 = ld_chunk * 16 < row_bytes_i;
+        {
+            // the key width need not fill the last 128-byte slice: chunks past it count as zero
+            const bool in0 = ld_chunk * 16 < row_bytes_i;
+            const uint32_t back = in0 ? 0u : (uint32_t)(ld_chunk * 16);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            ra_[u] = (pa[u] && in0) ? *(const uint4*)(pa[u]) : zero4;
-            rb_[u] = (pb[u] && in0) ? *(const uint4*)(pb[u]) : zero4;
+            for (int u = 0; u < 4; ++u) {
+                ra_[u] = *(const uint4*)(keys + (oa[u] - back));
+                rb_[u] = *(const uint4*)(keys + (ob[u] - back));
+                if (!in0) { ra_[u] = make_uint4(0, 0, 0, 0); rb_[u] = make_uint4(0, 0, 0, 0); }
+            }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -152,10 +170,13 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(Batch bt, GramArgs ga) {
             if (ks + 1 < nSlices) {
                 const int off = (ks + 1) * KSLICE_BYTES;
                 const bool in1 = off + ld_chunk * 16 < row_bytes_i;
+                const uint32_t o1 = in1 ? (uint32_t)off : 0u;
+                const uint32_t back = in1 ? 0u : (uint32_t)(ld_chunk * 16);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    ra_[u] = (pa[u] && in1) ? *(const uint4*)(pa[u] + off) : zero4;
-                    rb_[u] = (pb[u] && in1) ? *(const uint4*)(pb[u] + off) : zero4;
+                    ra_[u] = *(const uint4*)(keys + (oa[u] + o1 - back));
+                    rb_[u] = *(const uint4*)(keys + (ob[u] + o1 - back));
+                    if (!in1) { ra_[u] = make_uint4(0, 0, 0, 0); rb_[u] = make_uint4(0, 0, 0, 0); }
                 }
             }
 #pragma unroll
@@ -237,16 +258,27 @@ __global__ __launch_bounds__(256, 2) void gram_kernel(Batch bt, GramArgs ga) {
                     const uint64_t s1 = ((mSure[0] >> 32) | (mSure[1] & 0xFFFFFFFF00000000ull));
                     const uint64_t n0 = w0 & ~s0, n1 = w1 & ~s1;
                     if ((n0 | n1) != 0) {
+                        // one atomic per wavefront reserves the slots of all its near pairs
                         const uint64_t mine = hh ? n1 : n0;
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            if ((mine >> (j * 32 + l32)) & 1ull) {
-                                const int slot = atomicAdd(&ga.near_cnt[b], 1);
-                                if (slot < NEAR_CAP) {
-                                    uint32_t* e = ga.near_list + ((size_t)b * NEAR_CAP + slot) * 2;
-                                    e[0] = (uint32_t)rowP;
-                                    e[1] = (uint32_t)colP[j];
-                                }
+                        const bool f0 = (mine >> l32) & 1ull, f1 = (mine >> (32 + l32)) & 1ull;
+                        const uint64_t b0 = __ballot(f0), b1 = __ballot(f1);
+                        const int total = __popcll(b0) + __popcll(b1);
+                        int base_slot = 0;
+                        if (lane == 0) base_slot = atomicAdd(&ga.near_cnt[b], total);
+                        base_slot = __shfl(base_slot, 0, 64);
+                        const uint64_t below = (1ull << lane) - 1ull;
+                        if (f0) {
+                            const int slot = base_slot + __popcll(b0 & below);
+                            if (slot < NEAR_CAP) {
+                                uint32_t* e = ga.near_list + ((size_t)b * NEAR_CAP + slot) * 2;
+                                e[0] = (uint32_t)rowP; e[1] = (uint32_t)colP[0];
+                            }
+                        }
+                        if (f1) {
+                            const int slot = base_slot + __popcll(b0) + __popcll(b1 & below);
+                            if (slot < NEAR_CAP) {
+                                uint32_t* e = ga.near_list + ((size_t)b * NEAR_CAP + slot) * 2;
+                                e[0] = (uint32_t)rowP; e[1] = (uint32_t)colP[1];
                             }
                         }
                     }
@@ -276,6 +308,7 @@ static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hip
     int grid_x = tiles1 * tiles1;
     const int cap = (bt.B >= 8) ? 128 : 512;      // two workgroups per CU resident, 256 CUs
     if (grid_x > cap) grid_x = cap;
+    if (grid_x >= 8) grid_x &= ~7;                // a multiple of the 8 XCDs (see the tile order)
     dim3 grid(grid_x, bt.B);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH(name, (gram_kernel<PACT_BF16, MODE>), grid, dim3(256), st, bt, ga);

@@ -30,9 +30,9 @@ struct Batch {
 
 // ---------------------------------------------------------------------------------------
 // Workspace layout.  Offsets in bytes from the 256-aligned workspace base.
-constexpr int QG_CHUNKS = 128;        // row chunks of the global-query column sum
-constexpr int SCORE_TOK_PER_WG = 8;   // tokens (= wavefronts) per workgroup in the logits kernel
-constexpr int PRED_CAP = 64;          // preceding neighbours listed per kept token (16-bit positions)
+constexpr int QG_CHUNKS = 512;        // row chunks of the global-query column sum
+constexpr int SCORE_TOK_PER_WG = 16;  // tokens (= wavefronts) per workgroup in the logits kernel
+constexpr int PRED_CAP = 64;          // 16-bit slots per kept token: slot 0 = count, then up to 63 preceding neighbours
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
 constexpr int MAX_ROUNDS = 8;         // parallel centre rounds launched before the finishing kernel
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
@@ -158,7 +158,7 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
                    hipStream_t st);
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
-                         int32_t* cluster_counts, pact_report* rep, hipStream_t st);
+                         int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st);
 int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
                  const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
@@ -177,6 +177,12 @@ inline double cos_margin(int dk) { return (double)(dk + 16) * (1.0 / 8388608.0) 
 // Device helpers
 #ifdef __HIPCC__
 namespace pact {
+
+// LDS-qualified pointer types: accesses through them compile to ds_* instructions even when
+// the pointer travels through function arguments (a generic pointer would give flat_*).
+typedef __attribute__((address_space(3))) volatile unsigned char lds_vu8;
+typedef __attribute__((address_space(3))) int lds_i32;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;

@@ -12,9 +12,10 @@ namespace pact {
 // and the fill with LDS cursors.  grid (B), block 1024, dynamic LDS n_max * 4 bytes.
 // offsets of sample b live at [base + b, base + b + C].
 __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t* __restrict__ cluster_id,
-                                                         const pact_report* __restrict__ rep,
+                                                         pact_report* rep,
                                                          int32_t* cluster_counts, int recount,
-                                                         int32_t* offsets, int32_t* members) {
+                                                         int write_totals, int32_t* offsets,
+                                                         int32_t* members) {
     extern __shared__ int s_cur[];          // [C]: sizes, then running fill cursors
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
@@ -57,7 +58,14 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
         s_cur[c] = run;                     // cursor starts at the segment's offset
         run += sz;
     }
-    if (c1 == C && c0 < C) off[C] = run;
+    if (c1 == C && c0 < C) {
+        off[C] = run;                        // run = all cluster members = kept + recovered
+        if (write_totals) {
+            const int q = clamp_count(rep[b].n_kept, sg.n);
+            rep[b].n_reincorporated = run - q;
+            rep[b].n_dropped = sg.n - run;
+        }
+    }
     if (C == 0 && tid == 0) off[0] = 0;
     __syncthreads();
     int32_t* mem = members + sg.base;
@@ -204,8 +212,9 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
             return PACT_ERR_HIP;
         raised = lds;
     }
-    PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id, rep,
-                      cluster_counts, recount ? 1 : 0, w.offsets, w.members);
+    PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id,
+                      const_cast<pact_report*>(rep), cluster_counts, recount ? 1 : 0, recount ? 0 : 1,
+                      w.offsets, w.members);
     if (h_dt == PACT_BF16)
         return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
                                          cluster_counts, st);
