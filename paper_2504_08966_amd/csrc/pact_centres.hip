@@ -84,7 +84,7 @@ __device__ __forceinline__ void nearest_candidate(const lds_i32* cand, int ncand
 // After the density Gram pass, two independent jobs in one launch:
 //   blocks [0, REFINE_BLOCKS): the pairs the epilogue could not decide in fp32 - evaluate
 //       Eq. 5 in fp64 and clear the bit if the distance exceeds d_c (one wavefront per pair);
-//   the other blocks: Eq. 6 completed, rho_p = sum over the 64-row blocks of the column
+//   the other blocks: Eq. 6 completed, rho_p = sum over the row blocks of the column
 //       partials (64 tokens x 4 slices per block).  With d_n = 2 every term is an fp32 value
 //       in [e^-1, 1], so these fp64 additions are exact whatever their order.
 constexpr int REFINE_BLOCKS = 256;
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
     const int p0 = (blockIdx.x - REFINE_BLOCKS) * 64;
     if (p0 >= q) return;
     const int p = p0 + lane;
-    const int nrt = (q + 63) >> 6;
+    const int nrt = (q + GRAM_RHO_ROWS - 1) / GRAM_RHO_ROWS;
     double acc = 0.0;
     if (p < q) {
         const double* in = rho_part + (size_t)b * bt.W * bt.n_max + p;

@@ -19,7 +19,7 @@ struct PrepArgs {
     double* nn; float* rinv; uint64_t* adj; double* qg_part;
     uint32_t* status; int32_t* ident; int32_t* near_cnt; int32_t* round_new;
     pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
-    const int32_t* n_idx_dev;
+    const int32_t* n_idx_dev; uint32_t* zeros;
     int32_t mode; int32_t n_key_blocks;
 };
 
@@ -31,6 +31,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     const int n_q_blocks = a.q ? QG_CHUNKS : 0;      // the query chunks come first: they are the longer job
     if ((int)blockIdx.x >= n_q_blocks) {
         const int kblk = blockIdx.x - n_q_blocks;
+        if (kblk == 0 && b == 0 && threadIdx.x < 64) a.zeros[threadIdx.x] = 0u;
         if (kblk == 0 && threadIdx.x == 0) {
             a.near_cnt[b] = 0;
             for (int r = 0; r < MAX_ROUNDS; ++r) a.round_new[b * MAX_ROUNDS + r] = 0;
@@ -443,6 +444,7 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
     a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
     a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt; a.round_new = w.round_new;
     a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
+    a.zeros = w.zeros;
     a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;
     dim3 grid(a.n_key_blocks + (q ? QG_CHUNKS : 0), bt.B);
     return (k_dt == PACT_BF16) ? launch_prep_q<PACT_BF16>(bt, a, q_dt, grid, st)

@@ -33,6 +33,7 @@ struct Batch {
 constexpr int QG_CHUNKS = 512;        // row chunks of the global-query column sum
 constexpr int SCORE_TOK_PER_WG = 16;  // tokens (= wavefronts) per workgroup in the logits kernel
 constexpr int PRED_CAP = 64;          // 16-bit slots per kept token: slot 0 = count, then up to 63 preceding neighbours
+constexpr int GRAM_RHO_ROWS = 128;    // kept rows summed into one row of the density partials
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
 constexpr int MAX_ROUNDS = 8;         // parallel centre rounds launched before the finishing kernel
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
@@ -47,6 +48,7 @@ struct WsLayout {
     size_t preds, pcnt;                                // [B][n_max][PRED_CAP] u16, [B][n_max] i32
     size_t near_list, near_cnt, round_new;             // refine list, counters
     size_t cursor, offsets, members;                   // merge CSR (global row index)
+    size_t zeros;                                      // 256 zero bytes
     size_t total;
 };
 
@@ -81,6 +83,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.cursor = take(sizeof(int32_t) * total);
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
+    L.zeros = take(256);
     L.total = off;
     return L;
 }
@@ -91,7 +94,7 @@ struct Ws {
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; int32_t* pcnt; uint32_t* near_list; int32_t* near_cnt; int32_t* round_new;
-    int32_t* cursor; int32_t* offsets; int32_t* members;
+    int32_t* cursor; int32_t* offsets; int32_t* members; uint32_t* zeros;
 };
 
 inline Ws resolve(void* base, const WsLayout& L) {
@@ -108,7 +111,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
     w.near_cnt = (int32_t*)(p + L.near_cnt); w.round_new = (int32_t*)(p + L.round_new);
     w.cursor = (int32_t*)(p + L.cursor); w.offsets = (int32_t*)(p + L.offsets);
-    w.members = (int32_t*)(p + L.members);
+    w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
     return w;
 }
 
