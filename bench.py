@@ -45,6 +45,22 @@ def algorithmic_work(kernel: str, n, h, dk, q, C, n_reinc, key_bytes, hid_bytes,
     return None, 0.0, ""
 
 
+def measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` (read + write) from the committed rocprofv3 --pmc summary:
+    its table rows are `| kernel | fetch bytes | write bytes | ... |`; None when there is no row."""
+    path = os.path.join(ROOT, "profiles", "pact_reduce_img7b_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        cells = [c.strip() for c in ln.strip().strip("|").split("|")]
+        if len(cells) >= 3 and cells[0] == kernel:
+            try:
+                return float(cells[1]) + float(cells[2])
+            except ValueError:
+                return None
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +69,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print per-kernel averages to stderr")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also launch the library's plain copy kernel once over this many MiB "
+                         "(a dispatch of known HBM traffic for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (samples are independent; "
@@ -86,6 +105,14 @@ def main():
 
     def step():
         P.pact_reduce(hidden, keys, keys, q, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws, out=out)
+
+    if args.calibration_copy_mib > 0:
+        src = torch.full((args.calibration_copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        P.pact_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -132,10 +159,7 @@ def main():
             ach, peak, u = work / sec / 1e12, PEAK_MFMA_TFLOPS["bf16"], "TFLOP/s"
         else:
             ach, peak, u = work / sec / 1e9, PEAK_HBM_GBS, "GB/s"
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "traffic.json")
-        if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get(k)
+        traffic = measured_traffic(k)
         roof = {"kernel": k, "bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": u,
                 "frac": round(ach / peak, 4), "traffic": traffic, "us_per_launch": round(sec * 1e6, 2),
                 "work_per_launch": work, "work_unit": unit,

@@ -204,6 +204,12 @@ int pact_profile_enable(int on);
 int pact_profile_reset(void);
 int pact_profile_read(const char** names, float* ms, int32_t max_records);
 
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; src and dst 16-byte aligned,
+ * not overlapping) by one kernel named pact::calibration_copy_kernel: it reads and writes
+ * exactly `bytes` bytes, which gives hardware byte counters (rocprofv3's FETCH_SIZE and
+ * WRITE_SIZE) a dispatch of known traffic to be scaled by.  Benchmarks only. */
+int pact_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 const char* pact_strerror(int status);
 
 #ifdef __cplusplus

@@ -76,6 +76,8 @@ def load_library():
     lib.pact_reduce_varlen.argtypes = [vp, C.c_int, i32, vp, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
                                        C.POINTER(i32), i32, C.POINTER(_Params), vp, vp, vp, vp, vp, vp,
                                        C.c_int, vp, vp, vp, sz, vp]
+    lib.pact_calibration_copy.restype = C.c_int
+    lib.pact_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.pact_profile_enable.restype = C.c_int
     lib.pact_profile_enable.argtypes = [C.c_int]
     lib.pact_profile_reset.restype = C.c_int
@@ -241,6 +243,13 @@ def pact_reduce_varlen(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int,
         _p(o["center_idx"]), _p(o["cluster_id"]), _p(o["merged"]), _out_dt(o["merged"].dtype),
         _p(o["cluster_counts"]), _p(o["rep"]), _p(ws), ws.numel(), _stream()), "pact_reduce_varlen")
     return o
+
+
+def pact_calibration_copy(dst, src):
+    """Copy src into dst (same byte size) with the library's plain copy kernel."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load_library().pact_calibration_copy(_p(dst), _p(src), nbytes, _stream()), "pact_calibration_copy")
 
 
 def pact_profile_enable(on: bool):

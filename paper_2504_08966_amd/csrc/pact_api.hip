@@ -1,5 +1,6 @@
 // C ABI of libpact: argument validation (host-only, before anything touches the GPU),
 // workspace partitioning, stage sequencing.  Nothing here allocates or synchronises.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <vector>
@@ -106,6 +107,13 @@ static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStrea
                                    io.cluster_id, io.cluster_counts, io.rep, false, st))) return rc;
     return launch_merge(bt, w, io.hidden, io.h_dt, io.h, io.cluster_id, io.center_idx, io.rep, io.merged,
                         io.out_dt, io.cluster_counts, false, st);
+}
+
+// Grid-stride copy of 16-byte words: the dispatch of known traffic behind pact_calibration_copy.
+__global__ void __launch_bounds__(256) calibration_copy_kernel(uint4* __restrict__ dst,
+                                                                const uint4* __restrict__ src, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
 }  // namespace pact
@@ -351,6 +359,19 @@ int pact_profile_read(const char** names, float* ms, int32_t max_records) {
         if (ms) ms[n] = t;
     }
     return n;
+}
+
+int pact_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src) return PACT_ERR_NULL;
+    if (bytes == 0 || bytes % 16 || bytes > (size_t(1) << 34)) return PACT_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15) return PACT_ERR_ALIGN;
+    int rc;
+    if ((rc = check_device())) return rc;
+    const size_t n16 = bytes / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(pact::calibration_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       (uint4*)dst, (const uint4*)src, n16);
+    return hipGetLastError() == hipSuccess ? PACT_OK : PACT_ERR_HIP;
 }
 
 const char* pact_strerror(int status) {
