@@ -8,16 +8,18 @@
 // The distance matrix itself is never written.
 //
 // Shape of the kernel (gfx950):
-//  * one workgroup of 8 wavefronts per CU owns a 256x256 output tile (L2 traffic per flop is
-//    half that of 128x128 tiles, and the L2 -> CU path is what limits this contraction at a
-//    key width of 512); each wavefront computes 128x64 of it as 4x2 v_mfma_f32_32x32x16_bf16
-//    (or 32x32x2_f32) accumulators;
-//  * the key rows stream in 64-byte slices straight from global memory into a ring of LDS
-//    stages (global_load_lds_dwordx4: no staging registers), three slices ahead of the MFMAs;
-//    waits on the ring are explicit (s_waitcnt vmcnt + s_barrier);
+//  * one workgroup of 8 wavefronts per CU owns a (64*MI) x 256 output tile, MI = 4 or 2: 256x256
+//    halves the L2 traffic per flop of 128x128 tiles (the L2 -> CU path is what limits this
+//    contraction at a key width of 512), 128x256 is for launches that would otherwise leave
+//    CUs without a tile; each wavefront computes (32*MI) x 64 of it as MI x 2
+//    v_mfma_f32_32x32x16_bf16 (or 32x32x2_f32) accumulators;
+//  * the key rows stream in 128-byte slices (whole cache lines: eight lanes fetch one row's
+//    line) straight from global memory into a ring of LDS stages (global_load_lds_dwordx4: no
+//    staging registers); waits on the ring are explicit (s_waitcnt vmcnt + s_barrier);
 //  * both operands are rows of the same key matrix, so a lane takes 16 contiguous bytes of
-//    "its" row per MFMA; the four 16-byte chunks of a row slice are XOR-swizzled by the row
-//    number so that 16 consecutive rows read conflict-free;
+//    "its" row per MFMA; the eight 16-byte chunks of a row slice are XOR-swizzled by the row
+//    number so that 16 consecutive rows read conflict-free; the fragments of the next k-group
+//    are read from LDS while the MFMAs of the current one run;
 //  * the grid is persistent (the tile count depends on counts only the device knows) and
 //    XCD-aware: each of the 8 XCDs (own L2) works on its own band of tile columns.
 #include <type_traits>
@@ -25,6 +27,17 @@
 #include "pact_internal.h"
 
 namespace pact {
+
+// Optional in-kernel phase clock (build with -DPACT_GRAM_STAMPS): thread 0 of every workgroup
+// of sample 0 records the 100 MHz wall clock at five points of its last tile (and the shader
+// clock counter around the slice loop, slots 5 and 6).
+#ifdef PACT_GRAM_STAMPS
+__device__ unsigned long long g_gram_stamps[2][512][8];
+#define PACT_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.y == 0) { g_gram_stamps[MODE][blockIdx.x][k] = wall_clock64(); \
+        if ((k) == 1 || (k) == 2) g_gram_stamps[MODE][blockIdx.x][4 + (k)] = clock64(); } } while (0)
+#else
+#define PACT_STAMP(k) do { } while (0)
+#endif
 
 enum { MODE_DENSITY = 0, MODE_CAND = 1 };
 
@@ -43,17 +56,26 @@ struct GramArgs {
     float margin;              // worst-case fp32 error of a cosine
 };
 
-constexpr int TILE = 256;
-constexpr int SLICE_BYTES = 64;            // bytes of each row per stage: 4 chunks of 16 B
-constexpr int NSTAGE = 4;                  // LDS ring: 3 slices in flight + 1 being multiplied
-constexpr int AHEAD = NSTAGE - 1;
-constexpr int STAGE_BYTES = 2 * TILE * SLICE_BYTES;   // A rows then B rows: 32 KB
+constexpr int TILE_C = 256;
+constexpr int SLICE_BYTES = 128;           // bytes of each row per stage: 8 chunks of 16 B = one cache line
+constexpr int LDS_BUDGET = 160 * 1024 - 4096;
+
+template <int MI> struct Shape {
+    static constexpr int TILE_R = 64 * MI;                              // 2 wavefront rows x MI x 32
+    static constexpr int STAGE_BYTES = (TILE_R + TILE_C) * SLICE_BYTES; // A rows then B rows
+    static constexpr int NSTAGE = (LDS_BUDGET / STAGE_BYTES) < 4 ? (LDS_BUDGET / STAGE_BYTES) : 4;
+    static constexpr int AHEAD = NSTAGE - 1;                            // slices in flight besides the one being multiplied
+    static constexpr int NB = (TILE_R + TILE_C) / 64;                   // 1 KB blocks (8 rows) each wavefront brings per stage
+    static constexpr size_t LDS_BYTES = (size_t)NSTAGE * STAGE_BYTES + TILE_R * sizeof(float) + 4 * 64 * sizeof(double);
+    static_assert(NSTAGE >= 2, "the ring needs a slot to fill while another is multiplied");
+};
 
 typedef __attribute__((address_space(3))) char lds_char;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) u32x2_t lds_uint2;
+typedef __attribute__((address_space(3))) double lds_f64;
 constexpr int NEAR_BUF = 512;              // undecided pairs a wavefront buffers before reserving list slots
 
 // 16 bytes per lane, global -> LDS at (lds_base + lane * 16); asynchronous, counted by vmcnt.
@@ -63,6 +85,20 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
 }
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// v = value in lane `l` of a wavefront-wide register (value and lane are wave-uniform)
+// (the compiler cannot see into the asm to pad the distance a VALU-written scalar needs before
+// another VALU instruction reads it, hence the s_nop)
+template <int L> __device__ __forceinline__ void write_lane(uint32_t& v, uint32_t value) {
+    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(value), "n"(L));
+}
+// body(std::integral_constant<int, 0>{}) ... body(std::integral_constant<int, N-1>{})
+template <int N, int I = 0, class F> __device__ __forceinline__ void static_for(F&& body) {
+    if constexpr (I < N) {
+        body(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(body);
+    }
 }
 
 template <int DT> struct Mfma;
@@ -81,9 +117,12 @@ template <> struct Mfma<PACT_F32> {
     }
 };
 
-template <int DT, int MODE>
+template <int DT, int MODE, int MI>
 __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
-    extern __shared__ uint4 s_ring[];                         // NSTAGE x 32 KB, then 256 floats
+    typedef Shape<MI> SH;
+    constexpr int TILE_R = SH::TILE_R, STAGE_BYTES = SH::STAGE_BYTES, NSTAGE = SH::NSTAGE;
+    constexpr int AHEAD = SH::AHEAD, NB = SH::NB, WROWS = 32 * MI;
+    extern __shared__ uint4 s_ring[];                         // NSTAGE stages, TILE_R floats, 256 doubles
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q_kept = clamp_count(ga.rep[b].n_kept, sg.n);
@@ -91,18 +130,20 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_centers, q_kept);
     const int row_off = (MODE == MODE_DENSITY) ? 0 : q_kept;   // candidate rows follow the kept rows
     if (nA <= 0 || nB <= 0) return;
-    const int tilesR = (nA + TILE - 1) / TILE;
-    const int tilesC = (nB + TILE - 1) / TILE;
+    PACT_STAMP(0);
+    const int tilesR = (nA + TILE_R - 1) / TILE_R;
+    const int tilesC = (nB + TILE_C - 1) / TILE_C;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
-    const int wr = wave >> 2, wc = wave & 3;                      // 2 x 4 wavefronts of 128 x 64
+    const int wr = wave >> 2, wc = wave & 3;                      // 2 x 4 wavefronts of WROWS x 64
     const int l32_ = lane & 31, hh_ = lane >> 5;
 
     lds_char* ring = (lds_char*)s_ring;
     const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
-    float* sRinv = (float*)((char*)s_ring + NSTAGE * STAGE_BYTES);   // [TILE]
+    float* sRinv = (float*)((char*)s_ring + NSTAGE * STAGE_BYTES);   // [TILE_R]
+    lds_f64* sRho = (lds_f64*)(ring + NSTAGE * STAGE_BYTES + TILE_R * sizeof(float));   // [4][64]
 
     const int row_bytes = ga.dk * Elem<DT>::BYTES;
     const int nSlices = (row_bytes + SLICE_BYTES - 1) / SLICE_BYTES;
@@ -118,13 +159,16 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const float t_lo = (MODE == MODE_DENSITY) ? -(sg.d_c + ga.margin) * a_ : thr_cos - ga.margin;
     const float t_hi = -(sg.d_c - ga.margin) * a_;
 
-    // DMA roles: a stage is 32 blocks of 1 KB (16 rows x 4 chunks); wavefronts 0-3 bring the
-    // A rows, 4-7 the B rows, 4 blocks each.  Lane l of a block: row 16*blk + l/4, physical
-    // chunk l&3, which holds logical chunk (l&3) ^ ((row >> 2) & 3).
-    const int dma_is_b = wave >> 2;
-    const int dma_row0 = (wave & 3) * 64 + (lane >> 2);       // + 16 * k, k = 0..3
-    const int dma_chunk = (lane & 3) ^ ((lane >> 4) & 3);     // logical chunk this lane fetches
-    const uint32_t dma_lds0 = ring_base + (uint32_t)(dma_is_b * TILE * SLICE_BYTES + (wave & 3) * 4096);
+    // DMA roles: a stage is (TILE_R + 256) / 8 blocks of 1 KB (8 rows x 8 chunks), the A rows
+    // first; wavefront w brings blocks w*NB .. w*NB+NB-1.  Lane l of a block: row 8*blk + l/8,
+    // physical chunk l&7, which holds logical chunk (l&7) ^ ((row >> 1) & 7).
+    const int dma_row0 = wave * NB * 8 + (lane >> 3);          // stage row of block k: + 8 * k
+    const uint32_t dma_lds0 = ring_base + (uint32_t)(wave * NB * 1024);
+
+    // fragment addressing: lane (l32, hh) reads chunk 2g+hh of row (its wave's row block) + l32
+    const int swz = (l32_ >> 1) & 7;
+    const uint32_t fragA0 = (uint32_t)((wr * WROWS + l32_) * SLICE_BYTES);
+    const uint32_t fragB0 = (uint32_t)((TILE_R + wc * 64 + l32_) * SLICE_BYTES);
 
     // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (XCD = workgroup id mod 8) and
     // every XCD has its own L2, so each XCD works on its own band of tile columns: its key rows
@@ -138,36 +182,42 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int t_step = banded ? (int)(gridDim.x >> 3) : (int)gridDim.x;
 
     for (int tl = t_first; tl < myTiles; tl += t_step) {
-        const int rowBase = (tl / bw) * TILE, colBase = (c_lo + tl % bw) * TILE;
+        const int rowBase = (tl / bw) * TILE_R, colBase = (c_lo + tl % bw) * TILE_C;
 
-        // byte offsets of this lane's 4 DMA rows; rows past the end are clamped to the last one
+        // byte offsets of this lane's NB DMA rows; rows past the end are clamped to the last one
         // (their products are discarded in the epilogue)
-        uint32_t ro[4];
+        uint32_t ro[NB];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int r = dma_row0 + 16 * k;
-            const int tok = dma_is_b ? idxC[min(colBase + r, nB - 1)] : idxR[min(rowBase + r, nA - 1)];
+        for (int k = 0; k < NB; ++k) {
+            const int r = dma_row0 + 8 * k;
+            const int tok = (r >= TILE_R) ? idxC[min(colBase + r - TILE_R, nB - 1)] : idxR[min(rowBase + r, nA - 1)];
             ro[k] = (uint32_t)tok * (uint32_t)row_bytes;
         }
-        if (tid < TILE) sRinv[tid] = rinv[idxR[min(rowBase + tid, nA - 1)]];
+        // logical chunk this lane fetches: the swizzle term depends on the row only through
+        // (row >> 1) & 7 = (lane >> 4) & 3 plus 4 * (k & 1)  (rows advance by 8 per block)
+        if (tid < TILE_R) sRinv[tid] = rinv[idxR[min(rowBase + tid, nA - 1)]];
         float rj_pre[2];                                    // 1/|u_j| of this lane's two columns (used in the epilogue)
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
 
-        auto issue = [&](int s) __attribute__((always_inline)) {      // slice s -> ring slot s % NSTAGE
-            const int byte0 = s * SLICE_BYTES + dma_chunk * 16;
-            const bool ok = byte0 < row_bytes;                         // past the key width: zeros
+        auto issue_block = [&](int s, int k) __attribute__((always_inline)) {   // block k of slice s -> ring slot s % NSTAGE
             const uint32_t slot = dma_lds0 + (uint32_t)((s % NSTAGE) * STAGE_BYTES);
+            const int r = dma_row0 + 8 * k;
+            const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+            const int byte0 = s * SLICE_BYTES + chunk * 16;
+            const bool ok = byte0 < row_bytes;                         // past the key width: zeros
+            const char* src = ok ? keys + (ro[k] + (uint32_t)byte0) : ga.zeros;
+            dma16(src, slot + k * 1024);
+        };
+        auto issue = [&](int s) __attribute__((always_inline)) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const char* src = ok ? keys + (ro[k] + (uint32_t)byte0) : ga.zeros;
-                dma16(src, slot + k * 1024);
-            }
+            for (int k = 0; k < NB; ++k) issue_block(s, k);
         };
 
-        f32x16_t acc[4][2];
+        PACT_STAMP(1);
+        f32x16_t acc[MI][2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -179,36 +229,50 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 
         for (int s = 0; s < nSlices; ++s) {
             // slice s has landed once at most the younger slices' loads are outstanding
-            if (s + AHEAD - 1 < nSlices) wait_vmcnt<4 * (AHEAD - 1)>();
+            if (s + AHEAD - 1 < nSlices) wait_vmcnt<NB * (AHEAD - 1)>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();      // ... for every wavefront; and slot (s-1)%NSTAGE is free
             if (s + AHEAD < nSlices) issue(s + AHEAD);
 
-            const lds_char* stA = ring + (s % NSTAGE) * STAGE_BYTES;
-            const lds_char* stB = stA + TILE * SLICE_BYTES;
+            // the fragments of k-group g+1 are read from LDS while the MFMAs of group g run
+            const lds_char* st = ring + (s % NSTAGE) * STAGE_BYTES;
+            u32x4_t fa[2][MI], fb[2][2];
+            auto load_frags = [&](int g, int buf) __attribute__((always_inline)) {
+                const uint32_t co = (uint32_t)(((2 * g + hh_) ^ swz) << 4);
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {
-                const int chunk = 2 * g + hh_;
-                u32x4_t fa[4], fb[2];
+                for (int i = 0; i < MI; ++i) fa[buf][i] = *(const lds_u32x4*)(st + fragA0 + i * 32 * SLICE_BYTES + co);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = wr * 128 + i * 32 + l32_;
-                    fa[i] = *(const lds_u32x4*)(stA + r * SLICE_BYTES + ((chunk ^ ((r >> 2) & 3)) << 4));
+                for (int j = 0; j < 2; ++j) fb[buf][j] = *(const lds_u32x4*)(st + fragB0 + j * 32 * SLICE_BYTES + co);
+            };
+            constexpr int MF = (DT == PACT_BF16) ? 1 : 4;       // MFMA instructions per fragment pair
+            load_frags(0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, MI + 2, 0);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (g + 1 < 4) load_frags(g + 1, (g + 1) & 1);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) Mfma<DT>::run(fa[g & 1][i], fb[g & 1][j], acc[i][j]);
+                // issue order: the LDS reads of the next k-group go out one by one between the
+                // first MFMAs of this one (the scheduler would otherwise serialise read -> wait ->
+                // multiply on one set of fragment registers)
+                if (g + 1 < 4) {
+#pragma unroll
+                    for (int k = 0; k < MI + 2; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, MF * (2 * MI - (MI + 2)), 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x008, MF * 2 * MI, 0);
                 }
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int c = wc * 64 + j * 32 + l32_;
-                    fb[j] = *(const lds_u32x4*)(stB + c * SLICE_BYTES + ((chunk ^ ((c >> 2) & 3)) << 4));
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) Mfma<DT>::run(fa[i], fb[j], acc[i][j]);
             }
         }
+        PACT_STAMP(2);
 
         // ------------------------------------------------------------------ epilogue
-        // acc[i][j][r] holds row  rowBase + wr*128 + i*32 + 8*(r/4) + 4*hh + (r%4)
+        // acc[i][j][r] holds row  rowBase + wr*WROWS + i*32 + 8*(r/4) + 4*hh + (r%4)
         //              and column colBase + wc*64 + j*32 + l32.
         // (lane coordinates are laundered through an empty asm so that the per-element index
         //  arithmetic below is not hoisted out of the tile loop into long-lived registers)
@@ -216,6 +280,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         asm volatile("" : "+v"(l32), "+v"(hh));
         const int colW = colBase + wc * 64;                 // first column of this wave, multiple of 64
         const int wordIdx = colW >> 6;
+        const int rowW = rowBase + wr * WROWS;
         float rj[2];
         int colP[2];
         uint64_t laneOk[2];                                 // lanes whose column exists
@@ -242,122 +307,154 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             }
             nearN = 0;
         };
-        // rows past nA and the diagonal (d_ii = 0 exactly) need a fix-up; only few wave blocks
-        // contain either, the others run the plain variant
-        auto epilogue = [&](auto general_tag) __attribute__((always_inline)) {
-            constexpr bool GENERAL = decltype(general_tag)::value;
+        // (the barriers of the slice loop also ordered the sRinv writes before these reads)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float rs[16];
+        for (int i = 0; i < MI; ++i) {
+            float rs[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) rs[r] = sRinv[wr * 128 + i * 32 + 8 * (r >> 2) + 4 * hh + (r & 3)];
-                // phase A: straight-line arithmetic, values left in place of the accumulators
+            for (int r = 0; r < 16; ++r) rs[r] = sRinv[wr * WROWS + i * 32 + 8 * (r >> 2) + 4 * hh + (r & 3)];
+            const int rowI = rowW + i * 32;                 // first row of this 32-row block
+            // phase A1: cosines (scaled for the density exponent), left in place of the accumulators
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int rowP = rowBase + wr * 128 + i * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
+            for (int r = 0; r < 16; ++r) {
+                const bool pad = rowI + 8 * (r >> 2) + 4 * hh + (r & 3) >= nA;   // padded row: no term, no bit
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        if (MODE == MODE_DENSITY) {
-                            const float t = acc[i][j][r] * rs[r];
-                            float arg = fmaf(t, rj[j], -a_);
-                            if (GENERAL) {
-                                if (rowP >= nA) arg = -INFINITY;        // padded row: exp2 -> 0, no bit
-                                if (rowP == colP[j]) arg = 0.0f;        // d_ii = 0 exactly
-                            }
-                            rho[j][r & 1] += (double)__builtin_amdgcn_exp2f(arg);
-                            acc[i][j][r] = arg;
-                        } else {
-                            float c = acc[i][j][r] * rs[r] * rj[j];
-                            if (GENERAL && rowP >= nA) c = -INFINITY;
-                            acc[i][j][r] = c;
-                        }
-                    }
-                    if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bound the live ranges: registers are tight
-                }
-                __builtin_amdgcn_sched_barrier(0);      // keep the row blocks apart: registers are tight
-                // phase B: one bit per pair; almost every 2 x 64-pair group has none set
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const uint64_t m0 = __ballot(acc[i][0][r] >= t_lo) & laneOk[0];
-                    const uint64_t m1 = __ballot(acc[i][1][r] >= t_lo) & laneOk[1];
-                    if ((m0 | m1) == 0) continue;
-                    // lanes 0-31 of a ballot: row with hh = 0; lanes 32-63: the row 4 below it
-                    const uint64_t w0 = (m0 & 0xFFFFFFFFull) | (m1 << 32);
-                    const uint64_t w1 = (m0 >> 32) | (m1 & 0xFFFFFFFF00000000ull);
-                    const int rowP0 = rowBase + wr * 128 + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (w0 != 0 && lane == 0) adj[(size_t)(row_off + rowP0) * bt.W + wordIdx] = w0;
-                    if (w1 != 0 && lane == 0) adj[(size_t)(row_off + rowP0 + 4) * bt.W + wordIdx] = w1;
-                    if (MODE == MODE_DENSITY) {
-                        const uint64_t mS0 = __ballot(acc[i][0][r] >= t_hi), mS1 = __ballot(acc[i][1][r] >= t_hi);
-                        const uint64_t s0 = (mS0 & 0xFFFFFFFFull) | (mS1 << 32);
-                        const uint64_t s1 = (mS0 >> 32) | (mS1 & 0xFFFFFFFF00000000ull);
-                        const uint64_t n0 = w0 & ~s0, n1 = w1 & ~s1;
-                        if ((n0 | n1) != 0) {
-                            // too close to d_c for fp32: queue the pairs for the fp64 check.  They
-                            // collect in this wavefront's LDS buffer; one atomic reserves list slots
-                            // for a whole buffer (an atomic per event would cost a memory round trip).
-                            const uint64_t mine = hh ? n1 : n0;
-                            const bool f0 = (mine >> l32) & 1ull, f1 = (mine >> (32 + l32)) & 1ull;
-                            const uint64_t b0 = __ballot(f0), b1 = __ballot(f1);
-                            const uint64_t below = (1ull << lane) - 1ull;
-                            const int rowP = rowP0 + 4 * hh;
-                            if (f0) nearBuf[nearN + __popcll(b0 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[0]};
-                            if (f1) nearBuf[nearN + __popcll(b0) + __popcll(b1 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[1]};
-                            nearN += __popcll(b0) + __popcll(b1);
-                            if (nearN > NEAR_BUF - 128) flush_near();
-                        }
-                    }
+                for (int j = 0; j < 2; ++j) {
+                    const float t = acc[i][j][r] * rs[r];
+                    float v = (MODE == MODE_DENSITY) ? fmaf(t, rj[j], -a_) : t * rj[j];
+                    acc[i][j][r] = pad ? -INFINITY : v;
                 }
             }
-        };
-        // (the barriers of the slice loop also ordered the sRinv writes before these reads)
-        // One variant only: two copies of this block (with and without the fix-ups) made the
-        // register allocator spill inside it.
-        const int rowW = rowBase + wr * 128;
-        epilogue(std::true_type{});
+            if (MODE == MODE_DENSITY) {
+                // d_ii = 0 exactly: only the blocks on the diagonal hold such elements
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (rowI == colW + j * 32) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (8 * (r >> 2) + 4 * hh + (r & 3) == l32 && rowI + l32 < nA) acc[i][j][r] = 0.0f;
+                    }
+                // phase A2: density terms
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) rho[j][r & 1] += (double)__builtin_amdgcn_exp2f(acc[i][j][r]);
+                    if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bound the live ranges: registers are tight
+                }
+            }
+            // phase B: one bit per pair; most 32 x 64 blocks have none set: test the block's maximum first
+            float mx = fmaxf(acc[i][0][0], acc[i][1][0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(acc[i][0][r], acc[i][1][r]));
+            if (__ballot(mx >= t_lo) == 0) continue;
+            // Ballots put the 64 columns of two rows (hh = 0 / 1) into a scalar pair; v_writelane
+            // files each half under the lane of its row, so that lane k < 32 ends up holding the
+            // 64-bit bitmap word of row rowI + k.  (Scalar instructions are the scarce resource
+            // here: the CU's four SIMDs share one scalar unit.)
+            uint32_t wlo = 0, whi = 0;
+            static_for<16>([&](auto r_tag) __attribute__((always_inline)) {
+                constexpr int r = decltype(r_tag)::value;
+                constexpr int k0 = 8 * (r >> 2) + (r & 3);            // row of the lanes with hh = 0; hh = 1: k0 + 4
+                const uint64_t m0 = __ballot(acc[i][0][r] >= t_lo);
+                const uint64_t m1 = __ballot(acc[i][1][r] >= t_lo);
+                write_lane<k0>(wlo, (uint32_t)m0);
+                write_lane<k0>(whi, (uint32_t)m1);
+                write_lane<k0 + 4>(wlo, (uint32_t)(m0 >> 32));
+                write_lane<k0 + 4>(whi, (uint32_t)(m1 >> 32));
+                if (MODE == MODE_DENSITY) {
+                    const uint64_t n0 = m0 & ~__ballot(acc[i][0][r] >= t_hi);
+                    const uint64_t n1 = m1 & ~__ballot(acc[i][1][r] >= t_hi);
+                    if ((n0 | n1) != 0) {
+                        // too close to d_c for fp32: queue the pairs for the fp64 check.  They
+                        // collect in this wavefront's LDS buffer; one atomic reserves list slots
+                        // for a whole buffer (an atomic per event would cost a memory round trip).
+                        const uint64_t b0 = n0 & laneOk[0], b1 = n1 & laneOk[1];
+                        const uint64_t below = (1ull << lane) - 1ull;
+                        const bool f0 = (b0 >> lane) & 1ull, f1 = (b1 >> lane) & 1ull;
+                        const int rowP = rowI + k0 + 4 * hh;
+                        if (f0) nearBuf[nearN + __popcll(b0 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[0]};
+                        if (f1) nearBuf[nearN + __popcll(b0) + __popcll(b1 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[1]};
+                        nearN += __popcll(b0) + __popcll(b1);
+                        if (nearN > NEAR_BUF - 128) flush_near();
+                    }
+                }
+            });
+            // the 32 words of this block, one store instruction (the bitmap was cleared beforehand;
+            // columns past the last one come from a clamped row: mask them)
+            wlo &= (uint32_t)laneOk[0];
+            whi &= (uint32_t)laneOk[1];
+            if (lane < 32 && (wlo | whi) != 0)
+                adj[(size_t)(row_off + rowI + lane) * bt.W + wordIdx] = ((uint64_t)whi << 32) | wlo;
+        }
+        PACT_STAMP(3);
         if (MODE == MODE_DENSITY && nearN > 0) flush_near();
 
         if (MODE == MODE_DENSITY) {
-            // column sums over this wave's 128 rows: combine the two half-waves, one store per column
-            const int rt = (rowBase / GRAM_RHO_ROWS) + wr;
-            double* out = ga.rho_part + ((size_t)b * bt.W + rt) * bt.n_max;
+            // column sums over this wave's rows: combine the two half-waves; one row of partials
+            // covers GRAM_RHO_ROWS = 128 kept rows, i.e. one wavefront row (MI = 4) or both (MI = 2)
+            static_assert(GRAM_RHO_ROWS == 128, "the density partials are per 128 kept rows");
+            double tot[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const double part = rho[j][0] + rho[j][1];
-                const double tot = part + __shfl_xor(part, 32, 64);
-                if (hh == 0 && colP[j] < nB && rowW < nA) out[colP[j]] = tot;
+                tot[j] = part + __shfl_xor(part, 32, 64);
             }
+            if (MI == 2) {
+                if (wr == 1 && hh == 0) { sRho[wc * 64 + l32] = tot[0]; sRho[wc * 64 + 32 + l32] = tot[1]; }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                if (wr == 0 && hh == 0) { tot[0] += sRho[wc * 64 + l32]; tot[1] += sRho[wc * 64 + 32 + l32]; }
+            }
+            const int rt = (MI == 4) ? (rowBase / GRAM_RHO_ROWS) + wr : rowBase / GRAM_RHO_ROWS;
+            double* out = ga.rho_part + ((size_t)b * bt.W + rt) * bt.n_max;
+            const bool writer = hh == 0 && (MI == 4 ? rowW < nA : wr == 0);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (writer && colP[j] < nB) out[colP[j]] = tot[j];
         }
-        // the ring and sRinv are rewritten by the next tile: every wavefront must be done with them
-        wait_vmcnt<0>();
-        __syncthreads();
+        PACT_STAMP(4);
+        if (tl + t_step < myTiles) {
+            // the ring and sRinv are rewritten by the next tile: every wavefront must be done with
+            // them (and the slice loop's vmcnt arithmetic assumes nothing older is outstanding)
+            wait_vmcnt<0>();
+            __syncthreads();
+        }
     }
 }
 
-template <int MODE>
-static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                       const char* name) {
-    const int tiles1 = (bt.n_max + TILE - 1) / TILE;
-    int grid_x = tiles1 * tiles1;
+template <int MODE, int MI>
+static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
+                             const char* name) {
+    typedef Shape<MI> SH;
+    const int tilesR = (bt.n_max + SH::TILE_R - 1) / SH::TILE_R, tilesC = (bt.n_max + TILE_C - 1) / TILE_C;
+    int grid_x = tilesR * tilesC;
     const int cap = (bt.B >= 8) ? 32 : (bt.B >= 2 ? 128 : 256);   // one workgroup per CU, 256 CUs
     if (grid_x > cap) grid_x = cap;
     if (grid_x >= 8) grid_x &= ~7;                // a multiple of the 8 XCDs (see the tile order)
     dim3 grid(grid_x, bt.B);
-    const size_t lds = (size_t)NSTAGE * STAGE_BYTES + TILE * sizeof(float);
-    static bool raised[2][2] = {{false, false}, {false, false}};
+    const size_t lds = SH::LDS_BYTES;
+    static bool raised[2] = {false, false};
     const int di = k_dt == PACT_BF16 ? 1 : 0;
-    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE>
-                                         : (const void*)gram_kernel<PACT_F32, MODE>;
-    if (!raised[di][MODE]) {
+    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI>
+                                         : (const void*)gram_kernel<PACT_F32, MODE, MI>;
+    if (!raised[di]) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PACT_ERR_HIP;
-        raised[di][MODE] = true;
+        raised[di] = true;
     }
     if (k_dt == PACT_BF16)
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI>), grid, dim3(512), lds, st, bt, ga);
     else
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI>), grid, dim3(512), lds, st, bt, ga);
     return PACT_OK;
+}
+
+// 256 x 256 tiles when there are enough of them to occupy the chip, else 128 x 256.
+template <int MODE>
+static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
+                       const char* name, long tiles256) {
+    if (tiles256 * bt.B >= 256) return launch_gram_shape<MODE, 4>(bt, ga, k_dt, st, name);
+    return launch_gram_shape<MODE, 2>(bt, ga, k_dt, st, name);
 }
 
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -366,7 +463,8 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = idx; ga.idx_cols = idx; ga.rep = rep;
     ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = w.rho_part;
     ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.margin = (float)cos_margin(dk);
-    return launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density");
+    const long t1 = (bt.n_max + 255) / 256;
+    return launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1);
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -376,7 +474,16 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = pruned_idx; ga.idx_cols = center_idx;
     ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = nullptr;
     ga.near_list = nullptr; ga.near_cnt = nullptr; ga.margin = (float)cos_margin(dk);
-    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates");
+    // rows: the pruned tokens, columns: the centres; neither count is known on the host, a
+    // typical split (half pruned, a third of the rest centres) sizes the choice
+    const long tr = (bt.n_max / 2 + 255) / 256, tc = (bt.n_max / 6 + 255) / 256;
+    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc);
 }
+
+#ifdef PACT_GRAM_STAMPS
+extern "C" int pact_debug_stamps(unsigned long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_gram_stamps), sizeof(g_gram_stamps));
+}
+#endif
 
 }  // namespace pact
