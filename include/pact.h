@@ -73,9 +73,10 @@ typedef enum { PACT_F32 = 0, PACT_BF16 = 1 } pact_dtype;
 
 /* Hyper-parameters of Alg. 3 (host memory).  The paper's defaults: d_n = 2, alpha = 1.5,
  * fallback_T = 10 (appendix D/E).  lambda in [0,1] is the fraction of tokens deemed
- * unimportant; d_c >= 0; d_n > 0; alpha >= 0.  fallback_T >= 0 is Alg. 4's threshold: once a
- * parallel round finds fewer than fallback_T new centres the remaining rounds are left to
- * the single-workgroup finishing kernel.  It changes timing only, never the centres.
+ * unimportant; d_c >= 0; d_n > 0; alpha >= 0.  fallback_T >= 0 is Alg. 4's threshold for
+ * leaving its recursion to the sequential loop; here every round runs inside one workgroup
+ * and gives the sequential loop's centres whatever the threshold, so the value is validated
+ * and otherwise unused.
  * flags: bit 0 (PACT_FLAG_NO_MERGE) writes the centre token's hidden state instead of the
  * cluster mean (the paper's "no merging" ablation). */
 typedef struct {
@@ -96,7 +97,7 @@ typedef struct {
     int32_t n_centers;         /* C                                         (dbdpc_cluster) */
     int32_t n_reincorporated;  /* pruned tokens recovered by Eq. 8          (pact_reincorporate) */
     int32_t n_dropped;         /* pruned tokens not recovered                (pact_reincorporate) */
-    int32_t rounds;            /* parallel centre rounds that found work + finishing rounds */
+    int32_t rounds;            /* parallel centre rounds run, the last one confirming that no token is left */
     int32_t dc_checked_pairs;  /* ordered kept pairs re-evaluated in fp64 near d_c */
     int32_t dc_near_ties;      /* of those, pairs with |d - d_c| <= 1e-6 (each pair counted twice) */
     int32_t refine_overflow;   /* 1 if the near-d_c list overflowed (pairs then keep fp32 decisions) */
@@ -160,7 +161,8 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
 /* Eq. 10 (Alg. 3 step 4): merged[s] = mean of hidden[i] over cluster_id[i] == s.
  *   cluster_id     [n] values in -1..C-1, C = rep->n_centers (read on the device)
  *   center_idx     [C] needed only with PACT_FLAG_NO_MERGE (may be NULL otherwise)
- *   merged         [n, h] out_dt, worst case; rows 0..C-1 written
+ *   merged         [n, h] out_dt, worst case; rows 0..C-1 written (a cluster id nobody carries
+ *                  gives a row of zeros)
  *   cluster_counts [n] out: members per cluster (the weights W of Eq. 11) */
 int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
                const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,

@@ -21,53 +21,65 @@ __device__ __forceinline__ bool precedes(double rho_j, int j, double rho_i, int 
     return rho_j > rho_i || (rho_j == rho_i && j < i);
 }
 
-// fp64 dot product of two rows by a group of 8 lanes (sub = lane & 7); every lane of the
-// group returns the bit-identical total.
-template <int DT>
-__device__ __forceinline__ double group8_dot64(const char* ra, const char* rb, int dk, int sub) {
-    constexpr int EPL = Elem<DT>::EPL;
-    double acc = 0.0;
-    for (int e0 = sub * EPL; e0 < dk; e0 += 4 * 8 * EPL) {       // 4 independent load pairs in flight
-        uint4 va[4], vb[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = e0 + u * 8 * EPL;
-            const size_t o = (size_t)(e < dk ? e : e0) * Elem<DT>::BYTES;
-            va[u] = *(const uint4*)(ra + o);
-            vb[u] = *(const uint4*)(rb + o);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (e0 + u * 8 * EPL < dk) {
-                double a[8], b[8];
-                Elem<DT>::widen(va[u], a);
-                Elem<DT>::widen(vb[u], b);
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
-            }
-        }
-    }
-#pragma unroll
-    for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
-    return acc;
-}
-
-// Nearest of `ncand` candidates (ids in LDS), evaluated 8 at a time by 8-lane groups.
+// Nearest of `ncand` candidates (ids in LDS), eight at a time: the wavefront splits into eight
+// groups of 8 lanes, one candidate row each; lane `sub` of a group takes the 16-byte chunks
+// sub, sub + 8, ... of the rows (own row `mine` against the candidate's), eight candidate
+// chunks in flight per lane, fp64 products summed per lane, then over the group.
 // tok_of(c) maps a candidate id to its token; only distances < thr compete; ties go to the
 // lower candidate id.  Updates (best, bestc), identical in every lane.
+// The first eight of a lane's chunks of its own row (chunks sub, sub + 8, ..., sub + 56), read
+// once per token and kept in registers across the candidate batches.
+__device__ __forceinline__ void load_own_chunks(const char* mine, int nchunk, int sub, uint4 (&own)[8]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int k = sub + 8 * u;
+        own[u] = *(const uint4*)(mine + (size_t)(k < nchunk ? k : sub) * 16);
+    }
+}
+
 template <int DT, typename TokOf>
-__device__ __forceinline__ void nearest_candidate(const lds_i32* cand, int ncand, const char* mine, double nnp,
+__device__ __forceinline__ void nearest_candidate(const lds_i32* cand, int ncand, const char* mine,
+                                                  const uint4 (&own)[8], double nnp,
                                                   const char* kb, size_t row_bytes, const double* nnb,
                                                   int dk, int lane, double thr, TokOf tok_of,
                                                   double& best, int& bestc) {
+    constexpr int EPL = Elem<DT>::EPL;
     const int grp = lane >> 3, sub = lane & 7;
+    const int nchunk = dk / EPL;                       // 16-byte chunks per row (rows are 16-byte multiples)
     for (int c0 = 0; c0 < ncand; c0 += 8) {
         const int ci = c0 + grp;
         const bool valid = ci < ncand;
         const int c = cand[valid ? ci : c0];
         const int tok = tok_of(c);
-        const double dot = group8_dot64<DT>(mine, kb + (size_t)tok * row_bytes, dk, sub);
-        double d = cos_dist64(dot, nnp, nnb[tok]);
+        const char* rb = kb + (size_t)tok * row_bytes;
+        const double nnc = nnb[tok];
+        double acc = 0.0;
+        for (int k0 = sub; k0 < nchunk; k0 += 64) {    // 8 chunks per lane per pass
+            uint4 vb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + 8 * u;
+                vb[u] = *(const uint4*)(rb + (size_t)(k < nchunk ? k : k0) * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int k = k0 + 8 * u;
+                if (k < nchunk) {
+                    uint4 va = (k0 == sub) ? own[u] : *(const uint4*)(mine + (size_t)k * 16);
+                    // (opaque to the optimiser: it would otherwise widen the cached chunks to
+                    //  fp64 once, outside the candidate loop, and hold 64 doubles per lane)
+                    asm volatile("" : "+v"(va.x), "+v"(va.y), "+v"(va.z), "+v"(va.w));
+                    double a[8], x[8];
+                    Elem<DT>::widen(va, a);
+                    Elem<DT>::widen(vb[u], x);
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) acc = fma(a[i], x[i], acc);
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
+        double d = cos_dist64(acc, nnp, nnc);
         int cc = c;
         if (!valid || !(d < thr)) { d = INFINITY; cc = 0x7FFFFFFF; }
 #pragma unroll
@@ -281,7 +293,7 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
                                                               uint32_t* status, int32_t* cnum,
                                                               uint64_t* cmask, int32_t* center_idx) {
     extern __shared__ unsigned char s_raw[];
-    __shared__ int s_unknown, s_nover;
+    __shared__ int s_flag[3], s_nover;
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
@@ -297,8 +309,10 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     const uint4* rec = (const uint4*)(preds + (size_t)b * bt.n_max * PRED_CAP);   // 8 pieces per token
     const int Wq = (q + 63) >> 6;
 
-    if (tid == 0) { s_nover = 0; s_st[dummy] = ST_NOT; }
+    if (tid == 0) { s_nover = 0; s_st[dummy] = ST_NOT; s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0; }
     __syncthreads();
+    // The first round needs no look-ups: nothing is decided yet, so exactly the tokens without a
+    // preceding neighbour become centres and all others wait.  It is folded into the set-up.
     uint4 rc0[RESOLVE_CACHED], rc1[RESOLVE_CACHED];
 #pragma unroll
     for (int k = 0; k < RESOLVE_CACHED; ++k) {
@@ -306,20 +320,27 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         rc0[k] = (p < q) ? rec[(size_t)p * 8] : make_uint4(0, 0, 0, 0);
         rc1[k] = (p < q) ? rec[(size_t)p * 8 + 1] : make_uint4(0, 0, 0, 0);
     }
-    for (int p = tid; p < q; p += 1024) s_st[p] = ST_UNKNOWN;
 #pragma unroll
     for (int k = 0; k < RESOLVE_CACHED; ++k) {
         const int p = tid + 1024 * k;
-        if (p < q && (int)(rc0[k].x & 0xFFFF) > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+        if (p < q) {
+            const int c = rc0[k].x & 0xFFFF;
+            s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
+            if (c > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+        }
     }
-    for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024)
-        if ((int)(rec[(size_t)p * 8].x & 0xFFFF) > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {
+        const int c = rec[(size_t)p * 8].x & 0xFFFF;
+        s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
+        if (c > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    }
     __syncthreads();
     const int nover = s_nover;
-    int rounds = 0;
+    int rounds = 1;
+    // One barrier per round: round r raises s_flag[r % 3] if it leaves a token undecided, and
+    // clears the flag of round r + 1 (last read before the previous barrier) on the way.
     while (true) {
-        if (tid == 0) s_unknown = 0;
-        __syncthreads();
+        if (tid == 0) s_flag[(rounds + 1) % 3] = 0;
         bool still = false;
 #pragma unroll
         for (int k = 0; k < RESOLVE_CACHED; ++k) {
@@ -377,11 +398,10 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
             else if (!pending) { if (lane == 0) s_st[p] = ST_CENTER; }
             else still = true;
         }
-        if (still) s_unknown = 1;
+        if (still) s_flag[rounds % 3] = 1;
+        __syncthreads();
+        const int more = s_flag[rounds % 3];
         ++rounds;
-        __syncthreads();
-        const int more = s_unknown;
-        __syncthreads();
         if (!more) break;
     }
     // Publish: one ballot per 64 tokens gives the centre mask word; the centres are numbered in
@@ -471,6 +491,8 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
         const char* kb = keys + (size_t)sg.base * row_bytes;
         const char* mine = kb + (size_t)tok * row_bytes;
         const double nnp = nnb[tok];
+        uint4 own[8];
+        load_own_chunks(mine, dk / Elem<DT>::EPL, lane & 7, own);
         lds_i32* cand = (lds_i32*)s_cand[wave];
         double best = INFINITY;
         int bestj = 0x7FFFFFFF;
@@ -492,14 +514,14 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
                 nbuf += __popcll(m);
                 ntot += __popcll(m);
                 if (nbuf > CAND_BUF - 64) {
-                    nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
+                    nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
                                           tok_of, best, bestj);
                     nbuf = 0;
                 }
             }
         }
         if (ntot == 1) bestj = cand[0];                 // a single centre in reach: no distance needed
-        else if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
+        else if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
                                              tok_of, best, bestj);
         cid = bestj != 0x7FFFFFFF ? cn[bestj] : -1;
     }
@@ -520,6 +542,7 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
                                                             const int32_t* __restrict__ center_idx,
                                                             const double* __restrict__ nn,
                                                             const uint64_t* __restrict__ adj,
+                                                            int band_unit,
                                                             int32_t* cluster_id, int32_t* cluster_counts) {
     __shared__ int s_cand[4][CAND_BUF];
     const int b = blockIdx.y;
@@ -528,52 +551,65 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
               C = clamp_count(rep[b].n_centers, q);
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int t = blockIdx.x * 4 + wave;
-    if (t >= np) return;
-    const int tok = pruned_idx[sg.base + t];
+    // Token -> workgroup: the candidate Gram pass left the pruned rows of tile-row band x, and
+    // every centre row, in the L2 of XCD x (workgroup id mod 8); the same tokens are taken here
+    // by that XCD's workgroups.
+    int t_first = blockIdx.x * 4 + wave, t_end = np, t_step = gridDim.x * 4;
+    if ((np + band_unit - 1) / band_unit >= 8 && (gridDim.x & 7) == 0) {
+        int lo, hi;
+        xcd_band(np, band_unit, blockIdx.x & 7, lo, hi);
+        t_first = lo + (blockIdx.x >> 3) * 4 + wave;
+        t_end = hi;
+        t_step = (gridDim.x >> 3) * 4;
+    }
     const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
     const char* kb = keys + (size_t)sg.base * row_bytes;
     const double* nnb = nn + sg.base;
     const int32_t* co = center_idx + sg.base;
-    const char* mine = kb + (size_t)tok * row_bytes;
-    const double nnp = nnb[tok];
     const double thr = (double)sg.alpha * (double)sg.d_c;
-    double best = INFINITY;
-    int bestc = 0x7FFFFFFF;
-    if (thr > 0.0 && C > 0) {
-        lds_i32* cand = (lds_i32*)s_cand[wave];
-        auto tok_of = [&](int c) { return co[c]; };
-        const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
-        const int Wc = (C + 63) >> 6;
-        int nbuf = 0;
-        for (int w0 = 0; w0 < Wc; w0 += 64) {
-            const int w = w0 + lane;
-            BitPop bp{(w < Wc) ? row[w] : 0ull};
-            while (bp.any()) {
-                int bit;
-                const bool has = bp.pop(bit);
-                const int c = (w << 6) + bit;
-                const bool ok = has && c < C;
-                const uint64_t m = __ballot(ok);
-                if (ok) cand[nbuf + lanes_below(m, lane)] = c;
-                nbuf += __popcll(m);
-                if (nbuf > CAND_BUF - 64) {
-                    nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
-                                          best, bestc);
-                    nbuf = 0;
+    lds_i32* cand = (lds_i32*)s_cand[wave];
+    auto tok_of = [&](int c) { return co[c]; };
+    const int Wc = (C + 63) >> 6;
+    for (int t = t_first; t < t_end; t += t_step) {
+        const int tok = pruned_idx[sg.base + t];
+        const char* mine = kb + (size_t)tok * row_bytes;
+        const double nnp = nnb[tok];
+        double best = INFINITY;
+        int bestc = 0x7FFFFFFF;
+        uint4 own[8];
+        load_own_chunks(mine, dk / Elem<DT>::EPL, lane & 7, own);
+        if (thr > 0.0 && C > 0) {
+            const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
+            int nbuf = 0;
+            for (int w0 = 0; w0 < Wc; w0 += 64) {
+                const int w = w0 + lane;
+                BitPop bp{(w < Wc) ? row[w] : 0ull};
+                while (bp.any()) {
+                    int bit;
+                    const bool has = bp.pop(bit);
+                    const int c = (w << 6) + bit;
+                    const bool ok = has && c < C;
+                    const uint64_t m = __ballot(ok);
+                    if (ok) cand[nbuf + lanes_below(m, lane)] = c;
+                    nbuf += __popcll(m);
+                    if (nbuf > CAND_BUF - 64) {
+                        nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
+                                              best, bestc);
+                        nbuf = 0;
+                    }
                 }
             }
+            if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
+                                            best, bestc);
         }
-        if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
-                                        best, bestc);
-    }
-    if (lane == 0) {
-        const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
-        cluster_id[sg.base + tok] = cid;
-        // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
-        //  counter that every wavefront hits would serialise at one L2 address)
-        if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
-        if (!(nnp > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
+        if (lane == 0) {
+            const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
+            cluster_id[sg.base + tok] = cid;
+            // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
+            //  counter that every wavefront hits would serialise at one L2 address)
+            if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
+            if (!(nnp > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
+        }
     }
 }
 
@@ -636,20 +672,25 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
-                           hipStream_t st);
+                           int* tile_rows, hipStream_t st);
 
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
                          int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st) {
-    int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, st);
+    int band_unit = 256;
+    int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, &band_unit, st);
     if (rc != PACT_OK) return rc;
-    dim3 grid((bt.n_max + 3) / 4, bt.B);
+    // a wavefront per pruned token; a multiple of 8 workgroups, enough for the largest band
+    const int band_tokens = (bt.n_max + 7) / 8 + band_unit;
+    dim3 grid(8 * ((band_tokens + 3) / 4), bt.B);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_BF16>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, cluster_id, cluster_counts);
+                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit, cluster_id,
+                    cluster_counts);
     else
         PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_F32>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, cluster_id, cluster_counts);
+                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit, cluster_id,
+                    cluster_counts);
     if (count_totals)
         PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
                     pruned_idx, cluster_id);

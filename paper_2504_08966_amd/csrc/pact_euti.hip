@@ -317,7 +317,8 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
                                                            pact_report* __restrict__ rep) {
     extern __shared__ uint32_t s_key[];
     __shared__ double s_M[PACT_MAX_QHEADS], s_Z[PACT_MAX_QHEADS];
-    __shared__ int s_hist[256];
+    __shared__ int s_hist[256 * 16];
+    __shared__ int s_bin[256];
     __shared__ int s_digit, s_newk;
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
@@ -353,19 +354,29 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     int k = (int)floor((double)sg.lambda * (double)n);
     if (k > n - 1) k = n - 1;
     if (k < 0) k = 0;
+    // Radix select, 8 bits per pass from the top.  Scores of one image share their leading bits,
+    // so a plain histogram would serialise thousands of atomics on a handful of LDS words: every
+    // bin has 16 copies (one per lane & 15, in 16 different banks), summed after the pass.
     uint32_t prefix = 0, mask = 0;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        if (tid < 256) s_hist[tid] = 0;
+        for (int i = tid; i < 256 * 16; i += 1024) s_hist[i] = 0;
         __syncthreads();
         for (int i = tid; i < n; i += 1024) {
             const uint32_t u = s_key[i];
-            if ((u & mask) == prefix) atomicAdd(&s_hist[(u >> shift) & 255], 1);
+            if ((u & mask) == prefix) atomicAdd(&s_hist[(((u >> shift) & 255) << 4) + (lane & 15)], 1);
+        }
+        __syncthreads();
+        if (tid < 256) {
+            int t = 0;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) t += s_hist[(tid << 4) + ((c + tid) & 15)];   // (rotated: spreads the banks)
+            s_bin[tid] = t;
         }
         __syncthreads();
         if (tid < 64) {
-            const int c0 = s_hist[4 * tid], c1 = s_hist[4 * tid + 1];
-            const int c2 = s_hist[4 * tid + 2], c3 = s_hist[4 * tid + 3];
+            const int c0 = s_bin[4 * tid], c1 = s_bin[4 * tid + 1];
+            const int c2 = s_bin[4 * tid + 2], c3 = s_bin[4 * tid + 3];
             const int loc = c0 + c1 + c2 + c3;
             int inc = loc;
 #pragma unroll
@@ -389,31 +400,33 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     }
     const uint32_t tau = prefix;
 
-    const int chunk = (n + 1023) / 1024;
-    const int i0 = min(n, tid * chunk);
-    const int i1 = min(n, i0 + chunk);
+    // Ordered split (Eq. 3 / 4): wavefront w owns a contiguous range of tokens; a ballot per 64
+    // tokens gives each its place, so both index lists are written in coalesced runs.
+    const int per_wave = ((n + 15) / 16 + 63) / 64 * 64;
+    const int i0 = min(n, wave * per_wave), i1 = min(n, i0 + per_wave);
     int cnt = 0;
-    for (int i = i0; i < i1; ++i) cnt += s_key[i] >= tau;
-    int inc = cnt;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int v = __shfl_up(inc, d, 64);
-        if (lane >= d) inc += v;
+    for (int i = i0; i < i1; i += 64) {
+        const int t = i + lane;
+        cnt += __popcll(__ballot(t < i1 && s_key[t] >= tau));
     }
-    if (lane == 63) s_wtot[wave] = inc;
+    if (lane == 0) s_wtot[wave] = cnt;
     __syncthreads();
-    int woff = 0, total = 0;
+    int kp = 0, total = 0;
     for (int w = 0; w < 16; ++w) {
-        if (w < wave) woff += s_wtot[w];
+        if (w < wave) kp += s_wtot[w];
         total += s_wtot[w];
     }
-    int kp = woff + inc - cnt;
-    int pp = i0 - kp;
     int32_t* ko = kept_idx + sg.base;
     int32_t* po = pruned_idx + sg.base;
-    for (int i = i0; i < i1; ++i) {
-        if (s_key[i] >= tau) ko[kp++] = i;
-        else po[pp++] = i;
+    for (int i = i0; i < i1; i += 64) {
+        const int t = i + lane;
+        const bool in = t < i1;
+        const bool keep = in && s_key[t] >= tau;
+        const uint64_t m = __ballot(keep);
+        const int below = __popcll(m & ((1ull << lane) - 1ull));
+        if (keep) ko[kp + below] = t;
+        else if (in) po[t - (kp + below)] = t;
+        kp += __popcll(m);
     }
     if (tid == 0) {
         rep[b].n_kept = total;

@@ -171,18 +171,23 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const uint32_t fragB0 = (uint32_t)((TILE_R + wc * 64 + l32_) * SLICE_BYTES);
 
     // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (XCD = workgroup id mod 8) and
-    // every XCD has its own L2, so each XCD works on its own band of tile columns: its key rows
-    // for those columns stay in its L2 while the row tiles stream through.
+    // every XCD has its own L2, so each XCD takes a contiguous eighth of the tile sequence:
+    // column by column for the (symmetric) density pass, row by row for the candidate pass.  An
+    // XCD then works on few tile columns (rows) whose keys stay in its L2, and - counted in
+    // tiles, not in rows - every XCD gets the same load.  After the candidate pass the pruned
+    // rows of an XCD's share and every centre row sit in its L2, where the kernel that
+    // evaluates the candidates (same token -> XCD mapping, see xcd_band) finds them.
     const int xcd = blockIdx.x & 7;
-    const bool banded = tilesC >= 8 && (gridDim.x & 7) == 0;
-    const int c_lo = banded ? (int)((long)xcd * tilesC / 8) : 0;
-    const int bw = banded ? (int)((long)(xcd + 1) * tilesC / 8) - c_lo : tilesC;
-    const int myTiles = banded ? tilesR * bw : tilesR * tilesC;
-    const int t_first = banded ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const long nTiles = (long)tilesR * tilesC;
+    const bool banded = nTiles >= 8 && (gridDim.x & 7) == 0;
+    const int l_lo = banded ? (int)(xcd * nTiles / 8) : 0;
+    const int l_hi = banded ? (int)((xcd + 1) * nTiles / 8) : (int)nTiles;
+    const int t_first = l_lo + (banded ? (int)(blockIdx.x >> 3) : (int)blockIdx.x);
     const int t_step = banded ? (int)(gridDim.x >> 3) : (int)gridDim.x;
 
-    for (int tl = t_first; tl < myTiles; tl += t_step) {
-        const int rowBase = (tl / bw) * TILE_R, colBase = (c_lo + tl % bw) * TILE_C;
+    for (int tl = t_first; tl < l_hi; tl += t_step) {
+        const int rowBase = ((MODE == MODE_DENSITY) ? tl % tilesR : tl / tilesC) * TILE_R;
+        const int colBase = ((MODE == MODE_DENSITY) ? tl / tilesR : tl % tilesC) * TILE_C;
 
         // byte offsets of this lane's NB DMA rows; rows past the end are clamped to the last one
         // (their products are discarded in the epilogue)
@@ -413,7 +418,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 if (writer && colP[j] < nB) out[colP[j]] = tot[j];
         }
         PACT_STAMP(4);
-        if (tl + t_step < myTiles) {
+        if (tl + t_step < l_hi) {
             // the ring and sRinv are rewritten by the next tile: every wavefront must be done with
             // them (and the slice loop's vmcnt arithmetic assumes nothing older is outstanding)
             wait_vmcnt<0>();
@@ -452,8 +457,10 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
 // 256 x 256 tiles when there are enough of them to occupy the chip, else 128 x 256.
 template <int MODE>
 static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                       const char* name, long tiles256) {
-    if (tiles256 * bt.B >= 256) return launch_gram_shape<MODE, 4>(bt, ga, k_dt, st, name);
+                       const char* name, long tiles256, int* tile_rows) {
+    const bool big = tiles256 * bt.B >= 256;
+    if (tile_rows) *tile_rows = big ? Shape<4>::TILE_R : Shape<2>::TILE_R;
+    if (big) return launch_gram_shape<MODE, 4>(bt, ga, k_dt, st, name);
     return launch_gram_shape<MODE, 2>(bt, ga, k_dt, st, name);
 }
 
@@ -464,12 +471,12 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
     ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = w.rho_part;
     ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.margin = (float)cos_margin(dk);
     const long t1 = (bt.n_max + 255) / 256;
-    return launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1);
+    return launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, nullptr);
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
-                           hipStream_t st) {
+                           int* tile_rows, hipStream_t st) {
     GramArgs ga;
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = pruned_idx; ga.idx_cols = center_idx;
     ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = nullptr;
@@ -477,7 +484,7 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
     // rows: the pruned tokens, columns: the centres; neither count is known on the host, a
     // typical split (half pruned, a third of the rest centres) sizes the choice
     const long tr = (bt.n_max / 2 + 255) / 256, tc = (bt.n_max / 6 + 255) / 256;
-    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc);
+    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, tile_rows);
 }
 
 #ifdef PACT_GRAM_STAMPS

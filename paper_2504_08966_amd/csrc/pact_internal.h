@@ -261,6 +261,15 @@ __device__ __forceinline__ double wave_dot64(const char* ra, const char* rb, int
     return wave_sum_f64(acc);
 }
 
+// Rows [lo, hi) whose tile row starts in XCD x's share when `count` rows are cut into tiles of
+// `unit` rows and the row-major tile sequence is dealt to the 8 XCDs in contiguous eighths
+// (the candidate pass of the Gram kernel): tile row r belongs to XCD floor(8 r / tiles).
+__device__ __forceinline__ void xcd_band(int count, int unit, int x, int& lo, int& hi) {
+    const int tiles = (count + unit - 1) / unit;
+    lo = min(count, (int)(((long)x * tiles + 7) / 8) * unit);
+    hi = min(count, (int)(((long)(x + 1) * tiles + 7) / 8) * unit);
+}
+
 // Eq. 5 in fp64 from a dot product and the two squared norms; zero vector -> cosine 0.
 __device__ __forceinline__ double cos_dist64(double dot, double nna, double nnb) {
     const double den = sqrt(nna * nnb);

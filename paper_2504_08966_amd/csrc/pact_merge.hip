@@ -179,7 +179,7 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
             }
             double outv[EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : acc[i] / (double)m_eff;
+            for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : (m_eff == 0 ? 0.0 : acc[i] / (double)m_eff);
             StoreOut<ODT>::template put<EPL>(merged + ((size_t)sg.base + c) * (size_t)h * (ODT == PACT_BF16 ? 2 : 4),
                                              (size_t)e, outv);
         }
