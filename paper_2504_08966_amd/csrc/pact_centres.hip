@@ -225,11 +225,16 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 // For every kept token: the list of its neighbours (bitmap row) that precede it in the
 // density order, as 16-bit positions in slots 1..KP of its PRED_CAP-slot record; slot 0 holds
 // the list length, or KP+1 if the list did not fit (the token is then evaluated from its
-// bitmap row).  One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+// bitmap row).  The first four slots are also written to the token's 8-byte head: most tokens
+// have at most three preceding neighbours, and the kernel that runs the rounds - a single
+// workgroup - then has 8 bytes per token to fetch instead of 32.
+// One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+constexpr int HEAD_PREDS = 3;
 __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
                                                           const uint64_t* __restrict__ adj,
                                                           const double* __restrict__ rho,
-                                                          uint16_t* __restrict__ preds) {
+                                                          uint16_t* __restrict__ preds,
+                                                          uint2* __restrict__ heads) {
     const int b = blockIdx.y;
     const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
     const int lane = threadIdx.x & 63;
@@ -239,6 +244,7 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
     const double rp = r[p];
     const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
     uint16_t* out = preds + ((size_t)b * bt.n_max + p) * PRED_CAP;
+    uint16_t* head = (uint16_t*)(heads + (size_t)b * bt.n_max + p);
     const int Wq = (q + 63) >> 6;
     int total = 0;
     for (int w0 = 0; w0 < Wq; w0 += 64) {
@@ -252,48 +258,60 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
             const uint64_t m = __ballot(pre);
             const int slot = total + lanes_below(m, lane);
             if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
+            if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
             total += __popcll(m);
         }
     }
-    if (lane == 0) out[0] = (uint16_t)(total > KP ? KP + 1 : total);
+    if (lane == 0) {
+        const uint16_t c = (uint16_t)(total > KP ? KP + 1 : total);
+        out[0] = c;
+        head[0] = c;
+    }
 }
 
-// Status checks of the 8 slots of one 16-byte piece of a predecessor record; slot s of the
-// piece is list position pos0 + s, valid for 1 <= position <= c.
-__device__ __forceinline__ void check_preds8(const uint4& v, int pos0, int c, lds_vu8* st,
-                                             int dummy, bool& blocked, bool& pending) {
-    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-    unsigned char sj[8];
+// Status checks of the list positions 1..15 of a predecessor record held in two 16-byte
+// pieces; `pm` has bit s-1 set while the predecessor at position s is still undecided
+// (positions past the list length never are).  A centre among them blocks the token; the ones
+// found not to be centres are dropped from `pm`.
+__device__ __forceinline__ bool check_pending15(const uint4& v0, const uint4& v1, uint32_t& pm, lds_vu8* st) {
+    const uint32_t wv[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    bool blocked = false;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {          // eight independent LDS reads; st[dummy] == ST_NOT
-        const int pos = pos0 + t;
-        const int j = (wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF;
-        sj[t] = st[(pos >= 1 && pos <= c) ? j : dummy];
+    for (int s = 1; s < 16; ++s) {
+        if (pm & (1u << (s - 1))) {
+            const int j = (wv[s >> 1] >> ((s & 1) * 16)) & 0xFFFF;
+            const unsigned char sj = st[j];
+            blocked |= (sj == ST_CENTER);
+            if (sj == ST_NOT) pm &= ~(1u << (s - 1));
+        }
     }
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        blocked |= (sj[t] == ST_CENTER);
-        pending |= (sj[t] == ST_UNKNOWN);
-    }
+    return blocked;
 }
 
 // All rounds of the centre selection in one workgroup per sample, statuses in LDS; then the
-// centres are numbered in ascending token order and published.  Each thread owns the tokens
-// tid, tid + 1024, ... and keeps the first 32 bytes of their records (count + 15
-// predecessors) in registers across the rounds, so most tokens never touch memory again.
-// Tokens whose list overflowed are evaluated from their bitmap row by a whole wavefront.
-// grid (B), block 1024, dynamic LDS: (n_max + 64) bytes (status) + n_max * 2 bytes (overflow
-// token list) + W * 4 bytes (centres per 64 tokens).
-constexpr int RESOLVE_CACHED = 4;     // 4 tokens x 32 bytes: what fits beside the rest in 128 VGPRs
+// centres are numbered in ascending token order and published.
+//  * The first round needs no look-ups: nothing is decided yet, so exactly the tokens without a
+//    preceding neighbour become centres.  It is folded into the set-up.
+//  * Each thread owns the tokens tid, tid + 1024, ... and keeps the 8-byte heads of the first
+//    four in registers; tokens with more than HEAD_PREDS preceding neighbours are collected in
+//    a list, and thread i also keeps the first 32 bytes of the i-th listed token's record.
+//    Per token a bit mask remembers which predecessors are still undecided, so a round only
+//    looks at those.
+//  * Tokens whose list overflowed the record are evaluated from their bitmap row by a whole
+//    wavefront.
+// grid (B), block 1024, dynamic LDS: (n_max + 64) bytes (status) + n_max * 2 bytes (token
+// lists: long lists from the front, overflowed from the back) + W * 4 bytes (centres per word).
+constexpr int RESOLVE_CACHED = 4;
 __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_report* rep,
                                                               const uint64_t* __restrict__ adj,
                                                               const double* __restrict__ rho,
                                                               const uint16_t* __restrict__ preds,
+                                                              const uint2* __restrict__ heads,
                                                               const int32_t* __restrict__ idx,
                                                               uint32_t* status, int32_t* cnum,
                                                               uint64_t* cmask, int32_t* center_idx) {
     extern __shared__ unsigned char s_raw[];
-    __shared__ int s_flag[3], s_nover;
+    __shared__ int s_flag[3], s_nlong, s_nover;
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
@@ -301,79 +319,151 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int qpad = (bt.n_max + 63) / 64 * 64;
-    lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64], s_st[qpad] = ST_NOT
-    lds_u16* s_over = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
+    lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64]
+    lds_u16* s_list = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
     lds_i32* s_wcnt = (lds_i32*)(s_raw + qpad + 64 + (size_t)qpad * 2);   // [W + 1]
-    const int dummy = qpad;
     const double* r = rho + (size_t)b * bt.n_max;
     const uint4* rec = (const uint4*)(preds + (size_t)b * bt.n_max * PRED_CAP);   // 8 pieces per token
+    const uint2* hd = heads + (size_t)b * bt.n_max;
     const int Wq = (q + 63) >> 6;
+    const int last = bt.n_max - 1;                               // overflow list grows down from here
 
-    if (tid == 0) { s_nover = 0; s_st[dummy] = ST_NOT; s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0; }
+    if (tid == 0) { s_nlong = 0; s_nover = 0; s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0; }
     __syncthreads();
-    // The first round needs no look-ups: nothing is decided yet, so exactly the tokens without a
-    // preceding neighbour become centres and all others wait.  It is folded into the set-up.
-    uint4 rc0[RESOLVE_CACHED], rc1[RESOLVE_CACHED];
+    uint2 h[RESOLVE_CACHED];
 #pragma unroll
     for (int k = 0; k < RESOLVE_CACHED; ++k) {
         const int p = tid + 1024 * k;
-        rc0[k] = (p < q) ? rec[(size_t)p * 8] : make_uint4(0, 0, 0, 0);
-        rc1[k] = (p < q) ? rec[(size_t)p * 8 + 1] : make_uint4(0, 0, 0, 0);
+        h[k] = (p < q) ? hd[p] : make_uint2(0, 0);
     }
-#pragma unroll
-    for (int k = 0; k < RESOLVE_CACHED; ++k) {
-        const int p = tid + 1024 * k;
-        if (p < q) {
-            const int c = rc0[k].x & 0xFFFF;
-            s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
-            if (c > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+    // set-up = round 1, and the two token lists (appended a wavefront at a time)
+    auto setup = [&](int p, uint32_t hx) __attribute__((always_inline)) {
+        const int c = hx & 0xFFFF;
+        const bool in = p < q;
+        if (in) s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
+        const bool lng = in && c > HEAD_PREDS && c <= KP, ovr = in && c > KP;
+        const uint64_t ml = __ballot(lng), mo = __ballot(ovr);
+        if (ml) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_nlong, __popcll(ml));
+            base = __shfl(base, 0, 64);
+            if (lng) s_list[base + lanes_below(ml, lane)] = (uint16_t)p;
         }
-    }
-    for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {
-        const int c = rec[(size_t)p * 8].x & 0xFFFF;
-        s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
-        if (c > KP) s_over[atomicAdd(&s_nover, 1)] = (uint16_t)p;
+        if (mo) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_nover, __popcll(mo));
+            base = __shfl(base, 0, 64);
+            if (ovr) s_list[last - (base + lanes_below(mo, lane))] = (uint16_t)p;
+        }
+    };
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) setup(tid + 1024 * k, h[k].x);
+    for (int p0 = 1024 * RESOLVE_CACHED; p0 < q; p0 += 1024) {      // (wave-uniform trip count)
+        const int p = p0 + tid;
+        setup(p, p < q ? hd[p].x : 0u);
     }
     __syncthreads();
-    const int nover = s_nover;
+    const int nlong = s_nlong, nover = s_nover;
+    // pending masks: one bit per predecessor position
+    uint32_t pmh[RESOLVE_CACHED];
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) {
+        const int c = h[k].x & 0xFFFF;
+        pmh[k] = (c <= HEAD_PREDS) ? ((1u << c) - 1u) : 0u;
+    }
+    int lp = -1, lc = 0;                                         // this thread's listed token
+    uint4 l0 = make_uint4(0, 0, 0, 0), l1 = l0;
+    uint32_t pml = 0;
+    if (tid < nlong) {
+        lp = s_list[tid];
+        l0 = rec[(size_t)lp * 8];
+        l1 = rec[(size_t)lp * 8 + 1];
+        lc = l0.x & 0xFFFF;
+        pml = (lc >= 15) ? 0x7FFFu : ((1u << lc) - 1u);
+    }
     int rounds = 1;
     // One barrier per round: round r raises s_flag[r % 3] if it leaves a token undecided, and
     // clears the flag of round r + 1 (last read before the previous barrier) on the way.
     while (true) {
         if (tid == 0) s_flag[(rounds + 1) % 3] = 0;
         bool still = false;
-#pragma unroll
-        for (int k = 0; k < RESOLVE_CACHED; ++k) {
-            const int p = tid + 1024 * k;
-            if (p < q && s_st[p] == ST_UNKNOWN) {
-                const int c = rc0[k].x & 0xFFFF;
-                if (c <= KP) {
-                    bool blocked = false, pending = false;
-                    check_preds8(rc0[k], 0, c, s_st, dummy, blocked, pending);
-                    if (c >= 8) check_preds8(rc1[k], 8, c, s_st, dummy, blocked, pending);
-                    for (int piece = 2; piece * 8 <= c && !blocked; ++piece)
-                        check_preds8(rec[(size_t)p * 8 + piece], piece * 8, c, s_st, dummy, blocked, pending);
-                    if (blocked) s_st[p] = ST_NOT;
-                    else if (!pending) s_st[p] = ST_CENTER;
-                    else still = true;
-                }
-            }
-        }
-        for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {
-            if (s_st[p] != ST_UNKNOWN) continue;
-            const uint4 f = rec[(size_t)p * 8];
-            const int c = f.x & 0xFFFF;
-            if (c > KP) continue;
-            bool blocked = false, pending = false;
-            check_preds8(f, 0, c, s_st, dummy, blocked, pending);
-            for (int piece = 1; piece * 8 <= c && !blocked; ++piece)
-                check_preds8(rec[(size_t)p * 8 + piece], piece * 8, c, s_st, dummy, blocked, pending);
+        auto decide = [&](int p, bool blocked, bool pending) __attribute__((always_inline)) {
             if (blocked) s_st[p] = ST_NOT;
             else if (!pending) s_st[p] = ST_CENTER;
             else still = true;
+        };
+        // short lists, from the heads in registers
+#pragma unroll
+        for (int k = 0; k < RESOLVE_CACHED; ++k) {
+            const int p = tid + 1024 * k;
+            if (pmh[k] != 0 && s_st[p] == ST_UNKNOWN) {
+                const int j[HEAD_PREDS] = {(int)(h[k].x >> 16), (int)(h[k].y & 0xFFFF), (int)(h[k].y >> 16)};
+                bool blocked = false;
+#pragma unroll
+                for (int s = 0; s < HEAD_PREDS; ++s) {
+                    if (pmh[k] & (1u << s)) {
+                        const unsigned char sj = s_st[j[s]];
+                        blocked |= (sj == ST_CENTER);
+                        if (sj == ST_NOT) pmh[k] &= ~(1u << s);
+                    }
+                }
+                decide(p, blocked, pmh[k] != 0);
+            }
         }
-        for (int o = wave; o < nover; o += 16) {                 // wave-uniform trip count
-            const int p = s_over[o];
+        for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {     // beyond the cached tokens: heads from memory
+            if (s_st[p] != ST_UNKNOWN) continue;
+            const uint2 hv = hd[p];
+            const int c = hv.x & 0xFFFF;
+            if (c > HEAD_PREDS) continue;
+            const int j[HEAD_PREDS] = {(int)(hv.x >> 16), (int)(hv.y & 0xFFFF), (int)(hv.y >> 16)};
+            bool blocked = false, pending = false;
+            for (int s = 0; s < c; ++s) {
+                const unsigned char sj = s_st[j[s]];
+                blocked |= (sj == ST_CENTER);
+                pending |= (sj == ST_UNKNOWN);
+            }
+            decide(p, blocked, pending);
+        }
+        // long lists: the first 15 positions from registers, the rest of the record from memory
+        if (lp >= 0 && s_st[lp] == ST_UNKNOWN) {
+            bool blocked = check_pending15(l0, l1, pml, s_st);
+            bool pending = pml != 0;
+            for (int piece = 2; piece * 8 <= lc && !blocked; ++piece) {
+                const uint4 v = rec[(size_t)lp * 8 + piece];
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    if (piece * 8 + t <= lc) {
+                        const unsigned char sj = s_st[(wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF];
+                        blocked |= (sj == ST_CENTER);
+                        pending |= (sj == ST_UNKNOWN);
+                    }
+                }
+            }
+            decide(lp, blocked, pending);
+        }
+        for (int i = tid + 1024; i < nlong; i += 1024) {                    // more listed tokens than threads
+            const int p = s_list[i];
+            if (s_st[p] != ST_UNKNOWN) continue;
+            const int c = rec[(size_t)p * 8].x & 0xFFFF;
+            bool blocked = false, pending = false;
+            for (int piece = 0; piece * 8 <= c && !blocked; ++piece) {
+                const uint4 v = rec[(size_t)p * 8 + piece];
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int pos = piece * 8 + t;
+                    if (pos >= 1 && pos <= c) {
+                        const unsigned char sj = s_st[(wv[t >> 1] >> ((t & 1) * 16)) & 0xFFFF];
+                        blocked |= (sj == ST_CENTER);
+                        pending |= (sj == ST_UNKNOWN);
+                    }
+                }
+            }
+            decide(p, blocked, pending);
+        }
+        for (int o = wave; o < nover; o += 16) {                 // overflowed lists (wave-uniform trip count)
+            const int p = s_list[last - o];
             if (s_st[p] != ST_UNKNOWN) continue;
             const double rp = r[p];
             const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
@@ -649,7 +739,8 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
                     w.rho, rank_opt);
     dim3 gtok((bt.n_max + 3) / 4, bt.B);
-    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds);
+    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
+                w.heads);
     const size_t qpad = (size_t)((bt.n_max + 63) / 64 * 64);
     const size_t lds = qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4;
     static size_t raised = 0;
@@ -660,7 +751,7 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         raised = lds;
     }
     PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
-                      w.adj, w.rho, w.preds, idx, w.status, w.cnum, w.cmask, center_idx);
+                      w.adj, w.rho, w.preds, w.heads, idx, w.status, w.cnum, w.cmask, center_idx);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
                     w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);

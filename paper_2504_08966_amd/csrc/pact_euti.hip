@@ -17,7 +17,7 @@ struct PrepArgs {
     const char* keys; int32_t dk; int32_t key_dt_unused;
     const char* q; int32_t qcols;            // q == nullptr: no query pass
     double* nn; float* rinv; uint64_t* adj; double* qg_part;
-    uint32_t* status; int32_t* ident; int32_t* near_cnt; int32_t* round_new;
+    uint32_t* status; int32_t* ident; int32_t* near_cnt;
     pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
     const int32_t* n_idx_dev; uint32_t* zeros;
     int32_t mode; int32_t n_key_blocks;
@@ -34,7 +34,6 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         if (kblk == 0 && b == 0 && threadIdx.x < 64) a.zeros[threadIdx.x] = 0u;
         if (kblk == 0 && threadIdx.x == 0) {
             a.near_cnt[b] = 0;
-            for (int r = 0; r < MAX_ROUNDS; ++r) a.round_new[b * MAX_ROUNDS + r] = 0;
             pact_report* rp = a.rep + b;
             const int mode = a.mode;
             if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {
@@ -455,7 +454,7 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
     a.keys = (const char*)keys; a.dk = dk; a.key_dt_unused = 0;
     a.q = (const char*)q; a.qcols = qcols;
     a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
-    a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt; a.round_new = w.round_new;
+    a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt;
     a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
     a.zeros = w.zeros;
     a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;

@@ -35,7 +35,6 @@ constexpr int SCORE_TOK_PER_WG = 16;  // tokens (= wavefronts) per workgroup in 
 constexpr int PRED_CAP = 64;          // 16-bit slots per kept token: slot 0 = count, then up to 63 preceding neighbours
 constexpr int GRAM_RHO_ROWS = 128;    // kept rows summed into one row of the density partials
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
-constexpr int MAX_ROUNDS = 8;         // parallel centre rounds launched before the finishing kernel
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
 
 struct WsLayout {
@@ -45,9 +44,9 @@ struct WsLayout {
     size_t adj;                                        // [B][n_max][W] u64: rows < q adjacency, rows q.. candidates
     size_t rho_part;                                   // [B][W][n_max] f64
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
-    size_t preds, pcnt;                                // [B][n_max][PRED_CAP] u16, [B][n_max] i32
-    size_t near_list, near_cnt, round_new;             // refine list, counters
-    size_t cursor, offsets, members;                   // merge CSR (global row index)
+    size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
+    size_t near_list, near_cnt;                        // refine list, counter
+    size_t offsets, members;                           // merge CSR (global row index)
     size_t zeros;                                      // 256 zero bytes
     size_t total;
 };
@@ -76,11 +75,9 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.cnum = take(sizeof(int32_t) * B * n_max);
     L.cmask = take(sizeof(uint64_t) * B * W);
     L.preds = take(sizeof(uint16_t) * B * n_max * PRED_CAP);
-    L.pcnt = take(sizeof(int32_t) * B * n_max);
+    L.heads = take(sizeof(uint16_t) * 4 * B * n_max);
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
     L.near_cnt = take(sizeof(int32_t) * B);
-    L.round_new = take(sizeof(int32_t) * B * MAX_ROUNDS);
-    L.cursor = take(sizeof(int32_t) * total);
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
     L.zeros = take(256);
@@ -93,8 +90,8 @@ struct Ws {
     double* qg_part; double* qg; double* logits; double* hnorm; double* sm_part;
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
-    int32_t* cnum; uint64_t* cmask; uint16_t* preds; int32_t* pcnt; uint32_t* near_list; int32_t* near_cnt; int32_t* round_new;
-    int32_t* cursor; int32_t* offsets; int32_t* members; uint32_t* zeros;
+    int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt;
+    int32_t* offsets; int32_t* members; uint32_t* zeros;
 };
 
 inline Ws resolve(void* base, const WsLayout& L) {
@@ -107,10 +104,10 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.adj = (uint64_t*)(p + L.adj); w.rho_part = (double*)(p + L.rho_part);
     w.rho = (double*)(p + L.rho); w.rank = (int32_t*)(p + L.rank);
     w.status = (uint32_t*)(p + L.status); w.cnum = (int32_t*)(p + L.cnum);
-    w.preds = (uint16_t*)(p + L.preds); w.pcnt = (int32_t*)(p + L.pcnt);
+    w.preds = (uint16_t*)(p + L.preds); w.heads = (uint2*)(p + L.heads);
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
-    w.near_cnt = (int32_t*)(p + L.near_cnt); w.round_new = (int32_t*)(p + L.round_new);
-    w.cursor = (int32_t*)(p + L.cursor); w.offsets = (int32_t*)(p + L.offsets);
+    w.near_cnt = (int32_t*)(p + L.near_cnt);
+    w.offsets = (int32_t*)(p + L.offsets);
     w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
     return w;
 }
