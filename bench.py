@@ -61,6 +61,71 @@ def measured_traffic(kernel: str):
     return None
 
 
+def other_configs(P, gen, torch, np):
+    """us per call of the other workload shapes (warm, back to back), with their counts."""
+    with open(os.path.join(ROOT, "pact_synth", "manifest.json")) as f:
+        man = json.load(f)
+
+    def dev(x, dt):
+        t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+        return t.to(torch.bfloat16) if dt == "bf16" else t
+
+    def entry(sm):
+        grids = sm.n // (sm.config.gh * sm.config.gw)
+        return man[f"{sm.config.name}:s{sm.seed}:g{grids}:l{sm.lam:.2f}"]
+
+    def timeit(fn, steps):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e6
+
+    out = {}
+    for name, steps in (("img_0p5b", 200), ("vid_long", 20)):
+        cfg = gen.CONFIGS[name]
+        sm = gen.make_sample(cfg, 0)
+        m = entry(sm)
+        hid = dev(sm.hidden, cfg.hidden_dtype)
+        ks = dev(sm.keys.reshape(sm.n, -1), cfg.key_dtype)
+        qs = dev(sm.queries.reshape(sm.n, -1), cfg.key_dtype)
+        prm = P.PactParams(sm.lam, m["d_c"], 2.0, 1.5)
+        ws = P.alloc_workspace(sm.n, 1, cfg.dk, cfg.n_kv, cfg.d_h)
+        o = P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws)
+        us = timeit(lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws, out=o), steps)
+        r = P.read_report(o["rep"])
+        assert r["n_kept"] == m["q"] and r["n_centers"] == m["C"], (name, r, m)
+        out[name] = {"n": sm.n, "batch": 1, "us_per_call": round(us, 1), "samples_per_s": round(1e6 / us, 1),
+                     "q": r["n_kept"], "C": r["n_centers"]}
+        del hid, ks, qs, ws, o
+    for name, samples, steps in (("vid_7b_batch8", gen.make_batch("vid_7b", 0), 30),
+                                 ("varlen16", gen.make_varlen_batch(0), 30)):
+        cu = [0]
+        for sm in samples:
+            cu.append(cu[-1] + sm.n)
+        cfg0 = samples[0].config
+        hid = dev(np.concatenate([sm.hidden for sm in samples]), "bf16")
+        ks = dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "bf16")
+        qs = dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "bf16")
+        prms = [P.PactParams(sm.lam, entry(sm)["d_c"], 2.0, 1.5) for sm in samples]
+        exp = [(entry(sm)["q"], entry(sm)["C"]) for sm in samples]
+        n_max = max(sm.n for sm in samples)
+        ws = P.alloc_workspace(n_max, len(samples), cfg0.dk, cfg0.n_kv, cfg0.d_h)
+        o = P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h, cfg0.n_kv, cu, prms, ws=ws)
+        us = timeit(lambda: P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h, cfg0.n_kv, cu, prms,
+                                                 ws=ws, out=o), steps)
+        reps = P.read_report(o["rep"])
+        assert [(r["n_kept"], r["n_centers"]) for r in reps] == exp, (name, reps, exp)
+        out[name] = {"n_total": cu[-1], "batch": len(samples), "us_per_call": round(us, 1),
+                     "us_per_sample": round(us / len(samples), 1),
+                     "samples_per_s": round(len(samples) * 1e6 / us, 1)}
+        del hid, ks, qs, ws, o
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +134,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print per-kernel averages to stderr")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time the other workload shapes (single image, video batch, ragged batch, long "
+                         "video) and add them to the JSON line under other_configs")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel once over this many MiB "
                          "(a dispatch of known HBM traffic for rocprofv3 --pmc runs)")
@@ -148,6 +216,42 @@ def main():
         print(f"  sum of kernels      {sum(per_step.values()) * 1e3:9.2f} us/step; wall {ms_per_step * 1e3:.2f} us/step",
               file=sys.stderr)
 
+    # distribution over steps (events on the launch stream around each step), warm and cold:
+    # "cold" writes a 512 MiB scrub buffer between steps, so that neither the L2s nor the 256 MB
+    # Infinity Cache still hold the inputs (the hidden states alone are 52 MB)
+    def step_times(n_steps, scrub):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+        for a, b in evs:
+            if scrub is not None:
+                scrub.fill_(1)
+            a.record()
+            step()
+            b.record()
+        torch.cuda.synchronize()
+        return np.array([a.elapsed_time(b) * 1e3 for a, b in evs])      # us
+
+    dist_steps = min(max(args.steps, 100), 300)
+    warm_us = step_times(dist_steps, None)
+    scrub = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+    cold_us = step_times(dist_steps, scrub)
+    P.pact_profile_enable(True)
+    P.pact_profile_reset()
+    cold_prof_steps = 30
+    for _ in range(cold_prof_steps):
+        scrub.fill_(1)
+        step()
+    torch.cuda.synchronize()
+    crecs = P.pact_profile_read(cold_prof_steps * 64)
+    P.pact_profile_enable(False)
+    del scrub
+    ctot, ccnt = {}, {}
+    for name, ms in crecs:
+        ctot[name] = ctot.get(name, 0.0) + ms
+        ccnt[name] = ccnt.get(name, 0) + 1
+    cold_per_launch = {k: ctot[k] / ccnt[k] for k in ctot}
+    pct = lambda a: {"p10": round(float(np.percentile(a, 10)), 2), "p50": round(float(np.percentile(a, 50)), 2),
+                     "p90": round(float(np.percentile(a, 90)), 2)}
+
     q_kept, C, n_re = rep["n_kept"], rep["n_centers"], rep["n_reincorporated"]
     roof = None
     for k in sorted(per_step, key=per_step.get, reverse=True):
@@ -164,7 +268,27 @@ def main():
                 "frac": round(ach / peak, 4), "traffic": traffic, "us_per_launch": round(sec * 1e6, 2),
                 "work_per_launch": work, "work_unit": unit,
                 "share_of_step": round(per_step[k] / sum(per_step.values()), 3)}
+        if k == "gram_density":
+            # the kernel computes the full (symmetric) matrix: executed flops are twice the algorithmic ones
+            roof["executed_flop_per_launch"] = 2.0 * work
+            roof["frac_executed"] = round(2.0 * ach / peak, 4)
         break
+
+    # the bandwidth-bound stages, warm (inputs still in the caches from the previous step) and cold
+    hbm_stages = {}
+    for k in ("score_logits", "merge_mean", "prep"):
+        kk = "key_prep" if k == "prep" else k
+        bound, work, unit = algorithmic_work(kk, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
+        if k == "prep":
+            work = n * dk * 2 * 2 + n * ((n + 63) // 64) * 8     # keys + queries read, bitmap rows cleared
+        if k not in per_launch:
+            continue
+        ent = {"bytes_algorithmic": work, "traffic_measured": measured_traffic(k)}
+        for tag, tbl in (("warm", per_launch), ("cold", cold_per_launch)):
+            if k in tbl:
+                gbs = work / (tbl[k] * 1e-3) / 1e9
+                ent[tag] = {"us": round(tbl[k] * 1e3, 2), "GB/s": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
+        hbm_stages[k] = ent
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -197,8 +321,13 @@ def main():
                    "rounds": rep["rounds"], "dc_checked_pairs": rep["dc_checked_pairs"]},
         "roofline": roof,
         "cpu_baseline": cpu,
+        "us_per_step_warm": pct(warm_us), "us_per_step_cold": pct(cold_us),
+        "hbm_stages": hbm_stages,
         "kernels_us_per_step": {k: round(v * 1e3, 2) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
+        "kernels_us_per_step_cold": {k: round(v * 1e3, 2) for k, v in sorted(cold_per_launch.items(), key=lambda kv: -kv[1])},
     }
+    if args.all_configs:
+        line["other_configs"] = other_configs(P, gen, torch, np)
     print(json.dumps(line))
 
 
