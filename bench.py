@@ -134,6 +134,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print per-kernel averages to stderr")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache passes (profiling runs)")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the other workload shapes (single image, video batch, ragged batch, long "
                          "video) and add them to the JSON line under other_configs")
@@ -232,23 +233,25 @@ def main():
 
     dist_steps = min(max(args.steps, 100), 300)
     warm_us = step_times(dist_steps, None)
-    scrub = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
-    cold_us = step_times(dist_steps, scrub)
-    P.pact_profile_enable(True)
-    P.pact_profile_reset()
-    cold_prof_steps = 30
-    for _ in range(cold_prof_steps):
-        scrub.fill_(1)
-        step()
-    torch.cuda.synchronize()
-    crecs = P.pact_profile_read(cold_prof_steps * 64)
-    P.pact_profile_enable(False)
-    del scrub
-    ctot, ccnt = {}, {}
-    for name, ms in crecs:
-        ctot[name] = ctot.get(name, 0.0) + ms
-        ccnt[name] = ccnt.get(name, 0) + 1
-    cold_per_launch = {k: ctot[k] / ccnt[k] for k in ctot}
+    cold_us, cold_per_launch = None, {}
+    if not args.no_cold:
+        scrub = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+        cold_us = step_times(dist_steps, scrub)
+        P.pact_profile_enable(True)
+        P.pact_profile_reset()
+        cold_prof_steps = 30
+        for _ in range(cold_prof_steps):
+            scrub.fill_(1)
+            step()
+        torch.cuda.synchronize()
+        crecs = P.pact_profile_read(cold_prof_steps * 64)
+        P.pact_profile_enable(False)
+        del scrub
+        ctot, ccnt = {}, {}
+        for name, ms in crecs:
+            ctot[name] = ctot.get(name, 0.0) + ms
+            ccnt[name] = ccnt.get(name, 0) + 1
+        cold_per_launch = {k: ctot[k] / ccnt[k] for k in ctot}
     pct = lambda a: {"p10": round(float(np.percentile(a, 10)), 2), "p50": round(float(np.percentile(a, 50)), 2),
                      "p90": round(float(np.percentile(a, 90)), 2)}
 
@@ -321,7 +324,7 @@ def main():
                    "rounds": rep["rounds"], "dc_checked_pairs": rep["dc_checked_pairs"]},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "us_per_step_warm": pct(warm_us), "us_per_step_cold": pct(cold_us),
+        "us_per_step_warm": pct(warm_us), "us_per_step_cold": pct(cold_us) if cold_us is not None else None,
         "hbm_stages": hbm_stages,
         "kernels_us_per_step": {k: round(v * 1e3, 2) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
         "kernels_us_per_step_cold": {k: round(v * 1e3, 2) for k, v in sorted(cold_per_launch.items(), key=lambda kv: -kv[1])},
