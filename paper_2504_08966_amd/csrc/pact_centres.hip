@@ -17,78 +17,125 @@ namespace pact {
 
 constexpr int KP = PRED_CAP - 1;   // preceding neighbours kept per token (slot 0 holds the count); more -> bitmap fallback
 
+__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
+    return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
 __device__ __forceinline__ bool precedes(double rho_j, int j, double rho_i, int i) {
     return rho_j > rho_i || (rho_j == rho_i && j < i);
 }
 
-// Nearest of `ncand` candidates (ids in LDS), eight at a time: the wavefront splits into eight
-// groups of 8 lanes, one candidate row each; lane `sub` of a group takes the 16-byte chunks
-// sub, sub + 8, ... of the rows (own row `mine` against the candidate's), eight candidate
-// chunks in flight per lane, fp64 products summed per lane, then over the group.
-// tok_of(c) maps a candidate id to its token; only distances < thr compete; ties go to the
-// lower candidate id.  Updates (best, bestc), identical in every lane.
-// The first eight of a lane's chunks of its own row (chunks sub, sub + 8, ..., sub + 56), read
-// once per token and kept in registers across the candidate batches.
-__device__ __forceinline__ void load_own_chunks(const char* mine, int nchunk, int sub, uint4 (&own)[8]) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int k = sub + 8 * u;
-        own[u] = *(const uint4*)(mine + (size_t)(k < nchunk ? k : sub) * 16);
-    }
-}
-
+// Nearest of `ncand` candidates (ids in LDS) of one token, by one wavefront; only distances
+// < thr compete, ties go to the lower candidate id; (best, bestc) are updated, identical in
+// every lane.  tok_of(c) maps a candidate id to its token.
+//
+// What such a search costs is the conversion of the rows to fp64, so it screens in fp32 first:
+//  1. fp32 cosines of all candidates, eight at a time (the wavefront splits into eight groups
+//     of 8 lanes, one candidate row each; lane `sub` takes the 16-byte chunks sub, sub + 8, ...
+//     of the candidate's row against the token's own, four chunks of either in flight per lane);
+//  2. a candidate whose fp32 cosine is more than 2 * margin below the largest one cannot be the
+//     nearest (margin bounds the error of an fp32 cosine), so only the others - usually one -
+//     are evaluated in fp64, each by the whole wavefront (Eq. 5 as wave_dot64 computes it: a
+//     copy of the token's row is at distance exactly 0);
+//  3. if a single candidate is left, `complete` says that the call sees all candidates of the
+//     token, and its fp32 cosine is more than margin away from the threshold, it is decided
+//     without fp64: `best` is then only a placeholder that no other call will be compared with.
 template <int DT, typename TokOf>
-__device__ __forceinline__ void nearest_candidate(const lds_i32* cand, int ncand, const char* mine,
-                                                  const uint4 (&own)[8], double nnp,
+__device__ __forceinline__ void nearest_candidate(lds_i32* cand, lds_i32* ctok, lds_f32* ccos, int ncand,
+                                                  bool complete, const char* mine, double nnp,
                                                   const char* kb, size_t row_bytes, const double* nnb,
-                                                  int dk, int lane, double thr, TokOf tok_of,
+                                                  int dk, int lane, double thr, float margin, TokOf tok_of,
                                                   double& best, int& bestc) {
     constexpr int EPL = Elem<DT>::EPL;
     const int grp = lane >> 3, sub = lane & 7;
     const int nchunk = dk / EPL;                       // 16-byte chunks per row (rows are 16-byte multiples)
+    // the tokens of all candidates in one round trip (not one per batch of eight)
+    for (int i = lane; i < ncand; i += 64) ctok[i] = tok_of(cand[i]);
+    // 1. fp32 cosines
+    float top = -INFINITY;
     for (int c0 = 0; c0 < ncand; c0 += 8) {
         const int ci = c0 + grp;
         const bool valid = ci < ncand;
-        const int c = cand[valid ? ci : c0];
-        const int tok = tok_of(c);
+        const int tok = ctok[valid ? ci : c0];
         const char* rb = kb + (size_t)tok * row_bytes;
         const double nnc = nnb[tok];
-        double acc = 0.0;
-        for (int k0 = sub; k0 < nchunk; k0 += 64) {    // 8 chunks per lane per pass
-            uint4 vb[8];
+        float acc = 0.0f;
+        for (int k0 = sub; k0 < nchunk; k0 += 32) {    // 4 chunks of either row per lane per pass
+            uint4 vb[4], va[4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 4; ++u) {
                 const int k = k0 + 8 * u;
-                vb[u] = *(const uint4*)(rb + (size_t)(k < nchunk ? k : k0) * 16);
+                const size_t o = (size_t)(k < nchunk ? k : k0) * 16;
+                vb[u] = *(const uint4*)(rb + o);
+                va[u] = *(const uint4*)(mine + o);
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int k = k0 + 8 * u;
-                if (k < nchunk) {
-                    uint4 va = (k0 == sub) ? own[u] : *(const uint4*)(mine + (size_t)k * 16);
-                    // (opaque to the optimiser: it would otherwise widen the cached chunks to
-                    //  fp64 once, outside the candidate loop, and hold 64 doubles per lane)
-                    asm volatile("" : "+v"(va.x), "+v"(va.y), "+v"(va.z), "+v"(va.w));
-                    double a[8], x[8];
-                    Elem<DT>::widen(va, a);
-                    Elem<DT>::widen(vb[u], x);
+            for (int u = 0; u < 4; ++u) {
+                if (k0 + 8 * u < nchunk) {
+                    float a[8], x[8];
+                    Elem<DT>::widenf(va[u], a);
+                    Elem<DT>::widenf(vb[u], x);
 #pragma unroll
-                    for (int i = 0; i < EPL; ++i) acc = fma(a[i], x[i], acc);
+                    for (int i = 0; i < EPL; ++i) acc = fmaf(a[i], x[i], acc);
                 }
             }
         }
 #pragma unroll
         for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
-        double d = cos_dist64(acc, nnp, nnc);
-        int cc = c;
-        if (!valid || !(d < thr)) { d = INFINITY; cc = 0x7FFFFFFF; }
+        const double den = sqrt(nnp * nnc);
+        float cv = den > 0.0 ? (float)((double)acc / den) : 0.0f;
+        if (valid && sub == 0) ccos[ci] = cv;
+        if (!valid) cv = -INFINITY;
 #pragma unroll
-        for (int s = 8; s <= 32; s <<= 1) {
-            const double od = __shfl_xor(d, s, 64);
-            const int oc = __shfl_xor(cc, s, 64);
-            if (od < d || (od == d && oc < cc)) { d = od; cc = oc; }
+        for (int s = 8; s <= 32; s <<= 1) cv = fmaxf(cv, __shfl_xor(cv, s, 64));
+        top = fmaxf(top, cv);
+    }
+    // 2. the candidates that can still be the nearest, compacted in place (order kept)
+    const float floor32 = top - 2.0f * margin;
+    int na = 0;
+    for (int i0 = 0; i0 < ncand; i0 += 64) {
+        const int i = i0 + lane;
+        const bool amb = i < ncand && ccos[i] >= floor32;
+        const int c = amb ? cand[i] : 0, t = amb ? ctok[i] : 0;
+        const uint64_t m = __ballot(amb);
+        if (amb) { cand[na + lanes_below(m, lane)] = c; ctok[na + lanes_below(m, lane)] = t; }
+        na += __popcll(m);
+    }
+    // 3. decided by the fp32 screen alone?
+    const double cthr = 1.0 - thr;                     // d < thr  <=>  cosine > 1 - thr
+    if (complete && na == 1 && (double)top - cthr > (double)margin) {
+        best = fmax(1.0 - (double)top, 0.0);
+        bestc = cand[0];
+        return;
+    }
+    if ((double)top < cthr - (double)margin) return;   // nothing can pass the threshold
+    // fp64 for the rest, two candidates in flight
+    for (int k = 0; k < na; k += 2) {
+        const int k1 = min(k + 1, na - 1);
+        const int c0 = cand[k], c1 = cand[k1];
+        const int t0 = ctok[k], t1 = ctok[k1];
+        const char* r0 = kb + (size_t)t0 * row_bytes;
+        const char* r1 = kb + (size_t)t1 * row_bytes;
+        const double n0 = nnb[t0], n1 = nnb[t1];
+        double a0 = 0.0, a1 = 0.0;
+        for (int e = lane * EPL; e < dk; e += 64 * EPL) {
+            const size_t o = (size_t)e * Elem<DT>::BYTES;
+            const uint4 va = *(const uint4*)(mine + o);
+            const uint4 v0 = *(const uint4*)(r0 + o);
+            const uint4 v1 = *(const uint4*)(r1 + o);
+            double a[8], x[8];
+            Elem<DT>::widen(va, a);
+            Elem<DT>::widen(v0, x);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) a0 = fma(a[i], x[i], a0);
+            Elem<DT>::widen(v1, x);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) a1 = fma(a[i], x[i], a1);
         }
-        if (cc != 0x7FFFFFFF && (d < best || (d == best && cc < bestc))) { best = d; bestc = cc; }
+        const double d0 = cos_dist64(wave_sum_f64(a0), nnp, n0);
+        const double d1 = cos_dist64(wave_sum_f64(a1), nnp, n1);
+        if (d0 < thr && (d0 < best || (d0 == best && c0 < bestc))) { best = d0; bestc = c0; }
+        if (k1 != k && d1 < thr && (d1 < best || (d1 == best && c1 < bestc))) { best = d1; bestc = c1; }
     }
 }
 
@@ -218,9 +265,6 @@ struct BitPop {
         return has;
     }
 };
-__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
-    return __popcll(mask & ((1ull << lane) - 1ull));
-}
 
 // For every kept token: the list of its neighbours (bitmap row) that precede it in the
 // density order, as 16-bit positions in slots 1..KP of its PRED_CAP-slot record; slot 0 holds
@@ -558,9 +602,10 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
                                                       const uint64_t* __restrict__ adj,
                                                       const uint64_t* __restrict__ cmask,
                                                       const uint32_t* __restrict__ status,
-                                                      const int32_t* __restrict__ cnum,
+                                                      const int32_t* __restrict__ cnum, float margin,
                                                       int32_t* cluster_id, int32_t* cluster_counts) {
-    __shared__ int s_cand[4][CAND_BUF];
+    __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
+    __shared__ float s_ccos[4][CAND_BUF];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
@@ -581,9 +626,9 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
         const char* kb = keys + (size_t)sg.base * row_bytes;
         const char* mine = kb + (size_t)tok * row_bytes;
         const double nnp = nnb[tok];
-        uint4 own[8];
-        load_own_chunks(mine, dk / Elem<DT>::EPL, lane & 7, own);
         lds_i32* cand = (lds_i32*)s_cand[wave];
+        lds_i32* ctok = (lds_i32*)s_ctok[wave];
+        lds_f32* ccos = (lds_f32*)s_ccos[wave];
         double best = INFINITY;
         int bestj = 0x7FFFFFFF;
         auto tok_of = [&](int j) { return ix[j]; };
@@ -604,15 +649,15 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
                 nbuf += __popcll(m);
                 ntot += __popcll(m);
                 if (nbuf > CAND_BUF - 64) {
-                    nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
-                                          tok_of, best, bestj);
+                    nearest_candidate<DT>(cand, ctok, ccos, nbuf, false, mine, nnp, kb, row_bytes, nnb, dk,
+                                          lane, INFINITY, margin, tok_of, best, bestj);
                     nbuf = 0;
                 }
             }
         }
         if (ntot == 1) bestj = cand[0];                 // a single centre in reach: no distance needed
-        else if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, INFINITY,
-                                             tok_of, best, bestj);
+        else if (nbuf) nearest_candidate<DT>(cand, ctok, ccos, nbuf, nbuf == ntot, mine, nnp, kb, row_bytes, nnb,
+                                             dk, lane, INFINITY, margin, tok_of, best, bestj);
         cid = bestj != 0x7FFFFFFF ? cn[bestj] : -1;
     }
     if (lane == 0) {
@@ -632,9 +677,10 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
                                                             const int32_t* __restrict__ center_idx,
                                                             const double* __restrict__ nn,
                                                             const uint64_t* __restrict__ adj,
-                                                            int band_unit,
+                                                            int band_unit, float margin,
                                                             int32_t* cluster_id, int32_t* cluster_counts) {
-    __shared__ int s_cand[4][CAND_BUF];
+    __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
+    __shared__ float s_ccos[4][CAND_BUF];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
@@ -658,6 +704,8 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     const int32_t* co = center_idx + sg.base;
     const double thr = (double)sg.alpha * (double)sg.d_c;
     lds_i32* cand = (lds_i32*)s_cand[wave];
+    lds_i32* ctok = (lds_i32*)s_ctok[wave];
+    lds_f32* ccos = (lds_f32*)s_ccos[wave];
     auto tok_of = [&](int c) { return co[c]; };
     const int Wc = (C + 63) >> 6;
     for (int t = t_first; t < t_end; t += t_step) {
@@ -666,11 +714,10 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
         const double nnp = nnb[tok];
         double best = INFINITY;
         int bestc = 0x7FFFFFFF;
-        uint4 own[8];
-        load_own_chunks(mine, dk / Elem<DT>::EPL, lane & 7, own);
         if (thr > 0.0 && C > 0) {
             const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
             int nbuf = 0;
+            bool flushed = false;
             for (int w0 = 0; w0 < Wc; w0 += 64) {
                 const int w = w0 + lane;
                 BitPop bp{(w < Wc) ? row[w] : 0ull};
@@ -683,14 +730,15 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
                     if (ok) cand[nbuf + lanes_below(m, lane)] = c;
                     nbuf += __popcll(m);
                     if (nbuf > CAND_BUF - 64) {
-                        nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
-                                              best, bestc);
+                        nearest_candidate<DT>(cand, ctok, ccos, nbuf, false, mine, nnp, kb, row_bytes, nnb, dk,
+                                              lane, thr, margin, tok_of, best, bestc);
                         nbuf = 0;
+                        flushed = true;
                     }
                 }
             }
-            if (nbuf) nearest_candidate<DT>(cand, nbuf, mine, own, nnp, kb, row_bytes, nnb, dk, lane, thr, tok_of,
-                                            best, bestc);
+            if (nbuf) nearest_candidate<DT>(cand, ctok, ccos, nbuf, !flushed, mine, nnp, kb, row_bytes, nnb, dk,
+                                            lane, thr, margin, tok_of, best, bestc);
         }
         if (lane == 0) {
             const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
@@ -754,10 +802,10 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
                       w.adj, w.rho, w.preds, w.heads, idx, w.status, w.cnum, w.cmask, center_idx);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
-                    w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);
+                    w.adj, w.cmask, w.status, w.cnum, (float)cos_margin(dk), cluster_id, cluster_counts);
     else
         PACT_LAUNCH("assign", assign_kernel<PACT_F32>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
-                    w.adj, w.cmask, w.status, w.cnum, cluster_id, cluster_counts);
+                    w.adj, w.cmask, w.status, w.cnum, (float)cos_margin(dk), cluster_id, cluster_counts);
     return PACT_OK;
 }
 
@@ -776,12 +824,12 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
     dim3 grid(8 * ((band_tokens + 3) / 4), bt.B);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_BF16>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit, cluster_id,
-                    cluster_counts);
+                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit,
+                    (float)cos_margin(dk), cluster_id, cluster_counts);
     else
         PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_F32>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit, cluster_id,
-                    cluster_counts);
+                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit,
+                    (float)cos_margin(dk), cluster_id, cluster_counts);
     if (count_totals)
         PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
                     pruned_idx, cluster_id);

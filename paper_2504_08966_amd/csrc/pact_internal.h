@@ -182,6 +182,7 @@ namespace pact {
 // the pointer travels through function arguments (a generic pointer would give flat_*).
 typedef __attribute__((address_space(3))) volatile unsigned char lds_vu8;
 typedef __attribute__((address_space(3))) int lds_i32;
+typedef __attribute__((address_space(3))) float lds_f32;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
