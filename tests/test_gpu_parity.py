@@ -309,3 +309,94 @@ def test_zero_norm_key_and_equal_scores():
     o = oracle_reduce(s, 0.1, lam=0.5)
     assert_same(g, o, s, "identical tokens")
     assert g["rep"]["n_kept"] == 12 and list(g["center_idx"]) == [0] and list(g["counts"]) == [12]
+
+
+# ------------------------------------------------------------------ targeted cases
+
+def test_nearest_centre_may_come_later_in_the_density_order():
+    # token 0 is denser than centre 7, yet centre 7 is its nearest centre: the assignment
+    # must look at every centre in reach, not only at those that precede the token
+    xy = np.array([[59, 24], [63, 10], [64, 2], [64, 1], [57, 30], [55, 33], [60, 23], [58, 27], [61, 21],
+                   [54, 34], [56, 30], [64, 0]], dtype=np.float32) / 64.0
+    k = np.zeros((12, 1, 8), dtype=np.float32)
+    k[:, 0, :2] = xy
+    s = _mk(k)
+    d_c = 0.004
+    o = po.dbdpc(k.reshape(12, 8).astype(np.float64), float(np.float32(d_c)), 2.0)
+    rank = np.empty(12, dtype=np.int64)
+    rank[o["order"]] = np.arange(12)
+    c0 = o["centers"][o["labels"][0]]
+    assert c0 != 0 and rank[c0] > rank[0]          # the property this case exists for
+    g = gu.gpu_reduce(s, d_c, lam=0.0)
+    assert_same(g, oracle_reduce(s, d_c, lam=0.0), s, "later centre")
+    assert g["center_idx"][g["cluster_id"][0]] == c0
+
+
+@pytest.mark.parametrize("nearer", [0, 1])
+def test_candidates_closer_than_the_fp32_margin_are_decided_in_fp64(nearer):
+    # a pruned token whose two candidate centres differ by ~1e-6 in cosine: far below what an
+    # fp32 cosine can resolve, far above fp64 rounding; the nearer one must win whichever it is
+    k = np.zeros((3, 1, 8), dtype=np.float32)
+    k[0, 0, 0] = 1.0
+    k[1, 0, 1] = 1.0
+    k[2, 0, 0] = 1.0 + (1e-6 if nearer == 0 else 0.0)
+    k[2, 0, 1] = 1.0 + (1e-6 if nearer == 1 else 0.0)
+    h = np.random.default_rng(5).normal(size=(3, 32)).astype(np.float32)
+    h[2] *= 1e-3                # lowest score -> pruned
+    s = _mk(k, hidden=h, queries=np.zeros_like(k))
+    g = gu.gpu_reduce(s, 0.1, alpha=10.0, lam=0.34)
+    o = oracle_reduce(s, 0.1, alpha=10.0, lam=0.34)
+    assert_same(g, o, s, "sub-margin candidates")
+    assert list(g["pruned_idx"]) == [2] and g["cluster_id"][2] == nearer
+
+
+def test_recovery_threshold_within_the_fp32_margin():
+    # distance of the pruned token to its only centre sits 1e-7 on either side of alpha * d_c
+    k = np.zeros((2, 1, 8), dtype=np.float32)
+    k[0, 0, 0] = 1.0
+    k[1, 0, 0], k[1, 0, 1] = 1.0, 0.25
+    h = np.random.default_rng(6).normal(size=(2, 32)).astype(np.float32)
+    h[1] *= 1e-3
+    s = _mk(k, hidden=h, queries=np.zeros_like(k))
+    d = float(po.cosine_distance_matrix(k.reshape(2, 8).astype(np.float64))[0, 1])
+    for delta, joins in [(+1e-7, True), (-1e-7, False)]:
+        d_c = np.float32((d + delta) / 1.5)
+        thr = float(np.float32(1.5)) * float(d_c)
+        if (d < thr) != joins:          # fp32 rounding of d_c moved the threshold across: skip this side
+            continue
+        g = gu.gpu_reduce(s, float(d_c), alpha=1.5, lam=0.5)
+        o = oracle_reduce(s, float(d_c), alpha=1.5, lam=0.5)
+        assert_same(g, o, s, f"threshold {delta:+g}")
+        assert (g["cluster_id"][1] == 0) == joins
+
+
+@pytest.mark.parametrize("name,seed,dtype", [("img_0p5b", 2, "f32"), ("tiny_bf16", 4, "bf16")])
+def test_clustering_on_hidden_states(name, seed, dtype):
+    # DBDPC on the hidden states instead of the keys (the paper's ablation): same kernels at a
+    # much longer contraction (896 / 512 columns here)
+    s = gen.make_sample(name, seed)
+    H = s.hidden.astype(np.float64)
+    D = po.cosine_distance_matrix(H)
+    vals = np.sort(D[np.triu_indices(s.n, 1)])
+    lo = int(0.002 * vals.size)
+    window = vals[lo:lo + 400]
+    gaps = np.diff(window)
+    j = int(np.argmax(gaps))
+    d_c = float(np.float32(0.5 * (window[j] + window[j + 1])))
+    assert min(abs(window[j] - d_c), abs(window[j + 1] - d_c)) > 1e-6
+    ref = po.dbdpc(H, d_c, 2.0)
+    out = P.dbdpc_cluster(gu.dev(s.hidden, dtype), d_c, 2.0)
+    torch.cuda.synchronize()
+    rep = P.read_report(out["rep"])
+    C = rep["n_centers"]
+    assert np.array_equal(out["center_idx"][:C].cpu().numpy(), ref["centers"])
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["labels"])
+    assert 1 < C < s.n
+
+
+def test_calibration_copy_copies():
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    P.pact_calibration_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
