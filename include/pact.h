@@ -78,7 +78,10 @@ typedef enum { PACT_F32 = 0, PACT_BF16 = 1 } pact_dtype;
  * and gives the sequential loop's centres whatever the threshold, so the value is validated
  * and otherwise unused.
  * flags: bit 0 (PACT_FLAG_NO_MERGE) writes the centre token's hidden state instead of the
- * cluster mean (the paper's "no merging" ablation). */
+ * cluster mean (the paper's "no merging" ablation); bits 1 and 2 select the two ablations of
+ * Eq. 2 (Sec. "Ablation study", Table "Ablation Studies on the EUTI-based Visual Token
+ * Pruning"): PACT_FLAG_SCORE_NO_NORM drops the factor |h_i|, PACT_FLAG_SCORE_NORM_ONLY replaces
+ * the softmax term by the constant 1/n, i.e. scores by hidden-state norm alone. */
 typedef struct {
     float lambda;
     float d_c;
@@ -89,6 +92,8 @@ typedef struct {
 } pact_params;
 
 #define PACT_FLAG_NO_MERGE 1u
+#define PACT_FLAG_SCORE_NO_NORM 2u
+#define PACT_FLAG_SCORE_NORM_ONLY 4u
 
 /* Per-sample counters, in DEVICE memory, written by the entry points that produce them. */
 typedef struct {
@@ -114,12 +119,13 @@ size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_
  *   keys_pre [n, n_kv*d_h]    k_dt   keys before rotary embedding, heads concatenated
  *   q        [q_rows, n_q*d_h] q_dt  queries before rotary embedding; q_rows == n (Eq. 1 is
  *                                    applied) or q_rows == 1 (already the global query)
+ *   flags    0, PACT_FLAG_SCORE_NO_NORM and / or PACT_FLAG_SCORE_NORM_ONLY (other bits ignored)
  *   scores   [n] fp32 out
  * n_q must be a multiple of n_kv: query head j reads key head j / (n_q / n_kv).  Softmax is
  * taken across the n tokens inside each head; no 1/sqrt(d_h) factor (Eq. 2 has none). */
 int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
                const void* keys_pre, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
-               const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+               const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q, uint32_t flags,
                float* scores, void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 3/4 (Alg. 1 step 3): tau = the (m+1)-th smallest score, m = min(floor(lambda*n), n-1);

@@ -230,7 +230,8 @@ def merge(H, cluster_id, n_clusters: int):
     return merged, counts
 
 
-def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.float32):
+def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.float32,
+                use_norm: bool = True, use_query: bool = True):
     """Alg. 3: EUTI on (H, K_pre, Q), DBDPC on the flattened K_post of the important
     tokens, recovery of unimportant tokens, merge, position = centre index.
 
@@ -239,7 +240,8 @@ def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.flo
     lam, d_c, d_n, alpha cross the library boundary as float32 and are rounded to it
     here first.  The scores also cross it as float32, so the percentile split is taken
     on the float32-rounded scores (score_dtype), the precision that decision is made
-    in on both sides.
+    in on both sides.  use_norm / use_query select the two ablations of Eq. 2 (see
+    euti_scores).
     """
     lam, d_c, d_n, alpha = (float(np.float32(v)) for v in (lam, d_c, d_n, alpha))
     H = _f64(H)
@@ -247,7 +249,7 @@ def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.flo
     n = H.shape[0]
     U = K_post.reshape(n, -1)
 
-    scores = euti_scores(H, K_pre, Q)
+    scores = euti_scores(H, K_pre, Q, use_norm=use_norm, use_query=use_query)
     s_dec = scores.astype(score_dtype)
     kept, pruned, tau = percentile_split(s_dec, lam)
 

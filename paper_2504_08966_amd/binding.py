@@ -10,6 +10,8 @@ import torch
 
 PACT_F32, PACT_BF16 = 0, 1
 PACT_FLAG_NO_MERGE = 1
+PACT_FLAG_SCORE_NO_NORM = 2
+PACT_FLAG_SCORE_NORM_ONLY = 4
 REPORT_FIELDS = ("n_kept", "n_pruned", "n_centers", "n_reincorporated", "n_dropped", "rounds",
                  "dc_checked_pairs", "dc_near_ties", "refine_overflow", "zero_norm_seen")
 REPORT_INTS = 16
@@ -59,7 +61,7 @@ def load_library():
     lib.pact_workspace_bytes.argtypes = [i32] * 5
     lib.pact_score.restype = C.c_int
     lib.pact_score.argtypes = [vp, C.c_int, i32, i32, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
-                               vp, vp, sz, vp]
+                               C.c_uint32, vp, vp, sz, vp]
     lib.pact_prune.restype = C.c_int
     lib.pact_prune.argtypes = [vp, i32, f32, vp, vp, vp, vp, sz, vp]
     lib.dbdpc_cluster.restype = C.c_int
@@ -141,12 +143,12 @@ def read_report(rep: torch.Tensor):
     return out[0] if len(out) == 1 else out
 
 
-def pact_score(hidden, keys_pre, q, n_kv: int, d_h: int, n_q: int, ws=None):
+def pact_score(hidden, keys_pre, q, n_kv: int, d_h: int, n_q: int, ws=None, flags: int = 0):
     n, h = hidden.shape
     ws = ws if ws is not None else alloc_workspace(n, 1, n_kv * d_h, n_q, d_h, hidden.device)
     scores = torch.empty(n, dtype=torch.float32, device=hidden.device)
     _check(load_library().pact_score(_p(hidden), _dt(hidden), n, h, _p(keys_pre), _dt(keys_pre), n_kv, d_h,
-                                     _p(q), _dt(q), q.shape[0], n_q, _p(scores), _p(ws), ws.numel(),
+                                     _p(q), _dt(q), q.shape[0], n_q, flags, _p(scores), _p(ws), ws.numel(),
                                      _stream()), "pact_score")
     return scores
 

@@ -130,7 +130,7 @@ size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_
 
 int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
                const void* keys_pre, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
-               const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+               const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q, uint32_t flags,
                float* scores, void* ws, size_t ws_bytes, void* stream) {
     if (!scores) return PACT_ERR_NULL;
     if (n < 1 || n > PACT_MAX_TOKENS || n_kv < 1 || d_h < 1 || n_q < 1 || n_q > PACT_MAX_QHEADS ||
@@ -147,7 +147,9 @@ int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     Batch bt;
-    fill_single(bt, n, default_params());
+    pact_params sp = default_params();
+    sp.flags = flags & (PACT_FLAG_SCORE_NO_NORM | PACT_FLAG_SCORE_NORM_ONLY);
+    fill_single(bt, n, sp);
     const Ws w = resolve(ws, L);
     hipStream_t st = (hipStream_t)stream;
     ScoreIn si{hidden, h_dt, h, keys_pre, k_dt, n_kv, d_h, q, q_dt, q_rows == n ? 1 : 0, n_q};

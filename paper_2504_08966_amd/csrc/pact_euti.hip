@@ -288,9 +288,14 @@ __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= sg.n) return;
     const size_t g = (size_t)sg.base + i;
-    double acc = 0.0;
-    for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
-    scores[g] = (float)(hnorm[g] * (acc / (double)n_q));
+    // the two ablations of Eq. 2: without the norm; norm only (softmax term -> 1/n)
+    double p = 1.0 / (double)sg.n;
+    if (!(sg.flags & PACT_FLAG_SCORE_NORM_ONLY)) {
+        double acc = 0.0;
+        for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
+        p = acc / (double)n_q;
+    }
+    scores[g] = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hnorm[g] * p);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -339,9 +344,13 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
         __syncthreads();
         for (int i = tid; i < n; i += 1024) {
             const size_t g = (size_t)sg.base + i;
-            double acc = 0.0;
-            for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
-            const float v = (float)(hnorm[g] * (acc / (double)n_q));
+            double p = 1.0 / (double)n;
+            if (!(sg.flags & PACT_FLAG_SCORE_NORM_ONLY)) {
+                double acc = 0.0;
+                for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
+                p = acc / (double)n_q;
+            }
+            const float v = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hnorm[g] * p);
             s[i] = v;
             s_key[i] = ordered_key(v);
         }

@@ -59,7 +59,7 @@ def test_argument_validation_is_host_side():
     # pact_score
     sc = lambda **k: lib.pact_score(k.get("hidden", fake), k.get("h_dt", 0), k.get("n", 16), k.get("h", 64),
                                     fake, k.get("k_dt", 0), k.get("n_kv", 2), k.get("d_h", 8), fake, 0,
-                                    k.get("q_rows", 16), k.get("n_q", 2), k.get("scores", fake),
+                                    k.get("q_rows", 16), k.get("n_q", 2), 0, k.get("scores", fake),
                                     k.get("ws", fake), k.get("ws_bytes", ws_bytes), None)
     assert sc(hidden=None) == NULL and sc(scores=None) == NULL
     assert sc(n=0) == SHAPE and sc(n_q=3) == SHAPE and sc(q_rows=5) == SHAPE and sc(n=1 << 20) == SHAPE

@@ -17,8 +17,8 @@ def rtol_for(cfg):
     return 1e-3 if "bf16" in (cfg.key_dtype, cfg.hidden_dtype) else 1e-5
 
 
-def oracle_reduce(s, d_c, d_n=2.0, alpha=1.5, lam=None):
-    return po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam if lam is None else lam, d_c, d_n, alpha)
+def oracle_reduce(s, d_c, d_n=2.0, alpha=1.5, lam=None, **kw):
+    return po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam if lam is None else lam, d_c, d_n, alpha, **kw)
 
 
 def assert_same(g, o, s, what=""):
@@ -400,3 +400,26 @@ def test_calibration_copy_copies():
     P.pact_calibration_copy(dst, src)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+
+
+@pytest.mark.parametrize("name,seed", [("tiny_f32", 5), ("tiny_bf16", 6)])
+def test_score_ablations_of_eq2(name, seed):
+    # "EUTI w/o norm" and "norm only": stand-alone scores and the full reduction under each flag
+    s = gen.make_sample(name, seed)
+    d = gu.sample_to_dev(s)
+    cfg = s.config
+    d_c = gu.d_c_of(s)
+    tol = rtol_for(cfg)
+    for flags, kw in [(P.PACT_FLAG_SCORE_NO_NORM, dict(use_norm=False)),
+                      (P.PACT_FLAG_SCORE_NORM_ONLY, dict(use_query=False)),
+                      (P.PACT_FLAG_SCORE_NO_NORM | P.PACT_FLAG_SCORE_NORM_ONLY, dict(use_norm=False, use_query=False))]:
+        sc = P.pact_score(d["hidden"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, cfg.n_kv, flags=flags)
+        torch.cuda.synchronize()
+        ref = po.euti_scores(s.hidden, s.keys, s.queries, **kw)
+        np.testing.assert_allclose(sc.cpu().numpy(), ref, rtol=tol, atol=0)
+        g = gu.gpu_reduce(s, d_c, flags=flags)
+        o = oracle_reduce(s, d_c, **kw)
+        assert_same(g, o, s, f"flags={flags}")
+    # without the norm the scores are a mean of softmaxes over the tokens: they sum to one
+    sc = P.pact_score(d["hidden"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, cfg.n_kv, flags=P.PACT_FLAG_SCORE_NO_NORM)
+    assert abs(float(sc.double().sum()) - 1.0) < 1e-5
