@@ -230,6 +230,17 @@ def merge(H, cluster_id, n_clusters: int):
     return merged, counts
 
 
+def attention_handoff(center_idx, counts, positions=None):
+    """What the layers after the reduction need besides H' (Alg. 3 last loop, Eq. 11):
+    the position id of every merged token, p'_s = p_s of its cluster centre, and the
+    additive attention term log W of proportional attention, log of the cluster sizes
+    (a text token would carry log 1 = 0).  positions=None means p_i = i."""
+    center_idx = np.asarray(center_idx, dtype=np.int64)
+    counts = np.asarray(counts, dtype=np.int64)
+    pos = center_idx.copy() if positions is None else np.asarray(positions)[center_idx]
+    return pos, np.log(counts.astype(F64))
+
+
 def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.float32,
                 use_norm: bool = True, use_query: bool = True):
     """Alg. 3: EUTI on (H, K_pre, Q), DBDPC on the flattened K_post of the important

@@ -411,3 +411,22 @@ def test_generator_casts_are_exact_and_seeded():
     assert np.array_equal(back, a.keys)
     x = np.array([1.0, 1.00390625, 1.005859375, 1.001953125, -3.3895313892515355e38], dtype=np.float32)
     assert np.array_equal(gen.round_to_bf16(x)[:4], np.array([1.0, 1.0, 1.0078125, 1.0], dtype=np.float32))
+
+
+def test_attention_handoff_positions_and_weights():
+    # Eq. 11 / Alg. 3: positions are the centres' own, log-weights are logs of cluster sizes
+    cen = np.array([2, 5, 11])
+    cnt = np.array([1, 4, 7])
+    P = np.arange(100, 120) * 3
+    pos, lw = po.attention_handoff(cen, cnt, P)
+    assert list(pos) == [102 * 3, 105 * 3, 111 * 3]
+    assert lw[0] == 0.0 and abs(lw[1] - 2 * math.log(2.0)) < 1e-15 and abs(math.exp(lw[2]) - 7.0) < 1e-12
+    pos0, _ = po.attention_handoff(cen, cnt)
+    assert list(pos0) == [2, 5, 11]
+    # on a real reduction: weights sum to the number of tokens that survive in some cluster,
+    # positions ascend (cluster ids follow the centres' token order)
+    s = gen.make_sample("tiny_f32", 3)
+    r = po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, 0.05, 2.0, 1.5)
+    pos, lw = po.attention_handoff(r["center_idx"], r["counts"])
+    assert np.all(np.diff(pos) > 0)
+    assert round(float(np.exp(lw).sum())) == s.n - r["n_dropped"]
