@@ -203,6 +203,19 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
                        int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
                        pact_report* rep, void* ws, size_t ws_bytes, void* stream);
 
+/* What the layers after the reduction need besides the merged tokens (Alg. 3 last loop, Eq. 11):
+ * the position id of merged token s, p'_s = positions[center_idx[s]] (the centre's own), and
+ * the additive attention term of proportional attention, log_weight[s] = ln(cluster_counts[s]).
+ * One sample, or `batch` samples laid out by cu_seqlens as in pact_reduce_varlen.
+ *   center_idx, cluster_counts  as pact_reduce left them; entries 0..rep[b].n_centers-1 are read
+ *   positions      [total] int32 position ids of the input tokens, or NULL for p_i = i (local)
+ *   cu_seqlens     host, [batch+1], or NULL with batch == 1 and n tokens
+ *   positions_out  [total] int32 out, log_weight [total] fp32 out: entries 0..n_centers-1 of
+ *                  each sample are written */
+int pact_attention_handoff(const int32_t* center_idx, const int32_t* cluster_counts, const pact_report* rep,
+                           const int32_t* positions, const int32_t* cu_seqlens, int32_t batch, int32_t n,
+                           int32_t* positions_out, float* log_weight, void* stream);
+
 /* Optional per-kernel timing (for benchmarks; Sec. "Algo. Time" is what it decomposes).
  * While enabled, every kernel the library enqueues is bracketed by events on its stream.
  * pact_profile_read synchronises those events and returns the number of records since the

@@ -78,6 +78,8 @@ def load_library():
     lib.pact_reduce_varlen.argtypes = [vp, C.c_int, i32, vp, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
                                        C.POINTER(i32), i32, C.POINTER(_Params), vp, vp, vp, vp, vp, vp,
                                        C.c_int, vp, vp, vp, sz, vp]
+    lib.pact_attention_handoff.restype = C.c_int
+    lib.pact_attention_handoff.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, vp, vp, vp]
     lib.pact_calibration_copy.restype = C.c_int
     lib.pact_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.pact_profile_enable.restype = C.c_int
@@ -245,6 +247,24 @@ def pact_reduce_varlen(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int,
         _p(o["center_idx"]), _p(o["cluster_id"]), _p(o["merged"]), _out_dt(o["merged"].dtype),
         _p(o["cluster_counts"]), _p(o["rep"]), _p(ws), ws.numel(), _stream()), "pact_reduce_varlen")
     return o
+
+
+def pact_attention_handoff(center_idx, cluster_counts, rep, positions=None, cu_seqlens=None):
+    """Positions of the merged tokens (their centres') and log cluster sizes (Eq. 11); entries
+    0..n_centers-1 of each sample are written."""
+    total = center_idx.numel()
+    dev = center_idx.device
+    pos_out = torch.zeros(total, dtype=torch.int32, device=dev)
+    logw = torch.zeros(total, dtype=torch.float32, device=dev)
+    if cu_seqlens is None:
+        cu, batch = None, 1
+    else:
+        batch = len(cu_seqlens) - 1
+        cu = (C.c_int32 * (batch + 1))(*cu_seqlens)
+    _check(load_library().pact_attention_handoff(_p(center_idx), _p(cluster_counts), _p(rep), _p(positions), cu,
+                                                 batch, total, _p(pos_out), _p(logw), _stream()),
+           "pact_attention_handoff")
+    return pos_out, logw
 
 
 def pact_calibration_copy(dst, src):

@@ -343,6 +343,30 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
     return run_reduce(bt, w, io, (hipStream_t)stream);
 }
 
+int pact_attention_handoff(const int32_t* center_idx, const int32_t* cluster_counts, const pact_report* rep,
+                           const int32_t* positions, const int32_t* cu_seqlens, int32_t batch, int32_t n,
+                           int32_t* positions_out, float* log_weight, void* stream) {
+    if (!center_idx || !cluster_counts || !rep || !positions_out || !log_weight) return PACT_ERR_NULL;
+    if (batch < 1 || batch > PACT_MAX_BATCH) return PACT_ERR_SHAPE;
+    if (!cu_seqlens && batch != 1) return PACT_ERR_NULL;
+    Batch bt;
+    std::memset(&bt, 0, sizeof(bt));
+    int32_t n_max = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int64_t base = cu_seqlens ? cu_seqlens[b] : 0;
+        const int64_t nb = cu_seqlens ? (int64_t)cu_seqlens[b + 1] - cu_seqlens[b] : n;
+        if (nb < 1 || nb > PACT_MAX_TOKENS || base < 0 || (cu_seqlens && b == 0 && base != 0)) return PACT_ERR_SHAPE;
+        bt.s[b].base = (int32_t)base; bt.s[b].n = (int32_t)nb;
+        if (nb > n_max) n_max = (int32_t)nb;
+    }
+    bt.B = batch; bt.n_max = n_max; bt.W = (n_max + 63) / 64;
+    bt.total = cu_seqlens ? cu_seqlens[batch] : n;
+    int rc;
+    if ((rc = check_device())) return rc;
+    return launch_handoff(bt, center_idx, cluster_counts, rep, positions, positions_out, log_weight,
+                          (hipStream_t)stream);
+}
+
 int pact_profile_enable(int on) {
     g_prof_on = on != 0;
     return PACT_OK;

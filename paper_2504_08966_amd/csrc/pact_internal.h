@@ -164,6 +164,10 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
                  hipStream_t st);
 
+int launch_handoff(const Batch& bt, const int32_t* center_idx, const int32_t* cluster_counts,
+                   const pact_report* rep, const int32_t* positions, int32_t* positions_out,
+                   float* log_weight, hipStream_t st);
+
 // init modes
 enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_SCORE = 4 };
 

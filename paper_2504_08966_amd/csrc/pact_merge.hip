@@ -200,6 +200,32 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
     return PACT_OK;
 }
 
+// Positions and proportional-attention weights of the merged tokens (Alg. 3 last loop, Eq. 11).
+// grid (ceil(n_max/256), B), block 256.
+__global__ __launch_bounds__(256) void handoff_kernel(Batch bt, const int32_t* __restrict__ center_idx,
+                                                       const int32_t* __restrict__ cluster_counts,
+                                                       const pact_report* __restrict__ rep,
+                                                       const int32_t* __restrict__ positions,
+                                                       int32_t* __restrict__ positions_out,
+                                                       float* __restrict__ log_weight) {
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int C = clamp_count(rep[b].n_centers, sg.n);
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    const int tok = center_idx[sg.base + c];
+    positions_out[sg.base + c] = positions ? positions[sg.base + tok] : tok;
+    log_weight[sg.base + c] = (float)log((double)cluster_counts[sg.base + c]);
+}
+
+int launch_handoff(const Batch& bt, const int32_t* center_idx, const int32_t* cluster_counts,
+                   const pact_report* rep, const int32_t* positions, int32_t* positions_out,
+                   float* log_weight, hipStream_t st) {
+    PACT_LAUNCH("handoff", handoff_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt, center_idx,
+                cluster_counts, rep, positions, positions_out, log_weight);
+    return PACT_OK;
+}
+
 int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
                  const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,

@@ -423,3 +423,43 @@ def test_score_ablations_of_eq2(name, seed):
     # without the norm the scores are a mean of softmaxes over the tokens: they sum to one
     sc = P.pact_score(d["hidden"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, cfg.n_kv, flags=P.PACT_FLAG_SCORE_NO_NORM)
     assert abs(float(sc.double().sum()) - 1.0) < 1e-5
+
+
+def test_attention_handoff_matches_oracle():
+    s = gen.make_sample("tiny_bf16", 7)
+    cfg = s.config
+    d = gu.sample_to_dev(s)
+    d_c = gu.d_c_of(s)
+    prm = P.PactParams(s.lam, d_c, 2.0, 1.5)
+    o = P.pact_reduce(d["hidden"], d["keys"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, cfg.n_kv, prm)
+    ref = oracle_reduce(s, d_c)
+    C = len(ref["center_idx"])
+    positions = torch.arange(1000, 1000 + s.n, dtype=torch.int32, device="cuda") * 2
+    for pos_in in (None, positions):
+        pos, logw = P.pact_attention_handoff(o["center_idx"], o["cluster_counts"], o["rep"], pos_in)
+        torch.cuda.synchronize()
+        rp, rl = po.attention_handoff(ref["center_idx"], ref["counts"],
+                                      None if pos_in is None else pos_in.cpu().numpy())
+        assert np.array_equal(pos[:C].cpu().numpy(), rp)
+        np.testing.assert_allclose(logw[:C].cpu().numpy(), rl, rtol=1e-6, atol=0)
+    # ragged batch
+    samples = gen.make_varlen_batch(1, batch=3)
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), "bf16")
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "bf16")
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "bf16")
+    c0 = samples[0].config
+    prms = [P.PactParams(sm.lam, 0.02, 2.0, 1.5) for sm in samples]
+    ob = P.pact_reduce_varlen(hid, ks, ks, qs, c0.n_kv, c0.d_h, c0.n_kv, cu, prms)
+    pos, logw = P.pact_attention_handoff(ob["center_idx"], ob["cluster_counts"], ob["rep"], None, cu)
+    torch.cuda.synchronize()
+    reps = P.read_report(ob["rep"])
+    for b, sm in enumerate(samples):
+        Cb = reps[b]["n_centers"]
+        cen = ob["center_idx"][cu[b]:cu[b] + Cb].cpu().numpy()
+        cnt = ob["cluster_counts"][cu[b]:cu[b] + Cb].cpu().numpy()
+        rp, rl = po.attention_handoff(cen, cnt)
+        assert np.array_equal(pos[cu[b]:cu[b] + Cb].cpu().numpy(), rp)
+        np.testing.assert_allclose(logw[cu[b]:cu[b] + Cb].cpu().numpy(), rl, rtol=1e-6, atol=0)
