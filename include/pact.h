@@ -81,7 +81,9 @@ typedef enum { PACT_F32 = 0, PACT_BF16 = 1 } pact_dtype;
  * cluster mean (the paper's "no merging" ablation); bits 1 and 2 select the two ablations of
  * Eq. 2 (Sec. "Ablation study", Table "Ablation Studies on the EUTI-based Visual Token
  * Pruning"): PACT_FLAG_SCORE_NO_NORM drops the factor |h_i|, PACT_FLAG_SCORE_NORM_ONLY replaces
- * the softmax term by the constant 1/n, i.e. scores by hidden-state norm alone. */
+ * the softmax term by the constant 1/n, i.e. scores by hidden-state norm alone;
+ * bit 3 (PACT_FLAG_KEY_STATS) makes pact_reduce fill pact_report.max_key_distance (0 otherwise;
+ * dbdpc_cluster always fills it). */
 typedef struct {
     float lambda;
     float d_c;
@@ -94,6 +96,7 @@ typedef struct {
 #define PACT_FLAG_NO_MERGE 1u
 #define PACT_FLAG_SCORE_NO_NORM 2u
 #define PACT_FLAG_SCORE_NORM_ONLY 4u
+#define PACT_FLAG_KEY_STATS 8u
 
 /* Per-sample counters, in DEVICE memory, written by the entry points that produce them. */
 typedef struct {
@@ -107,7 +110,9 @@ typedef struct {
     int32_t dc_near_ties;      /* of those, pairs with |d - d_c| <= 1e-6 (each pair counted twice) */
     int32_t refine_overflow;   /* 1 if the near-d_c list overflowed (pairs then keep fp32 decisions) */
     int32_t zero_norm_seen;    /* kept or pruned tokens with a zero-norm clustering key */
-    int32_t reserved[6];
+    float   max_key_distance;  /* largest Eq. 5 distance between two clustered keys, from the fp32 pass
+                                * (the statistic Sec. "Selecting the layer L" looks at)  (dbdpc_cluster) */
+    int32_t reserved[5];
 } pact_report;
 
 /* Scratch bytes needed for one call on samples of at most n_max tokens each, `batch`

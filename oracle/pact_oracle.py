@@ -230,6 +230,14 @@ def merge(H, cluster_id, n_clusters: int):
     return merged, counts
 
 
+def max_pairwise_distance(U) -> float:
+    """The statistic Sec. "Selecting the layer L" (and the figure on the maximum distance
+    between keys) looks at: the largest Eq. 5 distance between two of the vectors; 0 for a
+    single vector."""
+    D = cosine_distance_matrix(U)
+    return float(D.max()) if D.shape[0] > 1 else 0.0
+
+
 def attention_handoff(center_idx, counts, positions=None):
     """What the layers after the reduction need besides H' (Alg. 3 last loop, Eq. 11):
     the position id of every merged token, p'_s = p_s of its cluster centre, and the

@@ -12,6 +12,7 @@ PACT_F32, PACT_BF16 = 0, 1
 PACT_FLAG_NO_MERGE = 1
 PACT_FLAG_SCORE_NO_NORM = 2
 PACT_FLAG_SCORE_NORM_ONLY = 4
+PACT_FLAG_KEY_STATS = 8
 REPORT_FIELDS = ("n_kept", "n_pruned", "n_centers", "n_reincorporated", "n_dropped", "rounds",
                  "dc_checked_pairs", "dc_near_ties", "refine_overflow", "zero_norm_seen")
 REPORT_INTS = 16
@@ -140,8 +141,12 @@ def new_report(batch: int = 1, device="cuda") -> torch.Tensor:
 
 def read_report(rep: torch.Tensor):
     """Host copy of the device-side report(s) (synchronises the current stream)."""
-    h = rep.cpu().tolist()
+    hc = rep.cpu()
+    h = hc.tolist()
     out = [dict(zip(REPORT_FIELDS, row)) for row in h]
+    fl = hc.view(torch.float32)
+    for b, d in enumerate(out):
+        d["max_key_distance"] = float(fl[b, len(REPORT_FIELDS)])
     return out[0] if len(out) == 1 else out
 
 

@@ -100,9 +100,13 @@ static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStrea
     if ((rc = launch_score_only(bt, w, io.n_q, io.scores, st))) return rc;
     if ((rc = launch_score_prune(bt, w, io.n_q, true, io.scores, io.kept_idx, io.pruned_idx, io.rep, st)))
         return rc;
-    if ((rc = launch_gram_density(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.rep, st))) return rc;
+    bool want_stat = false;                  // the key-distance statistic: only if a sample asks for it
+    for (int b = 0; b < bt.B; ++b) want_stat = want_stat || (bt.s[b].flags & PACT_FLAG_KEY_STATS);
+    int stat_words = 0;
+    if ((rc = launch_gram_density(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.rep, want_stat, &stat_words, st)))
+        return rc;
     if ((rc = launch_centres(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.center_idx, io.cluster_id,
-                             io.cluster_counts, io.rep, nullptr, nullptr, st))) return rc;
+                             io.cluster_counts, io.rep, nullptr, nullptr, stat_words, st))) return rc;
     if ((rc = launch_reincorporate(bt, w, io.keys, io.k_dt, dk, io.pruned_idx, io.center_idx,
                                    io.cluster_id, io.cluster_counts, io.rep, false, st))) return rc;
     return launch_merge(bt, w, io.hidden, io.h_dt, io.h, io.cluster_id, io.center_idx, io.rep, io.merged,
@@ -205,9 +209,10 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if ((rc = launch_prep(bt, w, keys, k_dt, dk, nullptr, PACT_F32, 0, rep, cluster_id, nullptr,
                           idx ? INIT_DBDPC_SUBSET : INIT_DBDPC_ALL, n_idx_dev, st))) return rc;
     const int32_t* use_idx = idx ? idx : w.ident;
-    if ((rc = launch_gram_density(bt, w, keys, k_dt, dk, use_idx, rep, st))) return rc;
+    int stat_words = 0;
+    if ((rc = launch_gram_density(bt, w, keys, k_dt, dk, use_idx, rep, true, &stat_words, st))) return rc;
     return launch_centres(bt, w, keys, k_dt, dk, use_idx, center_idx, cluster_id, nullptr, rep, rho_opt,
-                          rank_opt, st);
+                          rank_opt, stat_words, st);
 }
 
 int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,

@@ -154,6 +154,7 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
                                                          const double* __restrict__ nn,
                                                          const uint32_t* __restrict__ near_list,
                                                          const int32_t* __restrict__ near_cnt,
+                                                         const uint32_t* __restrict__ far_bits, int far_words,
                                                          uint64_t* adj, pact_report* rep,
                                                          const double* __restrict__ rho_part,
                                                          double* __restrict__ rho, double* rho_opt) {
@@ -168,9 +169,18 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
         const int nw = REFINE_BLOCKS * 4;
         const int raw = near_cnt[b];
         const int cnt = min(raw, NEAR_CAP);
-        if (gw == 0 && lane == 0) {
-            rep[b].dc_checked_pairs = cnt;
-            rep[b].refine_overflow = raw > NEAR_CAP;
+        if (gw == 0) {
+            // largest key distance: the wavefronts of the density pass each left the bits of their
+            // most negative exponent -(d / d_n) log2(e); negative floats order like those bits
+            uint32_t fb = 0u;
+            for (int k = lane; k < far_words; k += 64) fb = max(fb, far_bits[(size_t)b * far_words + k]);
+#pragma unroll
+            for (int sft = 32; sft >= 1; sft >>= 1) fb = max(fb, (uint32_t)__shfl_xor((int)fb, sft, 64));
+            if (lane == 0) {
+                rep[b].dc_checked_pairs = cnt;
+                rep[b].refine_overflow = raw > NEAR_CAP;
+                rep[b].max_key_distance = fb ? fminf(-__uint_as_float(fb) * sg.d_n * 0.6931471805599453f, 2.0f) : 0.0f;
+            }
         }
         const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
         const char* kb = keys + (size_t)sg.base * row_bytes;
@@ -774,15 +784,15 @@ __global__ __launch_bounds__(1024) void count_recovered_kernel(Batch bt, pact_re
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
-                   hipStream_t st) {
+                   int stat_words, hipStream_t st) {
     const char* k = (const char*)keys;
     dim3 gpost(REFINE_BLOCKS + (bt.n_max + 63) / 64, bt.B);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("post_gram", post_gram_kernel<PACT_BF16>, gpost, dim3(256), st, bt, k, dk, idx, w.nn,
-                    w.near_list, w.near_cnt, w.adj, rep, w.rho_part, w.rho, rho_opt);
+                    w.near_list, w.near_cnt, w.stat, stat_words, w.adj, rep, w.rho_part, w.rho, rho_opt);
     else
         PACT_LAUNCH("post_gram", post_gram_kernel<PACT_F32>, gpost, dim3(256), st, bt, k, dk, idx, w.nn,
-                    w.near_list, w.near_cnt, w.adj, rep, w.rho_part, w.rho, rho_opt);
+                    w.near_list, w.near_cnt, w.stat, stat_words, w.adj, rep, w.rho_part, w.rho, rho_opt);
     if (rank_opt)
         PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
                     w.rho, rank_opt);

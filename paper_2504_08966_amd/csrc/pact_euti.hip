@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
                 rp->n_centers = 0; rp->rounds = 0; rp->dc_checked_pairs = 0; rp->dc_near_ties = 0;
                 rp->refine_overflow = 0; rp->n_reincorporated = 0; rp->n_dropped = 0;
                 rp->zero_norm_seen = 0;     // counted by the assignment kernels, which run later
-                for (int k = 0; k < 6; ++k) rp->reserved[k] = 0;
+                rp->max_key_distance = 0.0f;
+                for (int k = 0; k < 5; ++k) rp->reserved[k] = 0;
             }
             if (mode == INIT_REINC) { rp->n_reincorporated = 0; rp->n_dropped = 0; }
         }

@@ -53,6 +53,8 @@ struct GramArgs {
     double* rho_part;          // [B][W][n_max], one row per GRAM_RHO_ROWS kept rows
     uint32_t* near_list;       // [B][NEAR_CAP][2]
     int32_t* near_cnt;         // [B]
+    uint32_t* stat;            // [B][gridDim.x * 8] per wavefront: bits of the most negative density exponent
+                               // it saw (largest distance), or NULL when the statistic is not wanted
     float margin;              // worst-case fp32 error of a cosine
 };
 
@@ -117,7 +119,7 @@ template <> struct Mfma<PACT_F32> {
     }
 };
 
-template <int DT, int MODE, int MI>
+template <int DT, int MODE, int MI, bool STAT>
 __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     typedef Shape<MI> SH;
     constexpr int TILE_R = SH::TILE_R, STAGE_BYTES = SH::STAGE_BYTES, NSTAGE = SH::NSTAGE;
@@ -129,7 +131,11 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int nA = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_pruned, sg.n - q_kept);
     const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_centers, q_kept);
     const int row_off = (MODE == MODE_DENSITY) ? 0 : q_kept;   // candidate rows follow the kept rows
-    if (nA <= 0 || nB <= 0) return;
+    if (nA <= 0 || nB <= 0) {
+        if (STAT && (threadIdx.x & 63) == 0)
+            ga.stat[((size_t)b * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)] = 0u;
+        return;
+    }
     PACT_STAMP(0);
     const int tilesR = (nA + TILE_R - 1) / TILE_R;
     const int tilesC = (nB + TILE_C - 1) / TILE_C;
@@ -185,6 +191,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int t_first = l_lo + (banded ? (int)(blockIdx.x >> 3) : (int)blockIdx.x);
     const int t_step = banded ? (int)(gridDim.x >> 3) : (int)gridDim.x;
 
+    float far = 0.0f;              // most negative density exponent seen = largest distance (density pass)
     for (int tl = t_first; tl < l_hi; tl += t_step) {
         const int rowBase = ((MODE == MODE_DENSITY) ? tl % tilesR : tl / tilesC) * TILE_R;
         const int colBase = ((MODE == MODE_DENSITY) ? tl / tilesR : tl % tilesC) * TILE_C;
@@ -351,6 +358,22 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             float mx = fmaxf(acc[i][0][0], acc[i][1][0]);
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(acc[i][0][r], acc[i][1][r]));
+            if (STAT) {
+                // the block's smallest exponent (largest distance); padded rows hold -inf and are
+                // left out (padded columns repeat a real column: harmless)
+                if (rowI + 32 <= nA) {
+                    float mn = fminf(acc[i][0][0], acc[i][1][0]);
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) mn = fminf(mn, fminf(acc[i][0][r], acc[i][1][r]));
+                    far = fminf(far, mn);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const bool pad = rowI + 8 * (r >> 2) + 4 * hh + (r & 3) >= nA;
+                        far = fminf(far, pad ? 0.0f : fminf(acc[i][0][r], acc[i][1][r]));
+                    }
+                }
+            }
             if (__ballot(mx >= t_lo) == 0) continue;
             // Ballots put the 64 columns of two rows (hh = 0 / 1) into a scalar pair; v_writelane
             // files each half under the lane of its row, so that lane k < 32 ends up holding the
@@ -425,11 +448,18 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             __syncthreads();
         }
     }
+    if (STAT) {
+        // one word per wavefront, no atomics (thousands of them on one address would take longer
+        // than the kernel); the kernel that finishes the densities takes the minimum
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) far = fminf(far, __shfl_xor(far, sft, 64));
+        if (lane == 0) ga.stat[((size_t)b * gridDim.x + blockIdx.x) * 8 + wave] = far < 0.0f ? __float_as_uint(far) : 0u;
+    }
 }
 
-template <int MODE, int MI>
+template <int MODE, int MI, bool STAT>
 static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                             const char* name) {
+                             const char* name, int* grid_out) {
     typedef Shape<MI> SH;
     const int tilesR = (bt.n_max + SH::TILE_R - 1) / SH::TILE_R, tilesC = (bt.n_max + TILE_C - 1) / TILE_C;
     int grid_x = tilesR * tilesC;
@@ -437,41 +467,49 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
     if (grid_x > cap) grid_x = cap;
     if (grid_x >= 8) grid_x &= ~7;                // a multiple of the 8 XCDs (see the tile order)
     dim3 grid(grid_x, bt.B);
+    if (grid_out) *grid_out = grid_x;
     const size_t lds = SH::LDS_BYTES;
     static bool raised[2] = {false, false};
     const int di = k_dt == PACT_BF16 ? 1 : 0;
-    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI>
-                                         : (const void*)gram_kernel<PACT_F32, MODE, MI>;
+    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI, STAT>
+                                         : (const void*)gram_kernel<PACT_F32, MODE, MI, STAT>;
     if (!raised[di]) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PACT_ERR_HIP;
         raised[di] = true;
     }
     if (k_dt == PACT_BF16)
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI, STAT>), grid, dim3(512), lds, st, bt, ga);
     else
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI, STAT>), grid, dim3(512), lds, st, bt, ga);
     return PACT_OK;
 }
 
 // 256 x 256 tiles when there are enough of them to occupy the chip, else 128 x 256.
 template <int MODE>
 static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                       const char* name, long tiles256, int* tile_rows) {
+                       const char* name, long tiles256, int* tile_rows, int* grid_out) {
     const bool big = tiles256 * bt.B >= 256;
     if (tile_rows) *tile_rows = big ? Shape<4>::TILE_R : Shape<2>::TILE_R;
-    if (big) return launch_gram_shape<MODE, 4>(bt, ga, k_dt, st, name);
-    return launch_gram_shape<MODE, 2>(bt, ga, k_dt, st, name);
+    if (MODE == MODE_DENSITY && ga.stat) {        // with the key-distance statistic
+        if (big) return launch_gram_shape<MODE, 4, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
+        return launch_gram_shape<MODE, 2, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
+    }
+    if (big) return launch_gram_shape<MODE, 4, false>(bt, ga, k_dt, st, name, grid_out);
+    return launch_gram_shape<MODE, 2, false>(bt, ga, k_dt, st, name, grid_out);
 }
 
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
-                        const int32_t* idx, pact_report* rep, hipStream_t st) {
+                        const int32_t* idx, pact_report* rep, bool want_stat, int* stat_words, hipStream_t st) {
     GramArgs ga;
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = idx; ga.idx_cols = idx; ga.rep = rep;
     ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = w.rho_part;
-    ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.margin = (float)cos_margin(dk);
+    ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.stat = want_stat ? w.stat : nullptr; ga.margin = (float)cos_margin(dk);
     const long t1 = (bt.n_max + 255) / 256;
-    return launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, nullptr);
+    int grid_x = 0;
+    const int rc = launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, nullptr, &grid_x);
+    if (stat_words) *stat_words = want_stat ? grid_x * 8 : 0;
+    return rc;
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -480,11 +518,11 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
     GramArgs ga;
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = pruned_idx; ga.idx_cols = center_idx;
     ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = nullptr;
-    ga.near_list = nullptr; ga.near_cnt = nullptr; ga.margin = (float)cos_margin(dk);
+    ga.near_list = nullptr; ga.near_cnt = nullptr; ga.stat = nullptr; ga.margin = (float)cos_margin(dk);
     // rows: the pruned tokens, columns: the centres; neither count is known on the host, a
     // typical split (half pruned, a third of the rest centres) sizes the choice
     const long tr = (bt.n_max / 2 + 255) / 256, tc = (bt.n_max / 6 + 255) / 256;
-    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, tile_rows);
+    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, tile_rows, nullptr);
 }
 
 #ifdef PACT_GRAM_STAMPS

@@ -45,7 +45,7 @@ struct WsLayout {
     size_t rho_part;                                   // [B][W][n_max] f64
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
-    size_t near_list, near_cnt;                        // refine list, counter
+    size_t near_list, near_cnt, stat;                  // refine list, counter; [B] most negative density exponent seen
     size_t offsets, members;                           // merge CSR (global row index)
     size_t zeros;                                      // 256 zero bytes
     size_t total;
@@ -78,6 +78,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.heads = take(sizeof(uint16_t) * 4 * B * n_max);
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
     L.near_cnt = take(sizeof(int32_t) * B);
+    L.stat = take(sizeof(uint32_t) * B);
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
     L.zeros = take(256);
@@ -90,7 +91,7 @@ struct Ws {
     double* qg_part; double* qg; double* logits; double* hnorm; double* sm_part;
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
-    int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt;
+    int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
     int32_t* offsets; int32_t* members; uint32_t* zeros;
 };
 
@@ -106,7 +107,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.status = (uint32_t*)(p + L.status); w.cnum = (int32_t*)(p + L.cnum);
     w.preds = (uint16_t*)(p + L.preds); w.heads = (uint2*)(p + L.heads);
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
-    w.near_cnt = (int32_t*)(p + L.near_cnt);
+    w.near_cnt = (int32_t*)(p + L.near_cnt); w.stat = (uint32_t*)(p + L.stat);
     w.offsets = (int32_t*)(p + L.offsets);
     w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
     return w;
@@ -150,12 +151,14 @@ int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st
 int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st);
 int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, float* scores,
                        int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep, hipStream_t st);
+// want_stat: also record the largest key distance; *stat_words = words per sample the kernel
+// wrote to w.stat (0 if not wanted), to be handed to launch_centres.
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
-                        const int32_t* idx, pact_report* rep, hipStream_t st);
+                        const int32_t* idx, pact_report* rep, bool want_stat, int* stat_words, hipStream_t st);
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
-                   hipStream_t st);
+                   int stat_words, hipStream_t st);
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
                          int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st);

@@ -463,3 +463,21 @@ def test_attention_handoff_matches_oracle():
         rp, rl = po.attention_handoff(cen, cnt)
         assert np.array_equal(pos[cu[b]:cu[b] + Cb].cpu().numpy(), rp)
         np.testing.assert_allclose(logw[cu[b]:cu[b] + Cb].cpu().numpy(), rl, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("name,seed", [("tiny_f32", 8), ("tiny_bf16", 9), ("img_0p5b", 3)])
+def test_max_key_distance_statistic(name, seed):
+    # by-product of the density pass: largest distance between two clustered keys (fp32 pass,
+    # so within the fp32 cosine error of the fp64 value)
+    s = gen.make_sample(name, seed)
+    d_c = gu.d_c_of(s)
+    assert gu.gpu_reduce(s, d_c)["rep"]["max_key_distance"] == 0.0         # only on request
+    g = gu.gpu_reduce(s, d_c, flags=P.PACT_FLAG_KEY_STATS)
+    U = s.keys.reshape(s.n, -1).astype(np.float64)[g["kept_idx"]]
+    ref = po.max_pairwise_distance(U)
+    tol = (U.shape[1] + 16) / 2.0 ** 23 + 3e-6
+    assert abs(g["rep"]["max_key_distance"] - ref) <= tol
+    out = P.dbdpc_cluster(gu.dev(s.keys.reshape(s.n, -1), s.config.key_dtype), d_c, 2.0)
+    torch.cuda.synchronize()
+    ref_all = po.max_pairwise_distance(s.keys.reshape(s.n, -1).astype(np.float64))
+    assert abs(P.read_report(out["rep"])["max_key_distance"] - ref_all) <= tol

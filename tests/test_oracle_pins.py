@@ -430,3 +430,13 @@ def test_attention_handoff_positions_and_weights():
     pos, lw = po.attention_handoff(r["center_idx"], r["counts"])
     assert np.all(np.diff(pos) > 0)
     assert round(float(np.exp(lw).sum())) == s.n - r["n_dropped"]
+
+
+def test_max_pairwise_distance_against_scipy_and_closed_forms():
+    r = np.random.default_rng(11)
+    U = r.normal(size=(40, 16))
+    assert abs(po.max_pairwise_distance(U) - ssd.pdist(U, "cosine").max()) < 1e-13
+    assert po.max_pairwise_distance(np.eye(5)) == 1.0                       # orthonormal: every pair at 1
+    assert po.max_pairwise_distance(np.array([[1.0, 0.0], [-2.0, 0.0]])) == 2.0   # opposite directions
+    assert po.max_pairwise_distance(np.tile(U[:1], (4, 1))) < 1e-15             # copies of one vector
+    assert po.max_pairwise_distance(U[:1]) == 0.0
