@@ -174,45 +174,73 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
     const size_t krow = (size_t)n_kv * d_h * Elem<KDT>::BYTES;
     constexpr int HE = Elem<HDT>::EPL;
 
+    // Fast path (the usual shapes: key row of at most 1 KB, one query head per key head, a
+    // power-of-two number of 16-byte chunks per head): the whole key row is one load per lane,
+    // issued together with the hidden-state loads, and a head's logit is a reduction over the
+    // few lanes that hold it.
+    const int lph = (int)((size_t)d_h * Elem<KDT>::BYTES / 16);      // lanes (chunks) per head
+    const bool fast = rep == 1 && krow <= 1024 && (size_t)lph * 16 == (size_t)d_h * Elem<KDT>::BYTES &&
+                      lph >= 1 && (lph & (lph - 1)) == 0;
     const int i = t0 + wave;
     if (i < sg.n) {
         const size_t g = (size_t)sg.base + i;
-        // hidden-state norm: 4 independent 16-byte loads in flight per lane
         const char* hp = hidden + g * hrow;
+        const char* kp = keys + g * krow;
+        const bool klane = (size_t)lane * 16 < krow;
+        uint4 kv = make_uint4(0, 0, 0, 0);
+        if (fast && klane) kv = *(const uint4*)(kp + (size_t)lane * 16);
+        // hidden-state norm: 8 independent 16-byte loads in flight per lane
         double ss[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int e0 = lane * HE; e0 < h; e0 += 4 * 64 * HE) {
-            uint4 v[4];
+        for (int e0 = lane * HE; e0 < h; e0 += 8 * 64 * HE) {
+            uint4 v[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const int e = e0 + u * 64 * HE;
                 v[u] = (e < h) ? *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 double x[8];
                 Elem<HDT>::widen(v[u], x);
 #pragma unroll
-                for (int k = 0; k < HE; ++k) ss[u] = fma(x[k], x[k], ss[u]);
+                for (int k = 0; k < HE; ++k) ss[u & 3] = fma(x[k], x[k], ss[u & 3]);
             }
         }
         const double sst = wave_sum_f64((ss[0] + ss[1]) + (ss[2] + ss[3]));
-        // per-head logits
-        const char* kp = keys + g * krow;
-        for (int j = 0; j < n_q; ++j) {
-            const int kvh = j / rep;
+        if (fast) {
+            // lane l holds elements [l * EPL, (l + 1) * EPL) of the row, i.e. of head l / lph
             double acc = 0.0;
-            for (int e = lane * Elem<KDT>::EPL; e < d_h; e += 64 * Elem<KDT>::EPL) {
-                const uint4 v = *(const uint4*)(kp + (size_t)(kvh * d_h + e) * Elem<KDT>::BYTES);
+            if (klane) {
                 double x[8];
-                Elem<KDT>::widen(v, x);
-                const double* qq = qgb + j * d_h + e;
+                Elem<KDT>::widen(kv, x);
+                const double* qq = qgb + lane * Elem<KDT>::EPL;
 #pragma unroll
                 for (int k = 0; k < Elem<KDT>::EPL; ++k) acc = fma(x[k], qq[k], acc);
             }
-            acc = wave_sum_f64(acc);
-            if (lane == 0) {
+            for (int sft = 1; sft < lph; sft <<= 1) acc += __shfl_xor(acc, sft, 64);
+            if (klane && (lane & (lph - 1)) == 0) {
+                const int j = lane / lph;
                 logits[g * n_q + j] = acc;
                 s_l[wave][j] = acc;
+            }
+        } else {
+            // per-head logits, one head after the other
+            for (int j = 0; j < n_q; ++j) {
+                const int kvh = j / rep;
+                double acc = 0.0;
+                for (int e = lane * Elem<KDT>::EPL; e < d_h; e += 64 * Elem<KDT>::EPL) {
+                    const uint4 v = *(const uint4*)(kp + (size_t)(kvh * d_h + e) * Elem<KDT>::BYTES);
+                    double x[8];
+                    Elem<KDT>::widen(v, x);
+                    const double* qq = qgb + j * d_h + e;
+#pragma unroll
+                    for (int k = 0; k < Elem<KDT>::EPL; ++k) acc = fma(x[k], qq[k], acc);
+                }
+                acc = wave_sum_f64(acc);
+                if (lane == 0) {
+                    logits[g * n_q + j] = acc;
+                    s_l[wave][j] = acc;
+                }
             }
         }
         if (lane == 0) hnorm[g] = sqrt(sst);
