@@ -90,10 +90,18 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // v = value in lane `l` of a wavefront-wide register (value and lane are wave-uniform)
-// (the compiler cannot see into the asm to pad the distance a VALU-written scalar needs before
-// another VALU instruction reads it, hence the s_nop)
-template <int L> __device__ __forceinline__ void write_lane(uint32_t& v, uint32_t value) {
-    asm("s_nop 1\n\tv_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(value), "n"(L));
+// Files the two halves of two ballots (m0: columns 0-31 of rows L and L+4, m1: columns 32-63)
+// under lanes L and L+4 of `lo` / `hi`.  (The compiler cannot see into the asm to pad the
+// distance a VALU-written scalar needs before another VALU instruction reads it, hence the s_nop.)
+template <int L> __device__ __forceinline__ void file_ballots(uint32_t& lo, uint32_t& hi, uint64_t m0, uint64_t m1) {
+    asm("s_nop 1\n\t"
+        "v_writelane_b32 %0, %2, %6\n\t"
+        "v_writelane_b32 %1, %4, %6\n\t"
+        "v_writelane_b32 %0, %3, %7\n\t"
+        "v_writelane_b32 %1, %5, %7"
+        : "+v"(lo), "+v"(hi)
+        : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)),
+          "n"(L), "n"(L + 4));
 }
 // body(std::integral_constant<int, 0>{}) ... body(std::integral_constant<int, N-1>{})
 template <int N, int I = 0, class F> __device__ __forceinline__ void static_for(F&& body) {
@@ -385,10 +393,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 constexpr int k0 = 8 * (r >> 2) + (r & 3);            // row of the lanes with hh = 0; hh = 1: k0 + 4
                 const uint64_t m0 = __ballot(acc[i][0][r] >= t_lo);
                 const uint64_t m1 = __ballot(acc[i][1][r] >= t_lo);
-                write_lane<k0>(wlo, (uint32_t)m0);
-                write_lane<k0>(whi, (uint32_t)m1);
-                write_lane<k0 + 4>(wlo, (uint32_t)(m0 >> 32));
-                write_lane<k0 + 4>(whi, (uint32_t)(m1 >> 32));
+                file_ballots<k0>(wlo, whi, m0, m1);
                 if (MODE == MODE_DENSITY) {
                     const uint64_t n0 = m0 & ~__ballot(acc[i][0][r] >= t_hi);
                     const uint64_t n1 = m1 & ~__ballot(acc[i][1][r] >= t_hi);
