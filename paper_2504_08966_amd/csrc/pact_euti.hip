@@ -352,7 +352,7 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     __shared__ double s_M[PACT_MAX_QHEADS], s_Z[PACT_MAX_QHEADS];
     __shared__ int s_hist[256 * 16];
     __shared__ int s_bin[256];
-    __shared__ int s_digit, s_newk;
+    __shared__ int s_sel[2][2];
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
@@ -395,19 +395,23 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     // so a plain histogram would serialise thousands of atomics on a handful of LDS words: every
     // bin has 16 copies (one per lane & 15, in 16 different banks), summed after the pass.
     uint32_t prefix = 0, mask = 0;
+    for (int i = tid; i < 256 * 16; i += 1024) s_hist[i] = 0;
+    __syncthreads();
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        for (int i = tid; i < 256 * 16; i += 1024) s_hist[i] = 0;
-        __syncthreads();
         for (int i = tid; i < n; i += 1024) {
             const uint32_t u = s_key[i];
             if ((u & mask) == prefix) atomicAdd(&s_hist[(((u >> shift) & 255) << 4) + (lane & 15)], 1);
         }
         __syncthreads();
-        if (tid < 256) {
+        if (tid < 256) {                   // sum the 16 copies of a bin and leave them cleared for the next pass
             int t = 0;
 #pragma unroll
-            for (int c = 0; c < 16; ++c) t += s_hist[(tid << 4) + ((c + tid) & 15)];   // (rotated: spreads the banks)
+            for (int c = 0; c < 16; ++c) {
+                const int a = (tid << 4) + ((c + tid) & 15);   // (rotated: spreads the banks)
+                t += s_hist[a];
+                s_hist[a] = 0;
+            }
             s_bin[tid] = t;
         }
         __syncthreads();
@@ -425,15 +429,14 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
             const int c[4] = {c0, c1, c2, c3};
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                if (k >= e && k < e + c[t]) { s_digit = 4 * tid + t; s_newk = k - e; }
+                if (k >= e && k < e + c[t]) { s_sel[pass & 1][0] = 4 * tid + t; s_sel[pass & 1][1] = k - e; }
                 e += c[t];
             }
         }
-        __syncthreads();
-        prefix |= (uint32_t)s_digit << shift;
+        __syncthreads();                   // (s_sel alternates, so no barrier is needed after reading it)
+        prefix |= (uint32_t)s_sel[pass & 1][0] << shift;
         mask |= 255u << shift;
-        k = s_newk;
-        __syncthreads();
+        k = s_sel[pass & 1][1];
     }
     const uint32_t tau = prefix;
 
