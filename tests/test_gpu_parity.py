@@ -481,3 +481,81 @@ def test_max_key_distance_statistic(name, seed):
     torch.cuda.synchronize()
     ref_all = po.max_pairwise_distance(s.keys.reshape(s.n, -1).astype(np.float64))
     assert abs(P.read_report(out["rep"])["max_key_distance"] - ref_all) <= tol
+
+
+# ------------------------------------------------------------------ shapes beyond the manifest
+
+def _gap_dc(U, frac=0.01, window=300):
+    """A cutoff in the middle of the widest gap of pair distances near the `frac` quantile, so
+    that no decision of the case sits on a rounding edge."""
+    D = po.cosine_distance_matrix(U.astype(np.float64))
+    vals = np.sort(D[np.triu_indices(U.shape[0], 1)])
+    lo = int(frac * vals.size)
+    w = vals[lo:lo + window]
+    j = int(np.argmax(np.diff(w)))
+    return float(np.float32(0.5 * (w[j] + w[j + 1])))
+
+
+def _random_sample(seed, n, n_kv, n_q, d_h, hidden, lam, dtype="f32"):
+    r = np.random.default_rng(seed)
+    nb = max(2, n // 20)
+    cen = r.normal(size=(nb, n_kv * d_h))
+    lab = r.integers(0, nb, n)
+    k = cen[lab] + 0.25 * r.normal(size=(n, n_kv * d_h))
+    h = r.normal(size=(n, hidden)) * np.exp(r.normal(0, 0.5, (n, 1)))
+    q = (r.normal(size=(n, n_q, d_h)) + 2.0 * r.normal(size=(1, n_q, d_h))) / (2.0 * np.sqrt(d_h))   # logits of order one
+    if dtype == "bf16":
+        k, h, q = gen.round_to_bf16(k), gen.round_to_bf16(h), gen.round_to_bf16(q)
+    cfg = gen.Config("adhoc", 1, 1, n, hidden, n_kv, d_h, dtype, dtype, nb, lam, 0.5)
+    return gen.Sample(cfg, seed, h.astype(np.float32), k.reshape(n, n_kv, d_h).astype(np.float32),
+                      q.astype(np.float32), lam)
+
+
+@pytest.mark.parametrize("n_kv,n_q,d_h,dtype", [(2, 6, 32, "f32"), (4, 28, 128, "bf16"), (1, 8, 16, "f32")])
+def test_grouped_query_heads(n_kv, n_q, d_h, dtype):
+    # more query heads than key heads: query head j reads key head j // (n_q / n_kv)
+    s = _random_sample(21, 300, n_kv, n_q, d_h, 256, 0.4, dtype)
+    n = s.n
+    hid, ks = gu.dev(s.hidden, dtype), gu.dev(s.keys.reshape(n, -1), dtype)
+    qs = gu.dev(s.queries.reshape(n, -1), dtype)
+    sc = P.pact_score(hid, ks, qs, n_kv, d_h, n_q)
+    torch.cuda.synchronize()
+    ref = po.euti_scores(s.hidden, s.keys, s.queries)
+    np.testing.assert_allclose(sc.cpu().numpy(), ref, rtol=1e-5 if dtype == "f32" else 1e-3, atol=0)
+    d_c = _gap_dc(s.keys.reshape(n, -1))
+    o = P.pact_reduce(hid, ks, ks, qs, n_kv, d_h, n_q, P.PactParams(s.lam, d_c, 2.0, 1.5))
+    torch.cuda.synchronize()
+    assert_same(gu.trim(o, n), oracle_reduce(s, d_c), s, f"gqa {n_kv}/{n_q}")
+
+
+@pytest.mark.parametrize("n,dk_heads,d_h,dtype", [(1000, 1, 40, "f32"), (333, 3, 24, "bf16"), (65, 1, 8, "bf16"),
+                                                  (257, 2, 520, "f32")])
+def test_odd_sizes_and_key_widths(n, dk_heads, d_h, dtype):
+    # token counts and key widths that are no multiple of any tile: 160-, 144-, 16- and 4160-byte rows
+    s = _random_sample(n, n, dk_heads, dk_heads, d_h, 96, 0.35, dtype)
+    d_c = _gap_dc(s.keys.reshape(n, -1), frac=0.02)
+    hid, ks = gu.dev(s.hidden, dtype), gu.dev(s.keys.reshape(n, -1), dtype)
+    qs = gu.dev(s.queries.reshape(n, -1), dtype)
+    o = P.pact_reduce(hid, ks, ks, qs, dk_heads, d_h, dk_heads, P.PactParams(s.lam, d_c, 2.0, 1.5))
+    torch.cuda.synchronize()
+    assert_same(gu.trim(o, n), oracle_reduce(s, d_c), s, f"n={n} dk={dk_heads * d_h} {dtype}")
+
+
+def test_largest_batch_of_small_samples():
+    # 64 samples (the batch limit) of ragged small sizes in one call
+    r = np.random.default_rng(77)
+    sizes = [int(x) for x in r.integers(20, 200, 64)]
+    samples = [_random_sample(1000 + b, sizes[b], 2, 2, 16, 64, float(r.choice([0.0, 0.3, 0.6])), "f32")
+               for b in range(64)]
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), "f32")
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "f32")
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "f32")
+    dcs = [_gap_dc(sm.keys.reshape(sm.n, -1), frac=0.03, window=60) for sm in samples]
+    prms = [P.PactParams(sm.lam, d, 2.0, 1.5) for sm, d in zip(samples, dcs)]
+    o = P.pact_reduce_varlen(hid, ks, ks, qs, 2, 16, 2, cu, prms)
+    torch.cuda.synchronize()
+    for b, sm in enumerate(samples):
+        assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b]), sm, f"sample {b}")
