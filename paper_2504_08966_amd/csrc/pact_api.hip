@@ -106,9 +106,10 @@ static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStrea
     if ((rc = launch_gram_density(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.rep, want_stat, &stat_words, st)))
         return rc;
     if ((rc = launch_centres(bt, w, io.keys, io.k_dt, dk, io.kept_idx, io.center_idx, io.cluster_id,
-                             io.cluster_counts, io.rep, nullptr, nullptr, stat_words, st))) return rc;
+                             io.cluster_counts, io.rep, nullptr, nullptr, stat_words, false, st))) return rc;
+    // (the kept tokens are assigned in the same launch as the pruned ones are recovered)
     if ((rc = launch_reincorporate(bt, w, io.keys, io.k_dt, dk, io.pruned_idx, io.center_idx,
-                                   io.cluster_id, io.cluster_counts, io.rep, false, st))) return rc;
+                                   io.cluster_id, io.cluster_counts, io.rep, false, io.kept_idx, st))) return rc;
     return launch_merge(bt, w, io.hidden, io.h_dt, io.h, io.cluster_id, io.center_idx, io.rep, io.merged,
                         io.out_dt, io.cluster_counts, false, st);
 }
@@ -212,7 +213,7 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     int stat_words = 0;
     if ((rc = launch_gram_density(bt, w, keys, k_dt, dk, use_idx, rep, true, &stat_words, st))) return rc;
     return launch_centres(bt, w, keys, k_dt, dk, use_idx, center_idx, cluster_id, nullptr, rep, rho_opt,
-                          rank_opt, stat_words, st);
+                          rank_opt, stat_words, true, st);
 }
 
 int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
@@ -235,7 +236,8 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     hipStream_t st = (hipStream_t)stream;
     if ((rc = launch_prep(bt, w, keys, k_dt, dk, nullptr, PACT_F32, 0, rep, cluster_id, nullptr, INIT_REINC,
                           nullptr, st))) return rc;
-    return launch_reincorporate(bt, w, keys, k_dt, dk, pruned_idx, center_idx, cluster_id, nullptr, rep, true, st);
+    return launch_reincorporate(bt, w, keys, k_dt, dk, pruned_idx, center_idx, cluster_id, nullptr, rep, true,
+                                nullptr, st);
 }
 
 int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,

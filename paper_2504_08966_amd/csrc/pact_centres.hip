@@ -11,6 +11,8 @@
 // A round evaluates this for all undecided tokens at once; the densest undecided token is
 // always decided, so the rounds terminate, and the result does not depend on how stale the
 // statuses read within a round are.
+#include <cstring>
+
 #include "pact_internal.h"
 
 namespace pact {
@@ -599,29 +601,47 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
 // ------------------------------------------------------------------------------------------
 constexpr int CAND_BUF = 128;
 
+// The two nearest-centre searches share one kernel (below): the assignment of the kept tokens
+// needs only the centres, so in the fused path it runs beside the recovery of the pruned tokens
+// (whose slowest wavefronts leave most of the chip idle) instead of before the candidate pass.
+struct NearArgs {
+    pact_report* rep;
+    const char* keys; int dk;
+    const double* nn;
+    const uint64_t* adj;
+    float margin;
+    int32_t* cluster_id; int32_t* cluster_counts;
+    // recovery of pruned tokens (Eq. 8/9); recover_blocks == 0: not in this launch
+    const int32_t* pruned_idx; const int32_t* center_idx; int band_unit; int recover_blocks;
+    // assignment of kept tokens (Alg. 2 last loop): the blocks after the recovery ones
+    const int32_t* idx; const uint64_t* cmask; const uint32_t* status; const int32_t* cnum;
+};
+
 // Alg. 2 last loop: every kept token joins the nearest centre.  Candidates are the centres
 // its bitmap row reaches (the nearest centre is within d_c, hence one of them; it need not
 // precede the token); with one candidate no distance is needed, otherwise Eq. 5 is
-// evaluated in fp64.
-// One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+// evaluated (fp32 screen, fp64 where it matters).  One wavefront per kept token, 4 per block.
 template <int DT>
-__global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
-                                                      const char* __restrict__ keys, int dk,
-                                                      const int32_t* __restrict__ idx,
-                                                      const double* __restrict__ nn,
-                                                      const uint64_t* __restrict__ adj,
-                                                      const uint64_t* __restrict__ cmask,
-                                                      const uint32_t* __restrict__ status,
-                                                      const int32_t* __restrict__ cnum, float margin,
-                                                      int32_t* cluster_id, int32_t* cluster_counts) {
-    __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
-    __shared__ float s_ccos[4][CAND_BUF];
+__device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, int blk, lds_i32* cand,
+                                            lds_i32* ctok, lds_f32* ccos) {
+    pact_report* rep = a.rep;
+    const char* keys = a.keys;
+    const int dk = a.dk;
+    const int32_t* idx = a.idx;
+    const double* nn = a.nn;
+    const uint64_t* adj = a.adj;
+    const uint64_t* cmask = a.cmask;
+    const uint32_t* status = a.status;
+    const int32_t* cnum = a.cnum;
+    const float margin = a.margin;
+    int32_t* cluster_id = a.cluster_id;
+    int32_t* cluster_counts = a.cluster_counts;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int p = blockIdx.x * 4 + wave;
+    const int p = blk * 4 + wave;
     if (p >= q) return;
     const int32_t* ix = idx + sg.base;
     const int32_t* cn = cnum + (size_t)b * bt.n_max;
@@ -636,9 +656,6 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
         const char* kb = keys + (size_t)sg.base * row_bytes;
         const char* mine = kb + (size_t)tok * row_bytes;
         const double nnp = nnb[tok];
-        lds_i32* cand = (lds_i32*)s_cand[wave];
-        lds_i32* ctok = (lds_i32*)s_ctok[wave];
-        lds_f32* ccos = (lds_f32*)s_ccos[wave];
         double best = INFINITY;
         int bestj = 0x7FFFFFFF;
         auto tok_of = [&](int j) { return ix[j]; };
@@ -679,18 +696,21 @@ __global__ __launch_bounds__(256) void assign_kernel(Batch bt, pact_report* rep,
 
 // Eq. 8/9: every pruned token joins the nearest centre iff its fp64 distance is below
 // alpha*d_c; candidates come from the matrix-core pass (bitmap rows q + t, bits over centres).
-// One wavefront per pruned token; grid (ceil(n_max/4), B), block 256.
+// One wavefront per pruned token, 4 per block; blocks 0 .. nblk-1 of the launch.
 template <int DT>
-__global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report* rep,
-                                                            const char* __restrict__ keys, int dk,
-                                                            const int32_t* __restrict__ pruned_idx,
-                                                            const int32_t* __restrict__ center_idx,
-                                                            const double* __restrict__ nn,
-                                                            const uint64_t* __restrict__ adj,
-                                                            int band_unit, float margin,
-                                                            int32_t* cluster_id, int32_t* cluster_counts) {
-    __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
-    __shared__ float s_ccos[4][CAND_BUF];
+__device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a, int blk, int nblk, lds_i32* cand,
+                                             lds_i32* ctok, lds_f32* ccos) {
+    pact_report* rep = a.rep;
+    const char* keys = a.keys;
+    const int dk = a.dk;
+    const int32_t* pruned_idx = a.pruned_idx;
+    const int32_t* center_idx = a.center_idx;
+    const double* nn = a.nn;
+    const uint64_t* adj = a.adj;
+    const int band_unit = a.band_unit;
+    const float margin = a.margin;
+    int32_t* cluster_id = a.cluster_id;
+    int32_t* cluster_counts = a.cluster_counts;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
@@ -700,22 +720,19 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     // Token -> workgroup: the candidate Gram pass left the pruned rows of tile-row band x, and
     // every centre row, in the L2 of XCD x (workgroup id mod 8); the same tokens are taken here
     // by that XCD's workgroups.
-    int t_first = blockIdx.x * 4 + wave, t_end = np, t_step = gridDim.x * 4;
-    if ((np + band_unit - 1) / band_unit >= 8 && (gridDim.x & 7) == 0) {
+    int t_first = blk * 4 + wave, t_end = np, t_step = nblk * 4;
+    if ((np + band_unit - 1) / band_unit >= 8 && (nblk & 7) == 0) {
         int lo, hi;
-        xcd_band(np, band_unit, blockIdx.x & 7, lo, hi);
-        t_first = lo + (blockIdx.x >> 3) * 4 + wave;
+        xcd_band(np, band_unit, blk & 7, lo, hi);
+        t_first = lo + (blk >> 3) * 4 + wave;
         t_end = hi;
-        t_step = (gridDim.x >> 3) * 4;
+        t_step = (nblk >> 3) * 4;
     }
     const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
     const char* kb = keys + (size_t)sg.base * row_bytes;
     const double* nnb = nn + sg.base;
     const int32_t* co = center_idx + sg.base;
     const double thr = (double)sg.alpha * (double)sg.d_c;
-    lds_i32* cand = (lds_i32*)s_cand[wave];
-    lds_i32* ctok = (lds_i32*)s_ctok[wave];
-    lds_f32* ccos = (lds_f32*)s_ccos[wave];
     auto tok_of = [&](int c) { return co[c]; };
     const int Wc = (C + 63) >> 6;
     for (int t = t_first; t < t_end; t += t_step) {
@@ -761,6 +778,28 @@ __global__ __launch_bounds__(256) void reinc_assign_kernel(Batch bt, pact_report
     }
 }
 
+// grid (recover_blocks + assign blocks, B), block 256: the recovery blocks first (their
+// wavefronts live longest).
+template <int DT>
+__global__ __launch_bounds__(256) void nearest_centre_kernel(Batch bt, NearArgs a) {
+    __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
+    __shared__ float s_ccos[4][CAND_BUF];
+    const int wave = threadIdx.x >> 6;
+    lds_i32* cand = (lds_i32*)s_cand[wave];
+    lds_i32* ctok = (lds_i32*)s_ctok[wave];
+    lds_f32* ccos = (lds_f32*)s_ccos[wave];
+    if ((int)blockIdx.x < a.recover_blocks) recover_body<DT>(bt, a, blockIdx.x, a.recover_blocks, cand, ctok, ccos);
+    else assign_body<DT>(bt, a, blockIdx.x - a.recover_blocks, cand, ctok, ccos);
+}
+
+static int launch_nearest(const Batch& bt, const NearArgs& a, int assign_blocks, pact_dtype k_dt, const char* name,
+                          hipStream_t st) {
+    dim3 grid(a.recover_blocks + assign_blocks, bt.B);
+    if (k_dt == PACT_BF16) PACT_LAUNCH(name, nearest_centre_kernel<PACT_BF16>, grid, dim3(256), st, bt, a);
+    else PACT_LAUNCH(name, nearest_centre_kernel<PACT_F32>, grid, dim3(256), st, bt, a);
+    return PACT_OK;
+}
+
 // Stand-alone pact_reincorporate: totals of recovered / dropped tokens (the fused path gets
 // them from the cluster sizes).  grid (B), block 1024.
 __global__ __launch_bounds__(1024) void count_recovered_kernel(Batch bt, pact_report* rep,
@@ -784,7 +823,7 @@ __global__ __launch_bounds__(1024) void count_recovered_kernel(Batch bt, pact_re
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
-                   int stat_words, hipStream_t st) {
+                   int stat_words, bool assign_now, hipStream_t st) {
     const char* k = (const char*)keys;
     dim3 gpost(REFINE_BLOCKS + (bt.n_max + 63) / 64, bt.B);
     if (k_dt == PACT_BF16)
@@ -810,36 +849,43 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     }
     PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
                       w.adj, w.rho, w.preds, w.heads, idx, w.status, w.cnum, w.cmask, center_idx);
-    if (k_dt == PACT_BF16)
-        PACT_LAUNCH("assign", assign_kernel<PACT_BF16>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
-                    w.adj, w.cmask, w.status, w.cnum, (float)cos_margin(dk), cluster_id, cluster_counts);
-    else
-        PACT_LAUNCH("assign", assign_kernel<PACT_F32>, gtok, dim3(256), st, bt, rep, k, dk, idx, w.nn,
-                    w.adj, w.cmask, w.status, w.cnum, (float)cos_margin(dk), cluster_id, cluster_counts);
-    return PACT_OK;
+    if (!assign_now) return PACT_OK;          // the caller runs it with the recovery (launch_reincorporate)
+    NearArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.rep = rep; a.keys = k; a.dk = dk; a.nn = w.nn; a.adj = w.adj; a.margin = (float)cos_margin(dk);
+    a.cluster_id = cluster_id; a.cluster_counts = cluster_counts;
+    a.idx = idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
+    return launch_nearest(bt, a, (bt.n_max + 3) / 4, k_dt, "assign", st);
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
                            int* tile_rows, hipStream_t st);
 
+// kept_idx != nullptr: the assignment of the kept tokens (deferred by launch_centres) runs in the
+// same launch as the recovery.
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
-                         int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st) {
+                         int32_t* cluster_counts, pact_report* rep, bool count_totals,
+                         const int32_t* kept_idx, hipStream_t st) {
     int band_unit = 256;
     int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, &band_unit, st);
     if (rc != PACT_OK) return rc;
+    NearArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.rep = rep; a.keys = (const char*)keys; a.dk = dk; a.nn = w.nn; a.adj = w.adj;
+    a.margin = (float)cos_margin(dk);
+    a.cluster_id = cluster_id; a.cluster_counts = cluster_counts;
+    a.pruned_idx = pruned_idx; a.center_idx = center_idx; a.band_unit = band_unit;
     // a wavefront per pruned token; a multiple of 8 workgroups, enough for the largest band
     const int band_tokens = (bt.n_max + 7) / 8 + band_unit;
-    dim3 grid(8 * ((band_tokens + 3) / 4), bt.B);
-    if (k_dt == PACT_BF16)
-        PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_BF16>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit,
-                    (float)cos_margin(dk), cluster_id, cluster_counts);
-    else
-        PACT_LAUNCH("reinc_assign", reinc_assign_kernel<PACT_F32>, grid, dim3(256), st, bt, rep,
-                    (const char*)keys, dk, pruned_idx, center_idx, w.nn, w.adj, band_unit,
-                    (float)cos_margin(dk), cluster_id, cluster_counts);
+    a.recover_blocks = 8 * ((band_tokens + 3) / 4);
+    int assign_blocks = 0;
+    if (kept_idx) {
+        a.idx = kept_idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
+        assign_blocks = (bt.n_max + 3) / 4;
+    }
+    if ((rc = launch_nearest(bt, a, assign_blocks, k_dt, "reinc_assign", st))) return rc;
     if (count_totals)
         PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
                     pruned_idx, cluster_id);

@@ -158,10 +158,11 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,
-                   int stat_words, hipStream_t st);
+                   int stat_words, bool assign_now, hipStream_t st);
 int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
-                         int32_t* cluster_counts, pact_report* rep, bool count_totals, hipStream_t st);
+                         int32_t* cluster_counts, pact_report* rep, bool count_totals,
+                         const int32_t* kept_idx, hipStream_t st);
 int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
                  const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
