@@ -78,7 +78,7 @@ typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) u32x2_t lds_uint2;
 typedef __attribute__((address_space(3))) double lds_f64;
-constexpr int NEAR_BUF = 512;              // undecided pairs a wavefront buffers before reserving list slots
+constexpr int NEAR_BUF = 512;              // undecided pairs a wavefront buffers before reserving list slots (> 32)
 
 // 16 bytes per lane, global -> LDS at (lds_base + lane * 16); asynchronous, counted by vmcnt.
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
@@ -101,6 +101,23 @@ template <int L> __device__ __forceinline__ void file_ballots(uint32_t& lo, uint
         "v_writelane_b32 %1, %5, %7"
         : "+v"(lo), "+v"(hi)
         : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)),
+          "n"(L), "n"(L + 4));
+}
+// The same for two sets of ballots at once (m -> lo/hi, h -> lo2/hi2).
+template <int L> __device__ __forceinline__ void file_ballots2(uint32_t& lo, uint32_t& hi, uint32_t& lo2, uint32_t& hi2,
+                                                               uint64_t m0, uint64_t m1, uint64_t h0, uint64_t h1) {
+    asm("s_nop 1\n\t"
+        "v_writelane_b32 %0, %4, %12\n\t"
+        "v_writelane_b32 %1, %6, %12\n\t"
+        "v_writelane_b32 %0, %5, %13\n\t"
+        "v_writelane_b32 %1, %7, %13\n\t"
+        "v_writelane_b32 %2, %8, %12\n\t"
+        "v_writelane_b32 %3, %10, %12\n\t"
+        "v_writelane_b32 %2, %9, %13\n\t"
+        "v_writelane_b32 %3, %11, %13"
+        : "+v"(lo), "+v"(hi), "+v"(lo2), "+v"(hi2)
+        : "s"((uint32_t)m0), "s"((uint32_t)(m0 >> 32)), "s"((uint32_t)m1), "s"((uint32_t)(m1 >> 32)),
+          "s"((uint32_t)h0), "s"((uint32_t)(h0 >> 32)), "s"((uint32_t)h1), "s"((uint32_t)(h1 >> 32)),
           "n"(L), "n"(L + 4));
 }
 // body(std::integral_constant<int, 0>{}) ... body(std::integral_constant<int, N-1>{})
@@ -387,29 +404,23 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             // files each half under the lane of its row, so that lane k < 32 ends up holding the
             // 64-bit bitmap word of row rowI + k.  (Scalar instructions are the scarce resource
             // here: the CU's four SIMDs share one scalar unit.)
-            uint32_t wlo = 0, whi = 0;
+            // The same is done with the ballots against the upper edge of the undecided band, so
+            // that the band itself (pairs too close to d_c for fp32) falls out per row afterwards.
+            // Straight-line code per element is kept to compares and lane writes: this part is
+            // unrolled 16 * MI times, and blocks that reach it are the minority, so its
+            // instructions are rarely in the instruction cache when they are needed.
+            uint32_t wlo = 0, whi = 0, hlo = 0, hhi = 0;
             static_for<16>([&](auto r_tag) __attribute__((always_inline)) {
                 constexpr int r = decltype(r_tag)::value;
                 constexpr int k0 = 8 * (r >> 2) + (r & 3);            // row of the lanes with hh = 0; hh = 1: k0 + 4
                 const uint64_t m0 = __ballot(acc[i][0][r] >= t_lo);
                 const uint64_t m1 = __ballot(acc[i][1][r] >= t_lo);
-                file_ballots<k0>(wlo, whi, m0, m1);
                 if (MODE == MODE_DENSITY) {
-                    const uint64_t n0 = m0 & ~__ballot(acc[i][0][r] >= t_hi);
-                    const uint64_t n1 = m1 & ~__ballot(acc[i][1][r] >= t_hi);
-                    if ((n0 | n1) != 0) {
-                        // too close to d_c for fp32: queue the pairs for the fp64 check.  They
-                        // collect in this wavefront's LDS buffer; one atomic reserves list slots
-                        // for a whole buffer (an atomic per event would cost a memory round trip).
-                        const uint64_t b0 = n0 & laneOk[0], b1 = n1 & laneOk[1];
-                        const uint64_t below = (1ull << lane) - 1ull;
-                        const bool f0 = (b0 >> lane) & 1ull, f1 = (b1 >> lane) & 1ull;
-                        const int rowP = rowI + k0 + 4 * hh;
-                        if (f0) nearBuf[nearN + __popcll(b0 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[0]};
-                        if (f1) nearBuf[nearN + __popcll(b0) + __popcll(b1 & below)] = u32x2_t{(uint32_t)rowP, (uint32_t)colP[1]};
-                        nearN += __popcll(b0) + __popcll(b1);
-                        if (nearN > NEAR_BUF - 128) flush_near();
-                    }
+                    const uint64_t h0 = __ballot(acc[i][0][r] >= t_hi);
+                    const uint64_t h1 = __ballot(acc[i][1][r] >= t_hi);
+                    file_ballots2<k0>(wlo, whi, hlo, hhi, m0, m1, h0, h1);
+                } else {
+                    file_ballots<k0>(wlo, whi, m0, m1);
                 }
             });
             // the 32 words of this block, one store instruction (the bitmap was cleared beforehand;
@@ -418,6 +429,23 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             whi &= (uint32_t)laneOk[1];
             if (lane < 32 && (wlo | whi) != 0)
                 adj[(size_t)(row_off + rowI + lane) * bt.W + wordIdx] = ((uint64_t)whi << 32) | wlo;
+            if (MODE == MODE_DENSITY) {
+                // Undecided pairs: queue them for the fp64 check.  They collect in this wavefront's
+                // LDS buffer, every lane adding one pair of its row per turn; one atomic reserves
+                // list slots for a whole buffer (an atomic per pair would cost a memory round trip).
+                uint64_t band = ((uint64_t)(whi & ~hhi) << 32) | (wlo & ~hlo);   // zero in lanes 32..63
+                uint64_t has;
+                while ((has = __ballot(band != 0)) != 0) {
+                    if (band != 0) {
+                        const int c = __builtin_ctzll(band);
+                        band &= band - 1;
+                        nearBuf[nearN + __popcll(has & ((1ull << lane) - 1ull))] =
+                            u32x2_t{(uint32_t)(rowI + lane), (uint32_t)(colW + c)};
+                    }
+                    nearN += __popcll(has);
+                    if (nearN > NEAR_BUF - 32) flush_near();
+                }
+            }
         }
         PACT_STAMP(3);
         if (MODE == MODE_DENSITY && nearN > 0) flush_near();
