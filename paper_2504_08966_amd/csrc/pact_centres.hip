@@ -611,10 +611,10 @@ struct NearArgs {
     const uint64_t* adj;
     float margin;
     int32_t* cluster_id; int32_t* cluster_counts;
-    // recovery of pruned tokens (Eq. 8/9); recover_blocks == 0: not in this launch
-    const int32_t* pruned_idx; const int32_t* center_idx; int band_unit; int recover_blocks;
-    // assignment of kept tokens (Alg. 2 last loop): the blocks after the recovery ones
-    const int32_t* idx; const uint64_t* cmask; const uint32_t* status; const int32_t* cnum;
+    // assignment of kept tokens (Alg. 2 last loop); assign_blocks == 0: not in this launch
+    const int32_t* idx; const uint64_t* cmask; const uint32_t* status; const int32_t* cnum; int assign_blocks;
+    // recovery of pruned tokens (Eq. 8/9): the blocks after the assignment ones
+    const int32_t* pruned_idx; const int32_t* center_idx; const float* cbest;
 };
 
 // Alg. 2 last loop: every kept token joins the nearest centre.  Candidates are the centres
@@ -694,107 +694,194 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
     }
 }
 
-// Eq. 8/9: every pruned token joins the nearest centre iff its fp64 distance is below
-// alpha*d_c; candidates come from the matrix-core pass (bitmap rows q + t, bits over centres).
-// One wavefront per pruned token, 4 per block; blocks 0 .. nblk-1 of the launch.
+// Dot product in fp64 of the rows `mine` and `other` by the 16 lanes part = 0..15 of a group
+// (lane `part` takes the 16-byte chunks part, part + 16, ...; four chunks of either row in
+// flight per lane).  Every lane of the group gets the sum.
 template <int DT>
-__device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a, int blk, int nblk, lds_i32* cand,
-                                             lds_i32* ctok, lds_f32* ccos) {
+__device__ __forceinline__ double group_dot64(const char* mine, const char* other, int nchunk, int part) {
+    constexpr int EPL = Elem<DT>::EPL;
+    double acc = 0.0;
+#pragma unroll 1
+    for (int k0 = part; k0 < nchunk; k0 += 64) {
+        uint4 va[4], vb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t o = (size_t)(k0 + 16 * u < nchunk ? k0 + 16 * u : k0) * 16;
+            va[u] = *(const uint4*)(mine + o);
+            vb[u] = *(const uint4*)(other + o);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (k0 + 16 * u < nchunk) {
+                // (the chunk is tied to the running sum so that the conversions of all chunks are
+                //  not hoisted ahead of the additions: registers decide this kernel's occupancy)
+                asm volatile("" : "+v"(va[u].x), "+v"(vb[u].x) : "v"(acc));
+                double a[8], x[8];
+                Elem<DT>::widen(va[u], a);
+                Elem<DT>::widen(vb[u], x);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc = fma(a[i], x[i], acc);
+            }
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft <= 8; sft <<= 1) acc += __shfl_xor(acc, sft, 64);
+    return acc;
+}
+
+// Eq. 8/9: every pruned token joins the nearest centre iff its fp64 distance is below
+// alpha*d_c.  The matrix-core pass left, per pruned token t and group w of 64 centres, the
+// group's largest fp32 cosine cbest[w][t] and a word of candidates (bits of the centres within
+// reach whose cosine is at most 2 * margin below it), laid out [w][t].  With gm the largest of
+// a token's cbest values, the nearest centre in exact arithmetic is a candidate of a group
+// whose cbest >= gm - 2 * margin (margin bounds the error of an fp32 cosine).  Usually that is
+// one centre, clear of the threshold: decided without touching a key.  Otherwise (several
+// candidates, or one too close to alpha*d_c) Eq. 5 is evaluated in fp64 for each of them.
+// What a token costs is its chain of dependent memory accesses, so 16 lanes work on one token
+// (16 tokens per block and turn): the values and words of 64 groups arrive in one trip and are
+// kept for the listing, a candidate row in another.  Blocks blk = 0 .. nblk-1, 256 threads.
+// s_c: [16][RECOVER_LIST] candidate ids per token slot.
+constexpr int RECOVER_LIST = 16;
+template <int DT>
+__device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a, int blk, int nblk, lds_i32* s_c) {
     pact_report* rep = a.rep;
-    const char* keys = a.keys;
-    const int dk = a.dk;
-    const int32_t* pruned_idx = a.pruned_idx;
-    const int32_t* center_idx = a.center_idx;
-    const double* nn = a.nn;
-    const uint64_t* adj = a.adj;
-    const int band_unit = a.band_unit;
-    const float margin = a.margin;
-    int32_t* cluster_id = a.cluster_id;
-    int32_t* cluster_counts = a.cluster_counts;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
               C = clamp_count(rep[b].n_centers, q);
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    // Token -> workgroup: the candidate Gram pass left the pruned rows of tile-row band x, and
-    // every centre row, in the L2 of XCD x (workgroup id mod 8); the same tokens are taken here
-    // by that XCD's workgroups.
-    int t_first = blk * 4 + wave, t_end = np, t_step = nblk * 4;
-    if ((np + band_unit - 1) / band_unit >= 8 && (nblk & 7) == 0) {
-        int lo, hi;
-        xcd_band(np, band_unit, blk & 7, lo, hi);
-        t_first = lo + (blk >> 3) * 4 + wave;
-        t_end = hi;
-        t_step = (nblk >> 3) * 4;
-    }
-    const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
-    const char* kb = keys + (size_t)sg.base * row_bytes;
-    const double* nnb = nn + sg.base;
-    const int32_t* co = center_idx + sg.base;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const size_t row_bytes = (size_t)a.dk * Elem<DT>::BYTES;
+    const int nchunk = (int)(row_bytes / 16);
+    const char* kb = a.keys + (size_t)sg.base * row_bytes;
+    const double* nnb = a.nn + sg.base;
+    const int32_t* co = a.center_idx + sg.base;
+    const int32_t* pruned = a.pruned_idx + sg.base;
+    int32_t* cluster_id = a.cluster_id + sg.base;
+    int32_t* cluster_counts = a.cluster_counts ? a.cluster_counts + sg.base : nullptr;
     const double thr = (double)sg.alpha * (double)sg.d_c;
-    auto tok_of = [&](int c) { return co[c]; };
+    const double cthr = 1.0 - thr;                                  // d < thr  <=>  cosine > 1 - thr
+    const float margin = a.margin;
+    const float t_lo = (1.0f - sg.alpha * sg.d_c) - margin;         // as the matrix-core pass computes it
     const int Wc = (C + 63) >> 6;
-    for (int t = t_first; t < t_end; t += t_step) {
-        const int tok = pruned_idx[sg.base + t];
-        const char* mine = kb + (size_t)tok * row_bytes;
-        const double nnp = nnb[tok];
-        double best = INFINITY;
-        int bestc = 0x7FFFFFFF;
+    const float* cb = a.cbest + (size_t)b * bt.W * bt.n_max;        // [W][n_max]
+    const uint64_t* cw = a.adj + ((size_t)b * bt.n_max + q) * bt.W; // [Wc][np]
+    const int part = tid & 15, ts = tid >> 4, gbase = lane & ~15;
+    lds_i32* list = s_c + ts * RECOVER_LIST;
+    for (int t = blk * 16 + ts; t < np; t += nblk * 16) {
+        const int tok = pruned[t];
+        int res = -1;                                               // -1: no centre in reach
         if (thr > 0.0 && C > 0) {
-            const uint64_t* row = adj + ((size_t)b * bt.n_max + q + t) * bt.W;
-            int nbuf = 0;
-            bool flushed = false;
-            for (int w0 = 0; w0 < Wc; w0 += 64) {
-                const int w = w0 + lane;
-                BitPop bp{(w < Wc) ? row[w] : 0ull};
-                while (bp.any()) {
-                    int bit;
-                    const bool has = bp.pop(bit);
-                    const int c = (w << 6) + bit;
-                    const bool ok = has && c < C;
-                    const uint64_t m = __ballot(ok);
-                    if (ok) cand[nbuf + lanes_below(m, lane)] = c;
-                    nbuf += __popcll(m);
-                    if (nbuf > CAND_BUF - 64) {
-                        nearest_candidate<DT>(cand, ctok, ccos, nbuf, false, mine, nnp, kb, row_bytes, nnb, dk,
-                                              lane, thr, margin, tok_of, best, bestc);
-                        nbuf = 0;
-                        flushed = true;
-                    }
+            // groups part, part + 16, .. of the first 64 with their candidate words (a word is
+            // only meaningful where the group's largest cosine is within reach); further
+            // groups, if any, for the maximum only
+            float v[4];
+            uint64_t word[4];
+            auto load_batch = [&](int wb) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int w = wb + part + 16 * u;
+                    v[u] = w < Wc ? cb[(size_t)w * bt.n_max + t] : -INFINITY;
+                    word[u] = w < Wc ? cw[(size_t)w * np + t] : 0ull;
                 }
+            };
+            load_batch(0);
+            float gm = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+            for (int w = 64 + part; w < Wc; w += 16) gm = fmaxf(gm, cb[(size_t)w * bt.n_max + t]);
+#pragma unroll
+            for (int sft = 1; sft <= 8; sft <<= 1) gm = fmaxf(gm, __shfl_xor(gm, sft, 64));
+            if (gm >= t_lo) {
+                const float floor32 = fmaxf(gm - 2.0f * margin, t_lo);
+                const bool clear = (double)gm - cthr > (double)margin;   // the nearest is certainly within alpha*d_c
+                const char* mine = kb + (size_t)tok * row_bytes;
+                double best = INFINITY;
+                int bestc = 0x7FFFFFFF;
+                bool first_batch_loaded = true;
+                // The candidates are listed in the token's LDS slots, RECOVER_LIST per turn (one
+                // turn unless the token is degenerate); all control flow from here on is uniform
+                // within the 16 lanes of a token.
+#pragma unroll 1
+                for (int skip = 0;; skip += RECOVER_LIST) {
+                    int n = 0, ntot = 0;
+#pragma unroll 1
+                    for (int wb = 0; wb < Wc; wb += 64) {
+                        if (!(wb == 0 && first_batch_loaded)) load_batch(wb);
+                        first_batch_loaded = first_batch_loaded && wb == 0;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const uint64_t wv = (v[u] >= floor32) ? word[u] : 0ull;
+                            uint32_t who = (uint32_t)(__ballot(wv != 0) >> gbase) & 0xFFFFu;
+                            while (who) {
+                                const int src = __builtin_ctz(who);
+                                who &= who - 1;
+                                uint64_t bits = __shfl(wv, gbase + src, 64);
+                                const int cbase = (wb + src + 16 * u) << 6;
+                                while (bits) {
+                                    const int c = cbase + __builtin_ctzll(bits);
+                                    bits &= bits - 1;
+                                    if (ntot >= skip && n < RECOVER_LIST) {
+                                        if (part == 0) list[n] = c;
+                                        ++n;
+                                    }
+                                    ++ntot;
+                                }
+                            }
+                        }
+                    }
+                    if (ntot == 1 && clear) {                          // decided by the fp32 screen alone
+                        bestc = list[0];
+                        break;
+                    }
+                    // fp64 for the n listed candidates: their tokens and norms in one trip, then row by row
+                    int ctk = 0, cid = 0;
+                    double cnn = 0.0;
+                    if (part < n) {
+                        cid = list[part];
+                        ctk = co[cid];
+                        cnn = nnb[ctk];
+                    }
+                    const double nnp = nnb[tok];
+#pragma unroll 1
+                    for (int k = 0; k < n; ++k) {
+                        const int c = __shfl(cid, gbase + k, 64);
+                        const int tc = __shfl(ctk, gbase + k, 64);
+                        const double nc = __shfl(cnn, gbase + k, 64);
+                        const double d = cos_dist64(group_dot64<DT>(mine, kb + (size_t)tc * row_bytes, nchunk, part), nnp, nc);
+                        if (d < thr && (d < best || (d == best && c < bestc))) { best = d; bestc = c; }
+                    }
+                    if (skip + RECOVER_LIST >= ntot) break;
+                }
+                res = bestc != 0x7FFFFFFF ? bestc : -1;
             }
-            if (nbuf) nearest_candidate<DT>(cand, ctok, ccos, nbuf, !flushed, mine, nnp, kb, row_bytes, nnb, dk,
-                                            lane, thr, margin, tok_of, best, bestc);
         }
-        if (lane == 0) {
-            const int cid = bestc != 0x7FFFFFFF ? bestc : -1;
-            cluster_id[sg.base + tok] = cid;
+        if (part == 0) {
+            cluster_id[tok] = res;
             // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
             //  counter that every wavefront hits would serialise at one L2 address)
-            if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
-            if (!(nnp > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
+            if (res >= 0 && cluster_counts) atomicAdd(&cluster_counts[res], 1);
+            if (!(nnb[tok] > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
         }
     }
 }
 
-// grid (recover_blocks + assign blocks, B), block 256: the recovery blocks first (their
+// grid (assign_blocks + recovery blocks, B), block 256: the assignment blocks first (their
 // wavefronts live longest).
 template <int DT>
 __global__ __launch_bounds__(256) void nearest_centre_kernel(Batch bt, NearArgs a) {
     __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
     __shared__ float s_ccos[4][CAND_BUF];
+    __shared__ int s_list[16 * RECOVER_LIST];
     const int wave = threadIdx.x >> 6;
     lds_i32* cand = (lds_i32*)s_cand[wave];
     lds_i32* ctok = (lds_i32*)s_ctok[wave];
     lds_f32* ccos = (lds_f32*)s_ccos[wave];
-    if ((int)blockIdx.x < a.recover_blocks) recover_body<DT>(bt, a, blockIdx.x, a.recover_blocks, cand, ctok, ccos);
-    else assign_body<DT>(bt, a, blockIdx.x - a.recover_blocks, cand, ctok, ccos);
+    if ((int)blockIdx.x < a.assign_blocks) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
+    else recover_body<DT>(bt, a, blockIdx.x - a.assign_blocks, gridDim.x - a.assign_blocks, (lds_i32*)s_list);
 }
 
-static int launch_nearest(const Batch& bt, const NearArgs& a, int assign_blocks, pact_dtype k_dt, const char* name,
+static int launch_nearest(const Batch& bt, const NearArgs& a, int recover_blocks, pact_dtype k_dt, const char* name,
                           hipStream_t st) {
-    dim3 grid(a.recover_blocks + assign_blocks, bt.B);
+    dim3 grid(a.assign_blocks + recover_blocks, bt.B);
     if (k_dt == PACT_BF16) PACT_LAUNCH(name, nearest_centre_kernel<PACT_BF16>, grid, dim3(256), st, bt, a);
     else PACT_LAUNCH(name, nearest_centre_kernel<PACT_F32>, grid, dim3(256), st, bt, a);
     return PACT_OK;
@@ -855,12 +942,13 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     a.rep = rep; a.keys = k; a.dk = dk; a.nn = w.nn; a.adj = w.adj; a.margin = (float)cos_margin(dk);
     a.cluster_id = cluster_id; a.cluster_counts = cluster_counts;
     a.idx = idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
-    return launch_nearest(bt, a, (bt.n_max + 3) / 4, k_dt, "assign", st);
+    a.assign_blocks = (bt.n_max + 3) / 4;
+    return launch_nearest(bt, a, 0, k_dt, "assign", st);
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
-                           int* tile_rows, hipStream_t st);
+                           hipStream_t st);
 
 // kept_idx != nullptr: the assignment of the kept tokens (deferred by launch_centres) runs in the
 // same launch as the recovery.
@@ -868,24 +956,19 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
                          const int32_t* pruned_idx, const int32_t* center_idx, int32_t* cluster_id,
                          int32_t* cluster_counts, pact_report* rep, bool count_totals,
                          const int32_t* kept_idx, hipStream_t st) {
-    int band_unit = 256;
-    int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, &band_unit, st);
+    int rc = launch_gram_candidates(bt, w, keys, k_dt, dk, pruned_idx, center_idx, rep, st);
     if (rc != PACT_OK) return rc;
     NearArgs a;
     std::memset(&a, 0, sizeof(a));
     a.rep = rep; a.keys = (const char*)keys; a.dk = dk; a.nn = w.nn; a.adj = w.adj;
     a.margin = (float)cos_margin(dk);
     a.cluster_id = cluster_id; a.cluster_counts = cluster_counts;
-    a.pruned_idx = pruned_idx; a.center_idx = center_idx; a.band_unit = band_unit;
-    // a wavefront per pruned token; a multiple of 8 workgroups, enough for the largest band
-    const int band_tokens = (bt.n_max + 7) / 8 + band_unit;
-    a.recover_blocks = 8 * ((band_tokens + 3) / 4);
-    int assign_blocks = 0;
+    a.pruned_idx = pruned_idx; a.center_idx = center_idx; a.cbest = w.cbest;
     if (kept_idx) {
         a.idx = kept_idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
-        assign_blocks = (bt.n_max + 3) / 4;
+        a.assign_blocks = (bt.n_max + 3) / 4;
     }
-    if ((rc = launch_nearest(bt, a, assign_blocks, k_dt, "reinc_assign", st))) return rc;
+    if ((rc = launch_nearest(bt, a, (bt.n_max + 15) / 16, k_dt, "reinc_assign", st))) return rc;
     if (count_totals)
         PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
                     pruned_idx, cluster_id);

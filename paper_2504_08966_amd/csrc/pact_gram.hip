@@ -3,8 +3,10 @@
 //   MODE_DENSITY  kept x kept  : density terms exp(-d/d_n) summed per column in fp64 (Eq. 6),
 //                                one bit per pair "cosine distance <= d_c (+ margin)", and a
 //                                list of the pairs too close to d_c for fp32 to decide;
-//   MODE_CAND     pruned x centres : one bit per pair "distance < alpha*d_c (+ margin)"
-//                                (candidates for Eq. 8).
+//   MODE_CAND     centres x pruned : per pruned token (a column) and group of 64 centres, the
+//                                largest cosine of the group and one bit per centre that is
+//                                within reach (alpha*d_c + margin) and can still be the
+//                                nearest of its group (candidates for Eq. 8).
 // The distance matrix itself is never written.
 //
 // Shape of the kernel (gfx950):
@@ -50,6 +52,7 @@ struct GramArgs {
     const float* rinv;         // [total] 1/|u| (0 for a zero vector)
     const char* zeros;         // >= 16 zero bytes (source of the slices past the key width)
     uint64_t* adj;             // [B][n_max][W]
+    float* cbest;              // candidate pass: [B][W][n_max] largest cosine per (group of 64 centres, pruned token)
     double* rho_part;          // [B][W][n_max], one row per GRAM_RHO_ROWS kept rows
     uint32_t* near_list;       // [B][NEAR_CAP][2]
     int32_t* near_cnt;         // [B]
@@ -153,9 +156,10 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int q_kept = clamp_count(ga.rep[b].n_kept, sg.n);
-    const int nA = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_pruned, sg.n - q_kept);
-    const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_centers, q_kept);
-    const int row_off = (MODE == MODE_DENSITY) ? 0 : q_kept;   // candidate rows follow the kept rows
+    // density pass: kept x kept; candidate pass: rows are the centres, columns the pruned tokens
+    // (what is wanted there is per pruned token, and a lane holds 16 rows of one column)
+    const int nA = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_centers, q_kept);
+    const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_pruned, sg.n - q_kept);
     if (nA <= 0 || nB <= 0) {
         if (STAT && (threadIdx.x & 63) == 0)
             ga.stat[((size_t)b * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)] = 0u;
@@ -205,9 +209,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     // every XCD has its own L2, so each XCD takes a contiguous eighth of the tile sequence:
     // column by column for the (symmetric) density pass, row by row for the candidate pass.  An
     // XCD then works on few tile columns (rows) whose keys stay in its L2, and - counted in
-    // tiles, not in rows - every XCD gets the same load.  After the candidate pass the pruned
-    // rows of an XCD's share and every centre row sit in its L2, where the kernel that
-    // evaluates the candidates (same token -> XCD mapping, see xcd_band) finds them.
+    // tiles, not in rows - every XCD gets the same load.
     const int xcd = blockIdx.x & 7;
     const long nTiles = (long)tilesR * tilesC;
     const bool banded = nTiles >= 8 && (gridDim.x & 7) == 0;
@@ -345,6 +347,57 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             nearN = 0;
         };
         // (the barriers of the slice loop also ordered the sRinv writes before these reads)
+        if constexpr (MODE == MODE_CAND) {
+            // A lane holds 2 x 16 of the 64 centres of a group for each of its two pruned tokens,
+            // the lane 32 further on the other 2 x 16: maximum and bits are assembled in the lane
+            // and completed with one exchange.  A bit is set for a centre within reach whose
+            // cosine is at most 2 * margin below the group's largest: no other centre of the
+            // group can be the nearest in exact arithmetic.  Layout [group][pruned token], so that
+            // the 32 lanes of a half-wave store contiguously.
+            uint64_t* cw = adj + (size_t)q_kept * bt.W;                   // [Wc][nB] words, in the unused bitmap rows
+            float* cb = ga.cbest + (size_t)b * bt.W * bt.n_max;
+            const float two_m = 2.0f * ga.margin;
+#pragma unroll
+            for (int gi = 0; gi < MI / 2; ++gi) {
+                const int rowG = rowW + gi * 64;                           // first centre of the group
+                if (rowG >= nA) continue;
+                float rs[2][16];
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        rs[i2][r] = sRinv[wr * WROWS + gi * 64 + i2 * 32 + 8 * (r >> 2) + 4 * hh + (r & 3)];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    float lb = -INFINITY;
+#pragma unroll
+                    for (int i2 = 0; i2 < 2; ++i2)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const bool pad = rowG + i2 * 32 + 8 * (r >> 2) + 4 * hh + (r & 3) >= nA;
+                            const float v = pad ? -INFINITY : acc[2 * gi + i2][j][r] * rs[i2][r] * rj[j];
+                            acc[2 * gi + i2][j][r] = v;
+                            lb = fmaxf(lb, v);
+                        }
+                    lb = fmaxf(lb, __shfl_xor(lb, 32, 64));
+                    const float cut = fmaxf(lb - two_m, t_lo);
+                    uint32_t w32[2];
+#pragma unroll
+                    for (int i2 = 0; i2 < 2; ++i2) {
+                        uint32_t bits = 0u;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            bits |= (acc[2 * gi + i2][j][r] >= cut) ? (1u << (8 * (r >> 2) + (r & 3))) : 0u;
+                        bits <<= 4 * hh;
+                        w32[i2] = bits | (uint32_t)__shfl_xor((int)bits, 32, 64);
+                    }
+                    if (hh == j && colP[j] < nB) {
+                        cb[(size_t)(rowG >> 6) * bt.n_max + colP[j]] = lb;
+                        if (lb >= t_lo) cw[(size_t)(rowG >> 6) * nB + colP[j]] = ((uint64_t)w32[1] << 32) | w32[0];
+                    }
+                }
+            }
+        } else {
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             float rs[16];
@@ -428,7 +481,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             wlo &= (uint32_t)laneOk[0];
             whi &= (uint32_t)laneOk[1];
             if (lane < 32 && (wlo | whi) != 0)
-                adj[(size_t)(row_off + rowI + lane) * bt.W + wordIdx] = ((uint64_t)whi << 32) | wlo;
+                adj[(size_t)(rowI + lane) * bt.W + wordIdx] = ((uint64_t)whi << 32) | wlo;
             if (MODE == MODE_DENSITY) {
                 // Undecided pairs: queue them for the fp64 check.  They collect in this wavefront's
                 // LDS buffer, every lane adding one pair of its row per turn; one atomic reserves
@@ -446,6 +499,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                     if (nearN > NEAR_BUF - 32) flush_near();
                 }
             }
+        }
         }
         PACT_STAMP(3);
         if (MODE == MODE_DENSITY && nearN > 0) flush_near();
@@ -521,9 +575,8 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
 // 256 x 256 tiles when there are enough of them to occupy the chip, else 128 x 256.
 template <int MODE>
 static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                       const char* name, long tiles256, int* tile_rows, int* grid_out) {
+                       const char* name, long tiles256, int* grid_out) {
     const bool big = tiles256 * bt.B >= 256;
-    if (tile_rows) *tile_rows = big ? Shape<4>::TILE_R : Shape<2>::TILE_R;
     if (MODE == MODE_DENSITY && ga.stat) {        // with the key-distance statistic
         if (big) return launch_gram_shape<MODE, 4, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
         return launch_gram_shape<MODE, 2, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
@@ -536,26 +589,27 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
                         const int32_t* idx, pact_report* rep, bool want_stat, int* stat_words, hipStream_t st) {
     GramArgs ga;
     ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = idx; ga.idx_cols = idx; ga.rep = rep;
-    ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = w.rho_part;
+    ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.cbest = nullptr; ga.rho_part = w.rho_part;
     ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.stat = want_stat ? w.stat : nullptr; ga.margin = (float)cos_margin(dk);
     const long t1 = (bt.n_max + 255) / 256;
     int grid_x = 0;
-    const int rc = launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, nullptr, &grid_x);
+    const int rc = launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, &grid_x);
     if (stat_words) *stat_words = want_stat ? grid_x * 8 : 0;
     return rc;
 }
 
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
-                           int* tile_rows, hipStream_t st) {
+                           hipStream_t st) {
     GramArgs ga;
-    ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = pruned_idx; ga.idx_cols = center_idx;
-    ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.rho_part = nullptr;
+    ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = center_idx; ga.idx_cols = pruned_idx;
+    ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.cbest = w.cbest;
+    ga.rho_part = nullptr;
     ga.near_list = nullptr; ga.near_cnt = nullptr; ga.stat = nullptr; ga.margin = (float)cos_margin(dk);
-    // rows: the pruned tokens, columns: the centres; neither count is known on the host, a
+    // rows: the centres, columns: the pruned tokens; neither count is known on the host, a
     // typical split (half pruned, a third of the rest centres) sizes the choice
-    const long tr = (bt.n_max / 2 + 255) / 256, tc = (bt.n_max / 6 + 255) / 256;
-    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, tile_rows, nullptr);
+    const long tr = (bt.n_max / 6 + 255) / 256, tc = (bt.n_max / 2 + 255) / 256;
+    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, nullptr);
 }
 
 #ifdef PACT_GRAM_STAMPS

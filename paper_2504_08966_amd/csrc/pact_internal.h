@@ -41,7 +41,8 @@ struct WsLayout {
     size_t qg_part, qg, logits, hnorm, sm_part;        // score
     size_t nn, rinv;                                   // key norms, per token (global row index)
     size_t ident;                                      // identity index list (idx == NULL)
-    size_t adj;                                        // [B][n_max][W] u64: rows < q adjacency, rows q.. candidates
+    size_t adj;                                        // [B][n_max][W] u64: rows < q adjacency; from row q on: candidate words [Wc][n_pruned]
+    size_t cbest;                                      // [B][W][n_max] f32: largest cosine per (group of 64 centres, pruned token)
     size_t rho_part;                                   // [B][W][n_max] f64
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
@@ -68,6 +69,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.rinv = take(sizeof(float) * total);
     L.ident = take(sizeof(int32_t) * total);
     L.adj = take(sizeof(uint64_t) * B * n_max * W);
+    L.cbest = take(sizeof(float) * B * W * n_max);
     L.rho_part = take(sizeof(double) * B * W * n_max);
     L.rho = take(sizeof(double) * B * n_max);
     L.rank = take(sizeof(int32_t) * B * n_max);
@@ -90,7 +92,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
 struct Ws {
     double* qg_part; double* qg; double* logits; double* hnorm; double* sm_part;
     double* nn; float* rinv; int32_t* ident;
-    uint64_t* adj; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
+    uint64_t* adj; float* cbest; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
     int32_t* offsets; int32_t* members; uint32_t* zeros;
 };
@@ -102,7 +104,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.logits = (double*)(p + L.logits); w.hnorm = (double*)(p + L.hnorm);
     w.sm_part = (double*)(p + L.sm_part);
     w.nn = (double*)(p + L.nn); w.rinv = (float*)(p + L.rinv); w.ident = (int32_t*)(p + L.ident);
-    w.adj = (uint64_t*)(p + L.adj); w.rho_part = (double*)(p + L.rho_part);
+    w.adj = (uint64_t*)(p + L.adj); w.cbest = (float*)(p + L.cbest); w.rho_part = (double*)(p + L.rho_part);
     w.rho = (double*)(p + L.rho); w.rank = (int32_t*)(p + L.rank);
     w.status = (uint32_t*)(p + L.status); w.cnum = (int32_t*)(p + L.cnum);
     w.preds = (uint16_t*)(p + L.preds); w.heads = (uint2*)(p + L.heads);
@@ -265,15 +267,6 @@ __device__ __forceinline__ double wave_dot64(const char* ra, const char* rb, int
         for (int i = 0; i < EPL; ++i) acc = fma(a[i], b[i], acc);
     }
     return wave_sum_f64(acc);
-}
-
-// Rows [lo, hi) whose tile row starts in XCD x's share when `count` rows are cut into tiles of
-// `unit` rows and the row-major tile sequence is dealt to the 8 XCDs in contiguous eighths
-// (the candidate pass of the Gram kernel): tile row r belongs to XCD floor(8 r / tiles).
-__device__ __forceinline__ void xcd_band(int count, int unit, int x, int& lo, int& hi) {
-    const int tiles = (count + unit - 1) / unit;
-    lo = min(count, (int)(((long)x * tiles + 7) / 8) * unit);
-    hi = min(count, (int)(((long)(x + 1) * tiles + 7) / 8) * unit);
 }
 
 // Eq. 5 in fp64 from a dot product and the two squared norms; zero vector -> cosine 0.
