@@ -206,10 +206,10 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const uint32_t fragB0 = (uint32_t)((TILE_R + wc * 64 + l32_) * SLICE_BYTES);
 
     // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (XCD = workgroup id mod 8) and
-    // every XCD has its own L2, so each XCD takes a contiguous eighth of the tile sequence:
-    // column by column for the (symmetric) density pass, row by row for the candidate pass.  An
-    // XCD then works on few tile columns (rows) whose keys stay in its L2, and - counted in
-    // tiles, not in rows - every XCD gets the same load.
+    // every XCD has its own L2, so each XCD takes a contiguous eighth of the tile sequence,
+    // column by column.  An XCD then works on few tile columns, whose keys stay in its L2 beside
+    // the row operand (all kept tokens, or all centres), and - counted in tiles, not in rows -
+    // every XCD gets the same load.
     const int xcd = blockIdx.x & 7;
     const long nTiles = (long)tilesR * tilesC;
     const bool banded = nTiles >= 8 && (gridDim.x & 7) == 0;
@@ -220,8 +220,8 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 
     float far = 0.0f;              // most negative density exponent seen = largest distance (density pass)
     for (int tl = t_first; tl < l_hi; tl += t_step) {
-        const int rowBase = ((MODE == MODE_DENSITY) ? tl % tilesR : tl / tilesC) * TILE_R;
-        const int colBase = ((MODE == MODE_DENSITY) ? tl / tilesR : tl % tilesC) * TILE_C;
+        const int rowBase = (tl % tilesR) * TILE_R;
+        const int colBase = (tl / tilesR) * TILE_C;
 
         // byte offsets of this lane's NB DMA rows; rows past the end are clamped to the last one
         // (their products are discarded in the epilogue)
