@@ -246,17 +246,27 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
         if (lane == 0) hnorm[g] = sqrt(sst);
     }
     __syncthreads();
-    if (threadIdx.x < n_q) {
-        const int j = threadIdx.x;
+    // the workgroup's softmax partial per head: thread (head j, token t) = 16 * j + t takes one
+    // exponential, the 16 lanes of a head combine (SCORE_TOK_PER_WG * PACT_MAX_QHEADS threads at most)
+    static_assert(SCORE_TOK_PER_WG == 16 && SCORE_TOK_PER_WG * PACT_MAX_QHEADS <= 1024, "one thread per (token, head)");
+    {
+        const int j = threadIdx.x >> 4, t = threadIdx.x & 15;
         const int cnt = min(SCORE_TOK_PER_WG, sg.n - t0);
-        double m = s_l[0][j];
-        for (int t = 1; t < cnt; ++t) m = fmax(m, s_l[t][j]);
-        double s = 0.0;
-        for (int t = 0; t < cnt; ++t) s += exp(s_l[t][j] - m);
-        const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
-        double* out = sm_part + (((size_t)b * smwg + blockIdx.x) * n_q + j) * 2;
-        out[0] = m;
-        out[1] = s;
+        if (j < n_q) {                                             // (whole groups of 16 lanes take the branch)
+            const double v = t < cnt ? s_l[t][j] : -INFINITY;
+            double m = v;
+#pragma unroll
+            for (int sft = 1; sft <= 8; sft <<= 1) m = fmax(m, __shfl_xor(m, sft, 64));
+            double e = t < cnt ? exp(v - m) : 0.0;
+#pragma unroll
+            for (int sft = 1; sft <= 8; sft <<= 1) e += __shfl_xor(e, sft, 64);
+            if (t == 0) {
+                const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+                double* out = sm_part + (((size_t)b * smwg + blockIdx.x) * n_q + j) * 2;
+                out[0] = m;
+                out[1] = e;
+            }
+        }
     }
 }
 

@@ -144,6 +144,7 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
         }
         __syncthreads();
         const int m_eff = no_merge ? 1 : m;
+        const double inv_m = 1.0 / (double)(m_eff > 0 ? m_eff : 1);
         for (int e = tid * EPL; e < h; e += 512 * EPL) {
             double acc[EPL];
 #pragma unroll
@@ -177,9 +178,11 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
                     for (int i = 0; i < EPL; ++i) acc[i] += x[i];
                 }
             }
+            // Eq. 10: the mean as sum * (1/m): an fp64 division per element would be most of this
+            // kernel's arithmetic, and the result is rounded to the output type right after
             double outv[EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : (m_eff == 0 ? 0.0 : acc[i] / (double)m_eff);
+            for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : (m_eff == 0 ? 0.0 : acc[i] * inv_m);
             StoreOut<ODT>::template put<EPL>(merged + ((size_t)sg.base + c) * (size_t)h * (ODT == PACT_BF16 ? 2 : 4),
                                              (size_t)e, outv);
         }
