@@ -88,6 +88,11 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :: "v"(gptr), "s"(lds_base) : "memory");
 }
+// The same with the address as a scalar base plus a 32-bit offset per lane (one add per fetch).
+__device__ __forceinline__ void dma16_off(const char* base, uint32_t off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(off), "s"(base), "s"(lds_base) : "memory");
+}
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
@@ -223,34 +228,40 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         const int rowBase = (tl % tilesR) * TILE_R;
         const int colBase = (tl / tilesR) * TILE_C;
 
-        // byte offsets of this lane's NB DMA rows; rows past the end are clamped to the last one
-        // (their products are discarded in the epilogue)
+        // byte offsets of this lane's 16 bytes in the first slice of its NB DMA rows; rows past the
+        // end are clamped to the last one (their products are discarded in the epilogue)
         uint32_t ro[NB];
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
             const int r = dma_row0 + 8 * k;
             const int tok = (r >= TILE_R) ? idxC[min(colBase + r - TILE_R, nB - 1)] : idxR[min(rowBase + r, nA - 1)];
-            ro[k] = (uint32_t)tok * (uint32_t)row_bytes;
+            // (with the lane's chunk: the swizzle term depends on the row only through
+            //  (row >> 1) & 7, and rows advance by 8 per block)
+            ro[k] = (uint32_t)tok * (uint32_t)row_bytes + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
         }
-        // logical chunk this lane fetches: the swizzle term depends on the row only through
-        // (row >> 1) & 7 = (lane >> 4) & 3 plus 4 * (k & 1)  (rows advance by 8 per block)
         if (tid < TILE_R) sRinv[tid] = rinv[idxR[min(rowBase + tid, nA - 1)]];
         float rj_pre[2];                                    // 1/|u_j| of this lane's two columns (used in the epilogue)
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
 
-        auto issue_block = [&](int s, int k) __attribute__((always_inline)) {   // block k of slice s -> ring slot s % NSTAGE
+        auto issue = [&](int s) __attribute__((always_inline)) {      // slice s -> ring slot s % NSTAGE
             const uint32_t slot = dma_lds0 + (uint32_t)((s % NSTAGE) * STAGE_BYTES);
-            const int r = dma_row0 + 8 * k;
-            const int chunk = (lane & 7) ^ ((r >> 1) & 7);
-            const int byte0 = s * SLICE_BYTES + chunk * 16;
-            const bool ok = byte0 < row_bytes;                         // past the key width: zeros
-            const char* src = ok ? keys + (ro[k] + (uint32_t)byte0) : ga.zeros;
-            dma16(src, slot + k * 1024);
-        };
-        auto issue = [&](int s) __attribute__((always_inline)) {
+            if ((s + 1) * SLICE_BYTES <= row_bytes) {
+                // a whole slice: scalar base + (row offset + chunk) + slice offset, one add per block.
+                // (These instructions sit between the barrier and the first MFMA of every
+                //  wavefront, i.e. the matrix cores idle meanwhile: they are kept few.)
 #pragma unroll
-            for (int k = 0; k < NB; ++k) issue_block(s, k);
+                for (int k = 0; k < NB; ++k) dma16_off(keys, ro[k] + (uint32_t)(s * SLICE_BYTES), slot + k * 1024);
+            } else {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    const int chunk = (lane & 7) ^ (((dma_row0 + 8 * k) >> 1) & 7);
+                    const int byte0 = s * SLICE_BYTES + chunk * 16;
+                    const bool ok = byte0 < row_bytes;                 // past the key width: zeros
+                    const char* src = ok ? keys + (ro[k] - (uint32_t)(chunk * 16) + (uint32_t)byte0) : ga.zeros;
+                    dma16(src, slot + k * 1024);
+                }
+            }
         };
 
         PACT_STAMP(1);
