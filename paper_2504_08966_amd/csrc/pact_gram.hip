@@ -282,7 +282,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             if (s + AHEAD - 1 < nSlices) wait_vmcnt<NB * (AHEAD - 1)>();
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();      // ... for every wavefront; and slot (s-1)%NSTAGE is free
-            if (s + AHEAD < nSlices) issue(s + AHEAD);
 
             // the fragments of k-group g+1 are read from LDS while the MFMAs of group g run
             const lds_char* st = ring + (s % NSTAGE) * STAGE_BYTES;
@@ -297,6 +296,9 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             constexpr int MF = (DT == PACT_BF16) ? 1 : 4;       // MFMA instructions per fragment pair
             load_frags(0, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, MI + 2, 0);
+            // (the next fetches are issued while the first fragments are on their way from the LDS:
+            //  nothing else can fill the time between the barrier and the first MFMA)
+            if (s + AHEAD < nSlices) issue(s + AHEAD);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 if (g + 1 < 4) load_frags(g + 1, (g + 1) & 1);
