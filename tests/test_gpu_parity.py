@@ -311,6 +311,36 @@ def test_zero_norm_key_and_equal_scores():
     assert g["rep"]["n_kept"] == 12 and list(g["center_idx"]) == [0] and list(g["counts"]) == [12]
 
 
+def test_recovery_with_more_tied_centres_than_one_list_holds():
+    # 40 orthonormal centres; pruned tokens exactly equidistant from all of them (or from the last
+    # 20), so the fp32 screen of the recovery leaves more candidates than it lists in one turn
+    k = np.zeros((43, 1, 64), dtype=np.float32)
+    k[np.arange(40), 0, np.arange(40)] = 1.0
+    k[40, 0, :40] = 1.0                       # ties with every centre -> centre 0
+    k[41, 0, 20:40] = 1.0                     # ties with centres 20..39 -> centre 20
+    k[42, 0, :40] = 1.0
+    k[42, 0, 25] = 1.0 + 2.0 ** -20           # a hair closer to centre 25: below fp32 resolution of the cosine
+    h = np.random.default_rng(8).normal(size=(43, 32)).astype(np.float32)
+    h[40:] *= 1e-3                            # lowest scores -> pruned
+    s = _mk(k, hidden=h, queries=np.zeros_like(k))
+    g = gu.gpu_reduce(s, 0.5, alpha=1.8, lam=0.07)
+    o = oracle_reduce(s, 0.5, alpha=1.8, lam=0.07)
+    assert_same(g, o, s, "tied centres")
+    assert list(g["pruned_idx"]) == [40, 41, 42] and g["rep"]["n_centers"] == 40
+    assert [int(g["cluster_id"][i]) for i in (40, 41, 42)] == [0, 20, 25]
+
+
+def test_recovery_with_more_than_64_groups_of_centres():
+    # a cutoff so small that almost every kept token is a centre: more than 4096 centres, i.e.
+    # more than 64 groups of 64 per pruned token
+    s = _random_sample(31, 7000, 1, 1, 16, 64, 0.3, "f32")
+    d_c, alpha = float(np.float32(0.0005)), 60.0
+    g = gu.gpu_reduce(s, d_c, alpha=alpha)
+    o = oracle_reduce(s, d_c, alpha=alpha)
+    assert g["rep"]["n_centers"] > 4096 and 0 < g["rep"]["n_reincorporated"] < g["rep"]["n_pruned"]
+    assert_same(g, o, s, "many centres")
+
+
 # ------------------------------------------------------------------ targeted cases
 
 def test_nearest_centre_may_come_later_in_the_density_order():
