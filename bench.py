@@ -34,8 +34,10 @@ def algorithmic_work(kernel: str, n, h, dk, q, C, n_reinc, key_bytes, hid_bytes,
         return "mfma", float(q) * q * dk, "flop"
     if kernel == "gram_candidates":
         return "mfma", 2.0 * (n - q) * C * dk, "flop"
-    if kernel == "score_logits":          # read H and K_pre once, write logits and norms
-        return "hbm", n * h * hid_bytes + n * dk * key_bytes + n * (n_q + 1) * 8, "B"
+    if kernel == "qglobal_hnorm":         # read H once (norms) and the query partials, write norms and the global query
+        return "hbm", n * h * hid_bytes + 512 * n_q * d_h * 8 + n * 8 + n_q * d_h * 8, "B"
+    if kernel == "score_logits":          # read K_pre once, write logits
+        return "hbm", n * dk * key_bytes + n * n_q * 8, "B"
     if kernel == "qglobal_partial":
         return "hbm", n * n_q * d_h * key_bytes, "B"
     if kernel == "merge_mean":            # read member rows once, write C merged rows
@@ -279,7 +281,7 @@ def main():
 
     # the bandwidth-bound stages, warm (inputs still in the caches from the previous step) and cold
     hbm_stages = {}
-    for k in ("score_logits", "merge_mean", "prep"):
+    for k in ("qglobal_hnorm", "merge_mean", "prep"):
         kk = "key_prep" if k == "prep" else k
         bound, work, unit = algorithmic_work(kk, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
         if k == "prep":

@@ -106,59 +106,93 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     }
 }
 
-// Eq. 1, pass 2: sum the chunk partials in a fixed order and divide by n.
-// grid (ceil(qcols/64), B), block 1024 = 64 columns x 16 slices of the chunk range.
-__global__ __launch_bounds__(1024) void qglobal_final_kernel(Batch bt, int qcols,
+// Eq. 1, pass 2, and the hidden-state norms of Eq. 2, two independent jobs in one launch (the
+// first is a handful of blocks; the second streams H, the stage's one large read, which needs
+// neither the global query nor the logits and so need not wait for them):
+//   blocks [0, nq_blocks): the global query - the chunk partials summed in a fixed order and
+//       divided by n (64 columns x 16 slices of the chunk range per block), or, when the caller
+//       supplied the global query ([B, qcols]), its widening to fp64 (1024 columns per block);
+//   the other blocks: |h_i|_2 in fp64, one wavefront per token, 16 tokens per block.
+// grid (nq_blocks + ceil(n_max/16), B), block 1024.
+template <int HDT, int QDT>
+__global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols, int q_per_token, int nq_blocks,
                                                              const double* __restrict__ qg_part,
-                                                             double* __restrict__ qg) {
+                                                             const char* __restrict__ q_given,
+                                                             double* __restrict__ qg,
+                                                             const char* __restrict__ hidden, int h,
+                                                             double* __restrict__ hnorm) {
     __shared__ double s_p[16][64];
     const int b = blockIdx.y;
-    const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + cl;
-    constexpr int PER = QG_CHUNKS / 16;
-    double acc = 0.0;
-    if (c < qcols) {
-        const double* in = qg_part + ((size_t)b * QG_CHUNKS + slice * PER) * qcols + c;
-        double v[PER];
+    const Seg sg = bt.s[b];
+    if ((int)blockIdx.x < nq_blocks) {
+        if (q_per_token) {
+            const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+            const int c = blockIdx.x * 64 + cl;
+            constexpr int PER = QG_CHUNKS / 16;
+            double acc = 0.0;
+            if (c < qcols) {
+                const double* in = qg_part + ((size_t)b * QG_CHUNKS + slice * PER) * qcols + c;
+                double v[PER];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) v[k] = in[(size_t)k * qcols];
+                for (int k = 0; k < PER; ++k) v[k] = in[(size_t)k * qcols];
 #pragma unroll
-        for (int k = 0; k < PER; ++k) acc += v[k];
+                for (int k = 0; k < PER; ++k) acc += v[k];
+            }
+            s_p[slice][cl] = acc;
+            __syncthreads();
+            if (slice == 0 && c < qcols) {
+                double t = 0.0;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) t += s_p[k][cl];
+                qg[(size_t)b * qcols + c] = t / (double)sg.n;
+            }
+        } else {
+            const int c = blockIdx.x * 1024 + threadIdx.x;
+            if (c < qcols) {
+                const char* p = q_given + ((size_t)b * qcols + c) * Elem<QDT>::BYTES;
+                float f;
+                if (QDT == PACT_BF16) f = __uint_as_float((uint32_t)(*(const uint16_t*)p) << 16);
+                else f = *(const float*)p;
+                qg[(size_t)b * qcols + c] = (double)f;
+            }
+        }
+        return;
     }
-    s_p[slice][cl] = acc;
-    __syncthreads();
-    if (slice == 0 && c < qcols) {
-        double t = 0.0;
+    const int lane = threadIdx.x & 63;
+    const int i = (blockIdx.x - nq_blocks) * SCORE_TOK_PER_WG + (threadIdx.x >> 6);
+    if (i >= sg.n) return;
+    const size_t g = (size_t)sg.base + i;
+    const char* hp = hidden + g * (size_t)h * Elem<HDT>::BYTES;
+    constexpr int HE = Elem<HDT>::EPL;
+    // 8 independent 16-byte loads in flight per lane
+    double ss[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int e0 = lane * HE; e0 < h; e0 += 8 * 64 * HE) {
+        uint4 v[8];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) t += s_p[k][cl];
-        qg[(size_t)b * qcols + c] = t / (double)bt.s[b].n;
+        for (int u = 0; u < 8; ++u) {
+            const int e = e0 + u * 64 * HE;
+            v[u] = (e < h) ? *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            double x[8];
+            Elem<HDT>::widen(v[u], x);
+#pragma unroll
+            for (int k = 0; k < HE; ++k) ss[u & 3] = fma(x[k], x[k], ss[u & 3]);
+        }
     }
-}
-
-// Caller supplied the global query ([B, qcols]): widen it to fp64.
-template <int DT>
-__global__ __launch_bounds__(256) void qglobal_copy_kernel(Batch bt, const char* __restrict__ q, int qcols,
-                                                            double* __restrict__ qg) {
-    const int b = blockIdx.y;
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= qcols) return;
-    const char* p = q + ((size_t)b * qcols + c) * Elem<DT>::BYTES;
-    float f;
-    if (DT == PACT_BF16) f = __uint_as_float((uint32_t)(*(const uint16_t*)p) << 16);
-    else f = *(const float*)p;
-    qg[(size_t)b * qcols + c] = (double)f;
+    const double sst = wave_sum_f64((ss[0] + ss[1]) + (ss[2] + ss[3]));
+    if (lane == 0) hnorm[g] = sqrt(sst);
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 2, pass 1: one wavefront per token computes |h_i|_2 and the n_q logits
-// k_i^(g(j)) . Qg^(j); the workgroup (SCORE_TOK_PER_WG tokens) then leaves one online-softmax
-// partial (max, sum of exp) per head.  grid (ceil(n_max/16), B), block 1024.
-template <int HDT, int KDT>
-__global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char* __restrict__ hidden, int h,
-                                                            const char* __restrict__ keys, int n_kv, int d_h,
+// Eq. 2, pass 1: one wavefront per token computes the n_q logits k_i^(g(j)) . Qg^(j); the
+// workgroup (SCORE_TOK_PER_WG tokens) then leaves one online-softmax partial (max, sum of exp)
+// per head.  grid (ceil(n_max/16), B), block 1024.
+template <int KDT>
+__global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char* __restrict__ keys, int n_kv, int d_h,
                                                             int n_q, const double* __restrict__ qg,
                                                             double* __restrict__ logits,
-                                                            double* __restrict__ hnorm,
                                                             double* __restrict__ sm_part) {
     __shared__ double s_l[SCORE_TOK_PER_WG][PACT_MAX_QHEADS];
     const int b = blockIdx.y;
@@ -170,47 +204,24 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
     const int qcols = n_q * d_h;
     const int rep = n_q / n_kv;
     const double* qgb = qg + (size_t)b * qcols;
-    const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
     const size_t krow = (size_t)n_kv * d_h * Elem<KDT>::BYTES;
-    constexpr int HE = Elem<HDT>::EPL;
 
     // Fast path (the usual shapes: key row of at most 1 KB, one query head per key head, a
-    // power-of-two number of 16-byte chunks per head): the whole key row is one load per lane,
-    // issued together with the hidden-state loads, and a head's logit is a reduction over the
-    // few lanes that hold it.
+    // power-of-two number of 16-byte chunks per head): the whole key row is one load per lane
+    // and a head's logit is a reduction over the few lanes that hold it.
     const int lph = (int)((size_t)d_h * Elem<KDT>::BYTES / 16);      // lanes (chunks) per head
     const bool fast = rep == 1 && krow <= 1024 && (size_t)lph * 16 == (size_t)d_h * Elem<KDT>::BYTES &&
                       lph >= 1 && (lph & (lph - 1)) == 0;
     const int i = t0 + wave;
     if (i < sg.n) {
         const size_t g = (size_t)sg.base + i;
-        const char* hp = hidden + g * hrow;
         const char* kp = keys + g * krow;
-        const bool klane = (size_t)lane * 16 < krow;
-        uint4 kv = make_uint4(0, 0, 0, 0);
-        if (fast && klane) kv = *(const uint4*)(kp + (size_t)lane * 16);
-        // hidden-state norm: 8 independent 16-byte loads in flight per lane
-        double ss[4] = {0.0, 0.0, 0.0, 0.0};
-        for (int e0 = lane * HE; e0 < h; e0 += 8 * 64 * HE) {
-            uint4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int e = e0 + u * 64 * HE;
-                v[u] = (e < h) ? *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                double x[8];
-                Elem<HDT>::widen(v[u], x);
-#pragma unroll
-                for (int k = 0; k < HE; ++k) ss[u & 3] = fma(x[k], x[k], ss[u & 3]);
-            }
-        }
-        const double sst = wave_sum_f64((ss[0] + ss[1]) + (ss[2] + ss[3]));
         if (fast) {
             // lane l holds elements [l * EPL, (l + 1) * EPL) of the row, i.e. of head l / lph
+            const bool klane = (size_t)lane * 16 < krow;
             double acc = 0.0;
             if (klane) {
+                const uint4 kv = *(const uint4*)(kp + (size_t)lane * 16);
                 double x[8];
                 Elem<KDT>::widen(kv, x);
                 const double* qq = qgb + lane * Elem<KDT>::EPL;
@@ -243,7 +254,6 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
                 }
             }
         }
-        if (lane == 0) hnorm[g] = sqrt(sst);
     }
     __syncthreads();
     // the workgroup's softmax partial per head: thread (head j, token t) = 16 * j + t takes one
@@ -515,36 +525,35 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
 }
 
 template <int HDT>
-static int launch_logits_k(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
-    dim3 grid((bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
-    if (in.k_dt == PACT_BF16)
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_BF16>), grid, dim3(1024), st, bt,
-                    (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
-                    w.qg, w.logits, w.hnorm, w.sm_part);
+static int launch_qglobal_hnorm(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
+    const int qcols = in.n_q * in.d_h;
+    const int nq_blocks = in.q_per_token ? (qcols + 63) / 64 : (qcols + 1023) / 1024;
+    dim3 grid(nq_blocks + (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
+    if (in.q_dt == PACT_BF16)
+        PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_BF16>), grid, dim3(1024), st, bt, qcols,
+                    in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
+                    in.h, w.hnorm);
     else
-        PACT_LAUNCH("score_logits", (score_logits_kernel<HDT, PACT_F32>), grid, dim3(1024), st, bt,
-                    (const char*)in.hidden, in.h, (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q,
-                    w.qg, w.logits, w.hnorm, w.sm_part);
+        PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_F32>), grid, dim3(1024), st, bt, qcols,
+                    in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
+                    in.h, w.hnorm);
     return PACT_OK;
 }
 
 // Scores for every sample.  The per-token query pass (Eq. 1 pass 1) must already have run
 // (launch_prep with q != nullptr) when in.q_per_token is set.
 int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
-    const int qcols = in.n_q * in.d_h;
-    if (in.q_per_token) {
-        PACT_LAUNCH("qglobal_final", qglobal_final_kernel, dim3((qcols + 63) / 64, bt.B), dim3(1024), st,
-                    bt, qcols, w.qg_part, w.qg);
-    } else {
-        if (in.q_dt == PACT_BF16)
-            PACT_LAUNCH("qglobal_copy", qglobal_copy_kernel<PACT_BF16>, dim3((qcols + 255) / 256, bt.B),
-                        dim3(256), st, bt, (const char*)in.q, qcols, w.qg);
-        else
-            PACT_LAUNCH("qglobal_copy", qglobal_copy_kernel<PACT_F32>, dim3((qcols + 255) / 256, bt.B),
-                        dim3(256), st, bt, (const char*)in.q, qcols, w.qg);
-    }
-    return (in.h_dt == PACT_BF16) ? launch_logits_k<PACT_BF16>(bt, w, in, st)
-                                  : launch_logits_k<PACT_F32>(bt, w, in, st);
+    int rc = (in.h_dt == PACT_BF16) ? launch_qglobal_hnorm<PACT_BF16>(bt, w, in, st)
+                                    : launch_qglobal_hnorm<PACT_F32>(bt, w, in, st);
+    if (rc) return rc;
+    dim3 grid((bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
+    if (in.k_dt == PACT_BF16)
+        PACT_LAUNCH("score_logits", score_logits_kernel<PACT_BF16>, grid, dim3(1024), st, bt,
+                    (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part);
+    else
+        PACT_LAUNCH("score_logits", score_logits_kernel<PACT_F32>, grid, dim3(1024), st, bt,
+                    (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part);
+    return PACT_OK;
 }
 
 int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st) {
