@@ -341,6 +341,23 @@ def test_recovery_with_more_than_64_groups_of_centres():
     assert_same(g, o, s, "many centres")
 
 
+def test_many_equal_scores_around_the_percentile():
+    # 1500 tokens that share one of three scores: the bin of the select's histogram that holds
+    # the threshold has more keys than are ranked directly
+    r = np.random.default_rng(12)
+    base_k = r.normal(size=(3, 2, 16)).astype(np.float32)
+    base_h = r.normal(size=(3, 32)).astype(np.float32) * np.array([[1.0], [1.0 + 2.0 ** -12], [1.0 + 2.0 ** -11]], dtype=np.float32)
+    base_h[1:] = base_h[0] * np.array([[1.0 + 2.0 ** -12], [1.0 + 2.0 ** -11]], dtype=np.float32)
+    which = r.integers(0, 3, 1500)
+    k = base_k[0][None].repeat(1500, 0)           # one key for all: uniform softmax, score = norm / n
+    h = base_h[which]
+    s = _mk(k, hidden=h, queries=np.zeros_like(k))
+    for lam in (0.2, 0.5, 0.9):
+        g = gu.gpu_reduce(s, 0.1, lam=lam)
+        o = oracle_reduce(s, 0.1, lam=lam)
+        assert_same(g, o, s, f"equal scores lam={lam}")
+
+
 # ------------------------------------------------------------------ targeted cases
 
 def test_nearest_centre_may_come_later_in_the_density_order():
