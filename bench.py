@@ -86,6 +86,20 @@ def other_configs(P, gen, torch, np):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps * 1e6
 
+    def kernel_table(fn, steps=10):
+        """us per call of every kernel (the library's event brackets), largest first."""
+        P.pact_profile_enable(True)
+        P.pact_profile_reset()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        recs = P.pact_profile_read(steps * 64)
+        P.pact_profile_enable(False)
+        tot = {}
+        for k, ms in recs:
+            tot[k] = tot.get(k, 0.0) + ms
+        return {k: round(v / steps * 1e3, 1) for k, v in sorted(tot.items(), key=lambda kv: -kv[1])}
+
     out = {}
     for name, steps in (("img_0p5b", 200), ("vid_long", 20)):
         cfg = gen.CONFIGS[name]
@@ -101,7 +115,9 @@ def other_configs(P, gen, torch, np):
         r = P.read_report(o["rep"])
         assert r["n_kept"] == m["q"] and r["n_centers"] == m["C"], (name, r, m)
         out[name] = {"n": sm.n, "batch": 1, "us_per_call": round(us, 1), "samples_per_s": round(1e6 / us, 1),
-                     "q": r["n_kept"], "C": r["n_centers"]}
+                     "q": r["n_kept"], "C": r["n_centers"],
+                     "kernels_us": kernel_table(lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv,
+                                                                      prm, ws=ws, out=o))}
         del hid, ks, qs, ws, o
     for name, samples, steps in (("vid_7b_batch8", gen.make_batch("vid_7b", 0), 30),
                                  ("varlen16", gen.make_varlen_batch(0), 30)):
@@ -123,7 +139,9 @@ def other_configs(P, gen, torch, np):
         assert [(r["n_kept"], r["n_centers"]) for r in reps] == exp, (name, reps, exp)
         out[name] = {"n_total": cu[-1], "batch": len(samples), "us_per_call": round(us, 1),
                      "us_per_sample": round(us / len(samples), 1),
-                     "samples_per_s": round(len(samples) * 1e6 / us, 1)}
+                     "samples_per_s": round(len(samples) * 1e6 / us, 1),
+                     "kernels_us": kernel_table(lambda: P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h,
+                                                                             cfg0.n_kv, cu, prms, ws=ws, out=o))}
         del hid, ks, qs, ws, o
     return out
 
