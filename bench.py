@@ -322,7 +322,7 @@ def main():
         except Exception:
             cores = 1
         reps, t_cpu = 0, 0.0
-        while reps < 3 or (t_cpu < 10.0 and reps < 8):
+        while reps < 3 or (t_cpu < 12.0 and reps < 40):        # about 12 s of CPU work
             t1 = time.perf_counter()
             po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5)
             t_cpu += time.perf_counter() - t1
