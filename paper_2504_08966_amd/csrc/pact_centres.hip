@@ -386,6 +386,15 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
 
     if (tid == 0) { s_nlong = 0; s_nover = 0; s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0; }
     __syncthreads();
+    // the token indices this thread will publish at the end (words wave, wave + 16, ...): fetched
+    // now, so that the last phase does not start with a trip to memory
+    const int32_t* ix = idx + sg.base;
+    int pub_ix[RESOLVE_CACHED];
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) {
+        const int p = ((wave + 16 * k) << 6) + lane;
+        pub_ix[k] = (p < q) ? ix[p] : 0;
+    }
     uint2 h[RESOLVE_CACHED];
 #pragma unroll
     for (int k = 0; k < RESOLVE_CACHED; ++k) {
@@ -578,9 +587,8 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     __syncthreads();
     uint32_t* st = status + (size_t)b * bt.n_max;
     int32_t* cn = cnum + (size_t)b * bt.n_max;
-    const int32_t* ix = idx + sg.base;
     int32_t* co = center_idx + sg.base;
-    for (int w = wave; w < Wq; w += 16) {
+    auto publish_word = [&](int w, int tok, bool have_tok) __attribute__((always_inline)) {
         const int p = (w << 6) + lane;
         const unsigned char sv = (p < q) ? s_st[p] : (unsigned char)ST_NOT;
         const bool isc = sv == ST_CENTER;
@@ -589,9 +597,13 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         if (p < q) {
             st[p] = sv;
             cn[p] = isc ? c : -1;
-            if (isc) co[c] = ix[p];
+            if (isc) co[c] = have_tok ? tok : ix[p];
         }
-    }
+    };
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k)
+        if (wave + 16 * k < Wq) publish_word(wave + 16 * k, pub_ix[k], true);
+    for (int w = wave + 16 * RESOLVE_CACHED; w < Wq; w += 16) publish_word(w, 0, false);
     if (tid == 0) {
         rep[b].n_centers = s_wcnt[Wq];
         rep[b].rounds = rounds;
