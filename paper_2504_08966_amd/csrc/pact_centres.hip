@@ -165,7 +165,6 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
     const Seg sg = bt.s[b];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int q = clamp_count(rep[b].n_kept, sg.n);
     if (blockIdx.x < REFINE_BLOCKS) {
         const int gw = blockIdx.x * 4 + wave;
         const int nw = REFINE_BLOCKS * 4;
@@ -210,13 +209,24 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
         return;
     }
     const int p0 = (blockIdx.x - REFINE_BLOCKS) * 64;
-    if (p0 >= q) return;
     const int p = p0 + lane;
+    // the first 32 rows of partials are requested before the number of kept tokens is known
+    // (they lie inside the workspace for any p < n_max; what is past the last row is masked)
+    const double* in = rho_part + (size_t)b * bt.W * bt.n_max + p;
+    double v0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int r = wave + 4 * u;
+        v0[u] = (p < bt.n_max && r < bt.W) ? in[(size_t)r * bt.n_max] : 0.0;
+    }
+    const int q = clamp_count(rep[b].n_kept, sg.n);
+    if (p0 >= q) return;
     const int nrt = (q + GRAM_RHO_ROWS - 1) / GRAM_RHO_ROWS;
     double acc = 0.0;
     if (p < q) {
-        const double* in = rho_part + (size_t)b * bt.W * bt.n_max + p;
-        for (int r0 = wave; r0 < nrt; r0 += 32) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += (wave + 4 * u < nrt) ? v0[u] : 0.0;
+        for (int r0 = wave + 32; r0 < nrt; r0 += 32) {
             double v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -292,9 +302,9 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
                                                           uint16_t* __restrict__ preds,
                                                           uint2* __restrict__ heads) {
     const int b = blockIdx.y;
-    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
     const int lane = threadIdx.x & 63;
     const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
     if (p >= q) return;
     const double* r = rho + (size_t)b * bt.n_max;
     const double rp = r[p];
@@ -370,10 +380,18 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     __shared__ int s_flag[3], s_nlong, s_nover;
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
-    const int q = clamp_count(rep[b].n_kept, sg.n);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
+    // the heads of this thread's first tokens are requested before the number of kept tokens is
+    // known (they lie inside the workspace for any position below n_max): one trip less
+    uint2 h[RESOLVE_CACHED];
+#pragma unroll
+    for (int k = 0; k < RESOLVE_CACHED; ++k) {
+        const int p = tid + 1024 * k;
+        h[k] = (p < bt.n_max) ? heads[(size_t)b * bt.n_max + p] : make_uint2(0, 0);
+    }
+    const int q = clamp_count(rep[b].n_kept, sg.n);
     const int qpad = (bt.n_max + 63) / 64 * 64;
     lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64]
     lds_u16* s_list = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
@@ -395,12 +413,9 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         const int p = ((wave + 16 * k) << 6) + lane;
         pub_ix[k] = (p < q) ? ix[p] : 0;
     }
-    uint2 h[RESOLVE_CACHED];
 #pragma unroll
-    for (int k = 0; k < RESOLVE_CACHED; ++k) {
-        const int p = tid + 1024 * k;
-        h[k] = (p < q) ? hd[p] : make_uint2(0, 0);
-    }
+    for (int k = 0; k < RESOLVE_CACHED; ++k)
+        if (tid + 1024 * k >= q) h[k] = make_uint2(0, 0);
     // set-up = round 1, and the two token lists (appended a wavefront at a time)
     auto setup = [&](int p, uint32_t hx) __attribute__((always_inline)) {
         const int c = hx & 0xFFFF;
@@ -650,19 +665,23 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
     int32_t* cluster_counts = a.cluster_counts;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    const int q = clamp_count(rep[b].n_kept, sg.n);
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int p = blk * 4 + wave;
+    const int q = clamp_count(rep[b].n_kept, sg.n);
     if (p >= q) return;
     const int32_t* ix = idx + sg.base;
     const int32_t* cn = cnum + (size_t)b * bt.n_max;
     const uint32_t* st = status + (size_t)b * bt.n_max;
     const double* nnb = nn + sg.base;
+    const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
+    const uint64_t* cm = cmask + (size_t)b * bt.W;
     const int tok = ix[p];
+    const uint32_t stp = st[p];
+    const int cnp = cn[p];
     int cid;
-    if (st[p] == ST_CENTER) {
-        cid = cn[p];
+    if (stp == ST_CENTER) {
+        cid = cnp;
     } else {
         const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
         const char* kb = keys + (size_t)sg.base * row_bytes;
@@ -671,8 +690,6 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
         double best = INFINITY;
         int bestj = 0x7FFFFFFF;
         auto tok_of = [&](int j) { return ix[j]; };
-        const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
-        const uint64_t* cm = cmask + (size_t)b * bt.W;
         const int Wq = (q + 63) >> 6;
         int nbuf = 0, ntot = 0;
         for (int w0 = 0; w0 < Wq; w0 += 64) {
@@ -759,10 +776,11 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
     pact_report* rep = a.rep;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
-              C = clamp_count(rep[b].n_centers, q);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
+    const int t_first = blk * 16 + (tid >> 4);
+    const int q = clamp_count(rep[b].n_kept, sg.n), np = clamp_count(rep[b].n_pruned, sg.n - q),
+              C = clamp_count(rep[b].n_centers, q);
     const size_t row_bytes = (size_t)a.dk * Elem<DT>::BYTES;
     const int nchunk = (int)(row_bytes / 16);
     const char* kb = a.keys + (size_t)sg.base * row_bytes;
@@ -780,7 +798,7 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
     const uint64_t* cw = a.adj + ((size_t)b * bt.n_max + q) * bt.W; // [Wc][np]
     const int part = tid & 15, ts = tid >> 4, gbase = lane & ~15;
     lds_i32* list = s_c + ts * RECOVER_LIST;
-    for (int t = blk * 16 + ts; t < np; t += nblk * 16) {
+    for (int t = t_first; t < np; t += nblk * 16) {
         const int tok = pruned[t];
         int res = -1;                                               // -1: no centre in reach
         if (thr > 0.0 && C > 0) {
@@ -817,8 +835,8 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
                     int n = 0, ntot = 0;
 #pragma unroll 1
                     for (int wb = 0; wb < Wc; wb += 64) {
-                        if (!(wb == 0 && first_batch_loaded)) load_batch(wb);
-                        first_batch_loaded = first_batch_loaded && wb == 0;
+                        if (!first_batch_loaded) load_batch(wb);     // (the first turn starts with the values already here)
+                        first_batch_loaded = false;
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
                             const uint64_t wv = (v[u] >= floor32) ? word[u] : 0ull;

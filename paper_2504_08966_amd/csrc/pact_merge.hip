@@ -25,10 +25,24 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
     int32_t* cnt = cluster_counts + sg.base;
     int32_t* off = offsets + sg.base + b;
     const int32_t* cid = cluster_id + sg.base;
+    // the cluster ids of this thread's tokens (i = tid, tid + 1024, ...): fetched now, beside the
+    // sizes, so that the fill below does not start with a trip to memory
+    constexpr int PRE = 8;
+    int cid_pre[PRE];
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        const int i = tid + 1024 * k;
+        cid_pre[k] = (i < sg.n) ? cid[i] : -1;
+    }
     if (recount) {
         for (int c = tid; c < C; c += 1024) s_cur[c] = 0;
         __syncthreads();
-        for (int i = tid; i < sg.n; i += 1024) {
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) {
+            const int c = cid_pre[k];
+            if (c >= 0 && c < C) atomicAdd(&s_cur[c], 1);
+        }
+        for (int i = tid + 1024 * PRE; i < sg.n; i += 1024) {
             const int c = cid[i];
             if (c >= 0 && c < C) atomicAdd(&s_cur[c], 1);
         }
@@ -69,7 +83,12 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
     if (C == 0 && tid == 0) off[0] = 0;
     __syncthreads();
     int32_t* mem = members + sg.base;
-    for (int i = tid; i < sg.n; i += 1024) {
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        const int c = cid_pre[k];
+        if (c >= 0 && c < C) mem[atomicAdd(&s_cur[c], 1)] = tid + 1024 * k;
+    }
+    for (int i = tid + 1024 * PRE; i < sg.n; i += 1024) {
         const int c = cid[i];
         if (c >= 0 && c < C) mem[atomicAdd(&s_cur[c], 1)] = i;
     }
@@ -117,20 +136,25 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
     constexpr int EPL = Elem<HDT>::EPL;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    const int C = clamp_count(rep[b].n_centers, sg.n);
     const int tid = threadIdx.x;
+    // size and offset of this block's first cluster are requested before the number of clusters
+    // is known (both arrays have an entry for every index below n): one trip less
+    const int c_first = blockIdx.x;
+    const int m_ahead = (c_first < sg.n) ? cluster_counts[sg.base + c_first] : 0;
+    const int off_ahead = (c_first < sg.n) ? offsets[sg.base + b + c_first] : 0;
+    const int C = clamp_count(rep[b].n_centers, sg.n);
     const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
     const char* hb = hidden + (size_t)sg.base * hrow;
     const bool no_merge = (sg.flags & PACT_FLAG_NO_MERGE) != 0;
 
     for (int c = blockIdx.x; c < C; c += gridDim.x) {
-        int m = cluster_counts[sg.base + c];
+        int m = (c == c_first) ? m_ahead : cluster_counts[sg.base + c];
         bool in_lds = true;
         __syncthreads();                       // previous cluster's readers are done with the LDS lists
         if (no_merge) {
             if (tid == 0) s_sorted[0] = center_idx[sg.base + c];
         } else if (m <= MERGE_LDS_MEMBERS) {
-            const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
+            const int32_t* mem = members + sg.base + ((c == c_first) ? off_ahead : offsets[sg.base + b + c]);
             for (int k = tid; k < m; k += 512) s_raw[k] = mem[k];
             __syncthreads();
             for (int k = tid; k < m; k += 512) {
