@@ -137,24 +137,19 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int tid = threadIdx.x;
-    // size and offset of this block's first cluster are requested before the number of clusters
-    // is known (both arrays have an entry for every index below n): one trip less
-    const int c_first = blockIdx.x;
-    const int m_ahead = (c_first < sg.n) ? cluster_counts[sg.base + c_first] : 0;
-    const int off_ahead = (c_first < sg.n) ? offsets[sg.base + b + c_first] : 0;
     const int C = clamp_count(rep[b].n_centers, sg.n);
     const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
     const char* hb = hidden + (size_t)sg.base * hrow;
     const bool no_merge = (sg.flags & PACT_FLAG_NO_MERGE) != 0;
 
     for (int c = blockIdx.x; c < C; c += gridDim.x) {
-        int m = (c == c_first) ? m_ahead : cluster_counts[sg.base + c];
+        int m = cluster_counts[sg.base + c];
         bool in_lds = true;
         __syncthreads();                       // previous cluster's readers are done with the LDS lists
         if (no_merge) {
             if (tid == 0) s_sorted[0] = center_idx[sg.base + c];
         } else if (m <= MERGE_LDS_MEMBERS) {
-            const int32_t* mem = members + sg.base + ((c == c_first) ? off_ahead : offsets[sg.base + b + c]);
+            const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
             for (int k = tid; k < m; k += 512) s_raw[k] = mem[k];
             __syncthreads();
             for (int k = tid; k < m; k += 512) {
