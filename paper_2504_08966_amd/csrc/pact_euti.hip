@@ -407,6 +407,12 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
         for (int i = tid; i < n; i += 1024) s_key[i] = ordered_key(s[i]);
     }
     __syncthreads();
+    // this thread's first keys stay in registers for the select (its passes then issue their
+    // histogram updates back to back instead of waiting for an LDS read before each)
+    constexpr int KREG = 8;
+    uint32_t kreg[KREG];
+#pragma unroll
+    for (int u = 0; u < KREG; ++u) kreg[u] = (tid + 1024 * u < n) ? s_key[tid + 1024 * u] : 0u;
 
     int k = (int)floor((double)sg.lambda * (double)n);
     if (k > n - 1) k = n - 1;
@@ -419,7 +425,13 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     __syncthreads();
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        for (int i = tid; i < n; i += 1024) {
+#pragma unroll
+        for (int r = 0; r < KREG; ++r) {
+            const uint32_t u = kreg[r];
+            if (tid + 1024 * r < n && (u & mask) == prefix)
+                atomicAdd(&s_hist[(((u >> shift) & 255) << 4) + (lane & 15)], 1);
+        }
+        for (int i = tid + 1024 * KREG; i < n; i += 1024) {
             const uint32_t u = s_key[i];
             if ((u & mask) == prefix) atomicAdd(&s_hist[(((u >> shift) & 255) << 4) + (lane & 15)], 1);
         }
