@@ -403,16 +403,27 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
             s[i] = v;
             s_key[i] = ordered_key(v);
         }
-    } else {
-        for (int i = tid; i < n; i += 1024) s_key[i] = ordered_key(s[i]);
     }
-    __syncthreads();
     // this thread's first keys stay in registers for the select (its passes then issue their
     // histogram updates back to back instead of waiting for an LDS read before each)
     constexpr int KREG = 8;
     uint32_t kreg[KREG];
+    if (have_scores) {
+        float sv[KREG];
 #pragma unroll
-    for (int u = 0; u < KREG; ++u) kreg[u] = (tid + 1024 * u < n) ? s_key[tid + 1024 * u] : 0u;
+        for (int u = 0; u < KREG; ++u) sv[u] = (tid + 1024 * u < n) ? s[tid + 1024 * u] : 0.0f;   // all in flight
+#pragma unroll
+        for (int u = 0; u < KREG; ++u) {
+            kreg[u] = ordered_key(sv[u]);
+            if (tid + 1024 * u < n) s_key[tid + 1024 * u] = kreg[u];
+        }
+        for (int i = tid + 1024 * KREG; i < n; i += 1024) s_key[i] = ordered_key(s[i]);
+        __syncthreads();
+    } else {
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < KREG; ++u) kreg[u] = (tid + 1024 * u < n) ? s_key[tid + 1024 * u] : 0u;
+    }
 
     int k = (int)floor((double)sg.lambda * (double)n);
     if (k > n - 1) k = n - 1;
