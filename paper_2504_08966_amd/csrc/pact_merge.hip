@@ -20,7 +20,6 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
     __shared__ int s_wtot[16];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
-    const int C = clamp_count(rep[b].n_centers, sg.n);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int32_t* cnt = cluster_counts + sg.base;
     int32_t* off = offsets + sg.base + b;
@@ -34,6 +33,13 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
         const int i = tid + 1024 * k;
         cid_pre[k] = (i < sg.n) ? cid[i] : -1;
     }
+    int cnt_pre[4];                          // likewise the sizes of the first clusters (an entry exists for every index below n)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int c = tid + 1024 * k;
+        cnt_pre[k] = (!recount && c < sg.n) ? cnt[c] : 0;
+    }
+    const int C = clamp_count(rep[b].n_centers, sg.n);
     if (recount) {
         for (int c = tid; c < C; c += 1024) s_cur[c] = 0;
         __syncthreads();
@@ -49,7 +55,10 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
         __syncthreads();
         for (int c = tid; c < C; c += 1024) cnt[c] = s_cur[c];
     } else {
-        for (int c = tid; c < C; c += 1024) s_cur[c] = cnt[c];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (tid + 1024 * k < C) s_cur[tid + 1024 * k] = cnt_pre[k];
+        for (int c = tid + 4096; c < C; c += 1024) s_cur[c] = cnt[c];
     }
     __syncthreads();
     const int chunk = (C + 1023) / 1024;
