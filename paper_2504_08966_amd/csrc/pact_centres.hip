@@ -189,14 +189,27 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
         const double* nnb = nn + sg.base;
         const double d_c = (double)sg.d_c;
         int ties = 0;
-        for (int e = gw; e < cnt; e += nw) {
-            const uint32_t pi = near_list[((size_t)b * NEAR_CAP + e) * 2];
-            const uint32_t pj = near_list[((size_t)b * NEAR_CAP + e) * 2 + 1];
-            const int ti = ix[pi], tj = ix[pj];
+        // lane l takes this wavefront's l-th pair (gw + l * nw): pair, tokens and norms of all of
+        // them arrive in three trips, whatever their number; then one trip per pair for the rows
+        static_assert(NEAR_CAP <= 64 * REFINE_BLOCKS * 4, "a wavefront's pairs fit its lanes");
+        const int my_e = gw + lane * nw;
+        uint32_t my_pi = 0, my_pj = 0;
+        int my_ti = 0, my_tj = 0;
+        double my_ni = 0.0, my_nj = 0.0;
+        if (my_e < cnt) {
+            const uint2 pr = *(const uint2*)(near_list + ((size_t)b * NEAR_CAP + my_e) * 2);
+            my_pi = pr.x; my_pj = pr.y;
+            my_ti = ix[my_pi]; my_tj = ix[my_pj];
+            my_ni = nnb[my_ti]; my_nj = nnb[my_tj];
+        }
+        const int mine = (cnt > gw) ? (cnt - gw + nw - 1) / nw : 0;     // pairs of this wavefront
+        for (int k = 0; k < mine; ++k) {
+            const uint32_t pi = (uint32_t)__shfl((int)my_pi, k, 64), pj = (uint32_t)__shfl((int)my_pj, k, 64);
+            const int ti = __shfl(my_ti, k, 64), tj = __shfl(my_tj, k, 64);
             double d = 0.0;
             if (pi != pj) {
                 const double dot = wave_dot64<DT>(kb + (size_t)ti * row_bytes, kb + (size_t)tj * row_bytes, dk, lane);
-                d = cos_dist64(dot, nnb[ti], nnb[tj]);
+                d = cos_dist64(dot, __shfl(my_ni, k, 64), __shfl(my_nj, k, 64));
             }
             if (lane == 0) {
                 if (d > d_c)
