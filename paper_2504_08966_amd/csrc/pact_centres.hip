@@ -706,6 +706,9 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
     const int tok = ix[p];
     const uint32_t stp = st[p];
     const int cnp = cn[p];
+    // (the first 64 words of the row and of the centre mask go out with them, before the status
+    //  is looked at: a trip less for the tokens that are not centres)
+    const uint64_t first = (lane < bt.W) ? (row[lane] & cm[lane]) : 0ull;
     int cid;
     if (stp == ST_CENTER) {
         cid = cnp;
@@ -721,7 +724,7 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
         int nbuf = 0, ntot = 0;
         for (int w0 = 0; w0 < Wq; w0 += 64) {
             const int w = w0 + lane;
-            BitPop bp{(w < Wq) ? (row[w] & cm[w]) : 0ull};
+            BitPop bp{(w < Wq) ? (w0 == 0 ? first : (row[w] & cm[w])) : 0ull};
             while (bp.any()) {
                 int bit;
                 const bool has = bp.pop(bit);

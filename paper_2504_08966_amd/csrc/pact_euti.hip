@@ -80,10 +80,10 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         const char* base = a.q + (size_t)sg.base * row_bytes + (size_t)c * Elem<QDT>::BYTES;
-        for (int r = r0; r < r1; r += 8) {
-            float f[8][4];
+        for (int r = r0; r < r1; r += 16) {                  // 16 rows in flight: a chunk is usually one trip
+            float f[16][4];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const bool ok = r + u < r1;
                 const char* p = base + (size_t)(ok ? r + u : r0) * row_bytes;
                 if (QDT == PACT_BF16) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
                 if (!ok) { f[u][0] = f[u][1] = f[u][2] = f[u][3] = 0.0f; }
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[i] += (double)f[u][i];
         }
@@ -328,23 +328,32 @@ __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
     const int wave = threadIdx.x >> 6;
     const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     const int nwg = (sg.n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+    // this thread's token: its norm and first logits are requested before the partials are
+    // combined (they do not depend on them)
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const size_t g = (size_t)sg.base + min(i, sg.n - 1);
+    const double hn = hnorm[g];
+    double lg[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) lg[j] = (j < n_q) ? logits[g * n_q + j] : 0.0;
     for (int j = wave; j < n_q; j += 4) {
         double m, z;
         combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
         if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
     }
     __syncthreads();
-    const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= sg.n) return;
-    const size_t g = (size_t)sg.base + i;
     // the two ablations of Eq. 2: without the norm; norm only (softmax term -> 1/n)
     double p = 1.0 / (double)sg.n;
     if (!(sg.flags & PACT_FLAG_SCORE_NORM_ONLY)) {
         double acc = 0.0;
-        for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < n_q) acc += exp(lg[j] - s_M[j]) / s_Z[j];
+        for (int j = 4; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
         p = acc / (double)n_q;
     }
-    scores[g] = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hnorm[g] * p);
+    scores[g] = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hn * p);
 }
 
 // ------------------------------------------------------------------------------------------
