@@ -284,8 +284,17 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
 // loads its (max, sum) pairs 8 at a time, then the usual two-step combine.
 __device__ __forceinline__ void combine_softmax_partials(const double* part, int nwg, int stride, int lane,
                                                          double& M, double& Z) {
+    // the first 512 pairs stay in registers between the two steps (one fetch, not two)
+    double2 v0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int w = lane + 64 * u;
+        v0[u] = (w < nwg) ? *(const double2*)(part + (size_t)w * stride) : make_double2(-INFINITY, 0.0);
+    }
     double m = -INFINITY;
-    for (int w0 = lane; w0 < nwg; w0 += 512) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) m = fmax(m, v0[u].x);
+    for (int w0 = lane + 512; w0 < nwg; w0 += 512) {
         double2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -297,7 +306,9 @@ __device__ __forceinline__ void combine_softmax_partials(const double* part, int
     }
     m = wave_max_f64(m);
     double z = 0.0;
-    for (int w0 = lane; w0 < nwg; w0 += 512) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) z += (v0[u].y != 0.0) ? v0[u].y * exp(v0[u].x - m) : 0.0;
+    for (int w0 = lane + 512; w0 < nwg; w0 += 512) {
         double2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
