@@ -330,29 +330,15 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
         const int w = w0 + lane;
         BitPop bp{(w < Wq) ? row[w] : 0ull};
         while (bp.any()) {
-            // up to four neighbours per lane and turn: their densities are fetched together (a
-            // turn per neighbour would be a trip to memory per neighbour)
-            int j[4];
-            bool has[4];
-            double rj[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                int bit;
-                has[u] = bp.pop(bit);
-                j[u] = (w << 6) + bit;
-                has[u] = has[u] && j[u] < q;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) rj[u] = r[has[u] ? j[u] : p];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const bool pre = has[u] && precedes(rj[u], j[u], rp, p);
-                const uint64_t m = __ballot(pre);
-                const int slot = total + lanes_below(m, lane);
-                if (pre && slot < KP) out[1 + slot] = (uint16_t)j[u];
-                if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j[u];
-                total += __popcll(m);
-            }
+            int bit;
+            const bool has = bp.pop(bit);
+            const int j = (w << 6) + bit;
+            const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
+            const uint64_t m = __ballot(pre);
+            const int slot = total + lanes_below(m, lane);
+            if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
+            if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
+            total += __popcll(m);
         }
     }
     if (lane == 0) {

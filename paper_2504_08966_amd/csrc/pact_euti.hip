@@ -80,10 +80,10 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         const char* base = a.q + (size_t)sg.base * row_bytes + (size_t)c * Elem<QDT>::BYTES;
-        for (int r = r0; r < r1; r += 16) {                  // 16 rows in flight: a chunk is usually one trip
-            float f[16][4];
+        for (int r = r0; r < r1; r += 8) {
+            float f[8][4];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 const bool ok = r + u < r1;
                 const char* p = base + (size_t)(ok ? r + u : r0) * row_bytes;
                 if (QDT == PACT_BF16) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
                 if (!ok) { f[u][0] = f[u][1] = f[u][2] = f[u][3] = 0.0f; }
             }
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
+            for (int u = 0; u < 8; ++u)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[i] += (double)f[u][i];
         }
