@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
     if (blockIdx.x < REFINE_BLOCKS) {
         const int gw = blockIdx.x * 4 + wave;
         const int nw = REFINE_BLOCKS * 4;
-        const int raw = near_cnt[b];
+        const int raw = near_cnt[2 * b];
         const int cnt = min(raw, NEAR_CAP);
         if (gw == 0) {
             // largest key distance: the wavefronts of the density pass each left the bits of their
@@ -178,7 +178,8 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
 #pragma unroll
             for (int sft = 32; sft >= 1; sft >>= 1) fb = max(fb, (uint32_t)__shfl_xor((int)fb, sft, 64));
             if (lane == 0) {
-                rep[b].dc_checked_pairs = cnt;
+                // (a listed pair that stands for both orders counts twice)
+                rep[b].dc_checked_pairs = raw > NEAR_CAP ? cnt : near_cnt[2 * b + 1];
                 rep[b].refine_overflow = raw > NEAR_CAP;
                 rep[b].max_key_distance = fb ? fminf(-__uint_as_float(fb) * sg.d_n * 0.6931471805599453f, 2.0f) : 0.0f;
             }
@@ -199,12 +200,14 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
         if (my_e < cnt) {
             const uint2 pr = *(const uint2*)(near_list + ((size_t)b * NEAR_CAP + my_e) * 2);
             my_pi = pr.x; my_pj = pr.y;
-            my_ti = ix[my_pi]; my_tj = ix[my_pj];
+            my_ti = ix[my_pi & ~NEAR_MIRROR]; my_tj = ix[my_pj];
             my_ni = nnb[my_ti]; my_nj = nnb[my_tj];
         }
         const int mine = (cnt > gw) ? (cnt - gw + nw - 1) / nw : 0;     // pairs of this wavefront
         for (int k = 0; k < mine; ++k) {
-            const uint32_t pi = (uint32_t)__shfl((int)my_pi, k, 64), pj = (uint32_t)__shfl((int)my_pj, k, 64);
+            const uint32_t pi_raw = (uint32_t)__shfl((int)my_pi, k, 64), pj = (uint32_t)__shfl((int)my_pj, k, 64);
+            const uint32_t pi = pi_raw & ~NEAR_MIRROR;
+            const bool both = (pi_raw & NEAR_MIRROR) != 0;
             const int ti = __shfl(my_ti, k, 64), tj = __shfl(my_tj, k, 64);
             double d = 0.0;
             if (pi != pj) {
@@ -212,10 +215,14 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
                 d = cos_dist64(dot, __shfl(my_ni, k, 64), __shfl(my_nj, k, 64));
             }
             if (lane == 0) {
-                if (d > d_c)
+                if (d > d_c) {
                     atomicAnd((unsigned long long*)&adj[((size_t)b * bt.n_max + pi) * bt.W + (pj >> 6)],
                               ~(1ull << (pj & 63)));
-                if (fabs(d - d_c) <= 1e-6) ++ties;
+                    if (both)
+                        atomicAnd((unsigned long long*)&adj[((size_t)b * bt.n_max + pj) * bt.W + (pi >> 6)],
+                                  ~(1ull << (pi & 63)));
+                }
+                if (fabs(d - d_c) <= 1e-6) ties += both ? 2 : 1;
             }
         }
         if (lane == 0 && ties) atomicAdd(&rep[b].dc_near_ties, ties);

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         const int kblk = blockIdx.x - n_q_blocks;
         if (kblk == 0 && b == 0 && threadIdx.x < 64) a.zeros[threadIdx.x] = 0u;
         if (kblk == 0 && threadIdx.x == 0) {
-            a.near_cnt[b] = 0;
+            a.near_cnt[2 * b] = 0; a.near_cnt[2 * b + 1] = 0;
             pact_report* rp = a.rep + b;
             const int mode = a.mode;
             if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {

@@ -55,7 +55,7 @@ struct GramArgs {
     float* cbest;              // candidate pass: [B][W][n_max] largest cosine per (group of 64 centres, pruned token)
     double* rho_part;          // [B][W][n_max], one row per GRAM_RHO_ROWS kept rows
     uint32_t* near_list;       // [B][NEAR_CAP][2]
-    int32_t* near_cnt;         // [B]
+    int32_t* near_cnt;         // [B][2]: list slots taken, ordered pairs they stand for (8-byte aligned)
     uint32_t* stat;            // [B][gridDim.x * 8] per wavefront: bits of the most negative density exponent
                                // it saw (largest distance), or NULL when the statistic is not wanted
     float margin;              // worst-case fp32 error of a cosine
@@ -129,6 +129,15 @@ template <int L> __device__ __forceinline__ void file_ballots2(uint32_t& lo, uin
           "n"(L), "n"(L + 4));
 }
 // body(std::integral_constant<int, 0>{}) ... body(std::integral_constant<int, N-1>{})
+// value of the lane whose number differs by XOR (1, 2, 4, 8 or 16): a swizzle inside each
+// group of 32 lanes, which needs no address register
+template <int XOR> __device__ __forceinline__ double swizzle_xor(double v) {
+    static_assert(XOR >= 1 && XOR < 32, "within 32 lanes");
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)u, (XOR << 10) | 0x1f);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)(u >> 32), (XOR << 10) | 0x1f);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 template <int N, int I = 0, class F> __device__ __forceinline__ void static_for(F&& body) {
     if constexpr (I < N) {
         body(std::integral_constant<int, I>{});
@@ -152,7 +161,14 @@ template <> struct Mfma<PACT_F32> {
     }
 };
 
-template <int DT, int MODE, int MI, bool STAT>
+// Density pass with t x t square tiles on g workgroups: do mirrored tiles (upper triangle only,
+// longer epilogue) save at least one turn in eight of a workgroup's tile loop?
+__host__ __device__ __forceinline__ bool mirrored_tiles_pay(int t, int g) {
+    const long full = (long)t * t, tri = (long)t * (t + 1) / 2;
+    return ((tri + g - 1) / g) * 9 < ((full + g - 1) / g) * 8;
+}
+
+template <int DT, int MODE, int MI, bool STAT, bool SYM>
 __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     typedef Shape<MI> SH;
     constexpr int TILE_R = SH::TILE_R, STAGE_BYTES = SH::STAGE_BYTES, NSTAGE = SH::NSTAGE;
@@ -178,7 +194,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keep it scalar
     const int wr = wave >> 2, wc = wave & 3;                      // 2 x 4 wavefronts of WROWS x 64
-    const int l32_ = lane & 31, hh_ = lane >> 5;
 
     lds_char* ring = (lds_char*)s_ring;
     const uint32_t ring_base = (uint32_t)(uintptr_t)ring;
@@ -202,21 +217,24 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     // DMA roles: a stage is (TILE_R + 256) / 8 blocks of 1 KB (8 rows x 8 chunks), the A rows
     // first; wavefront w brings blocks w*NB .. w*NB+NB-1.  Lane l of a block: row 8*blk + l/8,
     // physical chunk l&7, which holds logical chunk (l&7) ^ ((row >> 1) & 7).
-    const int dma_row0 = wave * NB * 8 + (lane >> 3);          // stage row of block k: + 8 * k
     const uint32_t dma_lds0 = ring_base + (uint32_t)(wave * NB * 1024);
-
-    // fragment addressing: lane (l32, hh) reads chunk 2g+hh of row (its wave's row block) + l32
-    const int swz = (l32_ >> 1) & 7;
-    const uint32_t fragA0 = (uint32_t)((wr * WROWS + l32_) * SLICE_BYTES);
-    const uint32_t fragB0 = (uint32_t)((TILE_R + wc * 64 + l32_) * SLICE_BYTES);
 
     // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (XCD = workgroup id mod 8) and
     // every XCD has its own L2, so each XCD takes a contiguous eighth of the tile sequence,
     // column by column.  An XCD then works on few tile columns, whose keys stay in its L2 beside
     // the row operand (all kept tokens, or all centres), and - counted in tiles, not in rows -
     // every XCD gets the same load.
+    // Symmetry (density pass, square tiles): d_ij = d_ji, so the tiles above the diagonal can
+    // stand for their mirror images as well (their epilogue then also leaves row sums and the
+    // transposed bits).  That epilogue is longer, and with a tile or less per workgroup the
+    // kernel lasts as long as its slowest tile whatever their number: mirrored tiles are used
+    // when they save at least one turn in eight of the workgroups' tile loop.
     const int xcd = blockIdx.x & 7;
-    const long nTiles = (long)tilesR * tilesC;
+    const long nFull = (long)tilesR * tilesC;
+    const long nTri = (long)tilesR * (tilesR + 1) / 2;
+    bool sym = false;
+    if constexpr (SYM) sym = mirrored_tiles_pay(tilesR, (int)gridDim.x);
+    const long nTiles = sym ? nTri : nFull;
     const bool banded = nTiles >= 8 && (gridDim.x & 7) == 0;
     const int l_lo = banded ? (int)(xcd * nTiles / 8) : 0;
     const int l_hi = banded ? (int)((xcd + 1) * nTiles / 8) : (int)nTiles;
@@ -225,8 +243,30 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 
     float far = 0.0f;              // most negative density exponent seen = largest distance (density pass)
     for (int tl = t_first; tl < l_hi; tl += t_step) {
-        const int rowBase = (tl % tilesR) * TILE_R;
-        const int colBase = (tl / tilesR) * TILE_C;
+        // Per-lane constants of a tile.  (The build with mirrored tiles has no register to spare
+        // in its epilogue: there they are derived anew for every tile from a laundered thread
+        // number, so that they do not occupy registers from one tile to the next.)
+        int tid_t = tid;
+        if constexpr (SYM) asm volatile("" : "+v"(tid_t));
+        const int lane = tid_t & 63;
+        const int l32_ = lane & 31, hh_ = lane >> 5;
+        const int dma_row0 = wave * NB * 8 + (lane >> 3);          // DMA: stage row of this lane in block k: + 8 * k
+        // fragment addressing: lane (l32, hh) reads chunk 2g+hh of row (its wave's row block) + l32
+        const int swz = (l32_ >> 1) & 7;
+        const uint32_t fragA0 = (uint32_t)((wr * WROWS + l32_) * SLICE_BYTES);
+        const uint32_t fragB0 = (uint32_t)((TILE_R + wc * 64 + l32_) * SLICE_BYTES);
+
+        int tr = tl % tilesR, tc = tl / tilesR;
+        if (sym) {
+            // upper triangle, column by column: tile tl is (tr, tc) with tr <= tc, tl = tc (tc + 1) / 2 + tr
+            tc = (int)((sqrtf(8.0f * (float)tl + 1.0f) - 1.0f) * 0.5f);
+            while ((tc + 1) * (tc + 2) / 2 <= tl) ++tc;
+            while (tc * (tc + 1) / 2 > tl) --tc;
+            tr = tl - tc * (tc + 1) / 2;
+        }
+        const int rowBase = tr * TILE_R;
+        const int colBase = tc * TILE_C;
+        const bool mirror = SYM && sym && tr != tc;  // this tile also stands for tile (tc, tr)
 
         // byte offsets of this lane's 16 bytes in the first slice of its NB DMA rows; rows past the
         // end are clamped to the last one (their products are discarded in the epilogue)
@@ -239,7 +279,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             //  (row >> 1) & 7, and rows advance by 8 per block)
             ro[k] = (uint32_t)tok * (uint32_t)row_bytes + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
         }
-        if (tid < TILE_R) sRinv[tid] = rinv[idxR[min(rowBase + tid, nA - 1)]];
+        if (tid_t < TILE_R) sRinv[tid_t] = rinv[idxR[min(rowBase + tid_t, nA - 1)]];
         float rj_pre[2];                                    // 1/|u_j| of this lane's two columns (used in the epilogue)
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
@@ -346,9 +386,14 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         // per-wavefront buffer of undecided pairs, in a ring slot no wavefront reads any more
         lds_uint2* nearBuf = (lds_uint2*)(ring + (nSlices % NSTAGE) * STAGE_BYTES + wave * (NEAR_BUF * 8));
         int nearN = 0;
+        // mirrored tiles: the wavefronts' row sums (128 rows x 64 columns each), behind the pair buffers
+        lds_f64* rowBuf = (lds_f64*)(ring + (nSlices % NSTAGE) * STAGE_BYTES + 8 * (NEAR_BUF * 8));
         auto flush_near = [&]() __attribute__((always_inline)) {
             int base_slot = 0;
-            if (lane == 0) base_slot = atomicAdd(&ga.near_cnt[b], nearN);
+            // (one 64-bit atomic: slots in the low word, ordered pairs in the high word)
+            if (lane == 0)
+                base_slot = (int)(uint32_t)atomicAdd((unsigned long long*)&ga.near_cnt[2 * b],
+                                                     (unsigned long long)nearN | ((unsigned long long)(mirror ? 2 * nearN : nearN) << 32));
             base_slot = __shfl(base_slot, 0, 64);
             for (int k = lane; k < nearN; k += 64) {
                 const int slot = base_slot + k;
@@ -438,11 +483,53 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                             if (8 * (r >> 2) + 4 * hh + (r & 3) == l32 && rowI + l32 < nA) acc[i][j][r] = 0.0f;
                     }
                 // phase A2: density terms
+                if (mirror) {
+                    // ... which also belong to the densities of this tile's rows: sum them over
+                    // the wavefront's 64 columns.  Each lane has 4 rows x 2 columns at a time; the 32
+                    // lanes of a half-wave halve their row sets twice (a lane sends the sums of the
+                    // rows it gives up and adds what it receives for those it keeps) and are left
+                    // with one row each, eight neighbouring lanes with parts of the same one.
+                    const bool ok0 = colP[0] < nB, ok1 = colP[1] < nB;      // clamped columns count nowhere
+                    static_for<4>([&](auto r4_tag) __attribute__((always_inline)) {   // four rows at a time: registers are tight
+                        constexpr int r4 = 4 * decltype(r4_tag)::value;
+                        double d[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const double e0 = (double)__builtin_amdgcn_exp2f(acc[i][0][r4 + r]);
+                            const double e1 = (double)__builtin_amdgcn_exp2f(acc[i][1][r4 + r]);
+                            rho[0][r & 1] += e0;
+                            rho[1][r & 1] += e1;
+                            d[r] = (ok0 ? e0 : 0.0) + (ok1 ? e1 : 0.0);
+                        }
+                        {
+                            const bool up = (l32 & 16) != 0;
+#pragma unroll
+                            for (int k = 0; k < 2; ++k) {
+                                const double keep = up ? d[k + 2] : d[k];
+                                const double send = up ? d[k] : d[k + 2];
+                                d[k] = keep + swizzle_xor<16>(send);
+                            }
+                        }
+                        {
+                            const bool up = (l32 & 8) != 0;
+                            const double keep = up ? d[1] : d[0];
+                            const double send = up ? d[0] : d[1];
+                            d[0] = keep + swizzle_xor<8>(send);
+                        }
+                        d[0] += swizzle_xor<4>(d[0]);
+                        d[0] += swizzle_xor<2>(d[0]);
+                        d[0] += swizzle_xor<1>(d[0]);
+                        // rows r4 .. r4+3 of this lane are rows 2 r4 + 4 hh + (0..3) of the block
+                        if ((l32 & 7) == 0) rowBuf[wave * 128 + i * 32 + 2 * r4 + 4 * hh + (l32 >> 3)] = d[0];
+                        if (r4 == 4) __builtin_amdgcn_sched_barrier(0);     // two groups at a time may overlap their exchanges
+                    });
+                } else {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
 #pragma unroll
                     for (int j = 0; j < 2; ++j) rho[j][r & 1] += (double)__builtin_amdgcn_exp2f(acc[i][j][r]);
                     if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bound the live ranges: registers are tight
+                }
                 }
             }
             // phase B: one bit per pair; most 32 x 64 blocks have none set: test the block's maximum first
@@ -495,6 +582,22 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             whi &= (uint32_t)laneOk[1];
             if (lane < 32 && (wlo | whi) != 0)
                 adj[(size_t)(rowI + lane) * bt.W + wordIdx] = ((uint64_t)whi << 32) | wlo;
+            if (MODE == MODE_DENSITY && mirror) {
+                // the same bits for the mirror image: 32 rows of this block are 32 columns (half a
+                // bitmap word) of the rows that are this tile's columns; assembled in the lane
+                // from its 16 rows and completed by the lane 32 further on
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    uint32_t bits = 0u;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        bits |= (acc[i][j][r] >= t_lo) ? (1u << (8 * (r >> 2) + (r & 3))) : 0u;
+                    bits <<= 4 * hh;
+                    bits |= (uint32_t)__shfl_xor((int)bits, 32, 64);
+                    if (hh == j && colP[j] < nB && bits != 0u)
+                        ((uint32_t*)adj)[((size_t)colP[j] * bt.W + (rowI >> 6)) * 2 + ((rowI >> 5) & 1)] = bits;
+                }
+            }
             if (MODE == MODE_DENSITY) {
                 // Undecided pairs: queue them for the fp64 check.  They collect in this wavefront's
                 // LDS buffer, every lane adding one pair of its row per turn; one atomic reserves
@@ -506,7 +609,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                         const int c = __builtin_ctzll(band);
                         band &= band - 1;
                         nearBuf[nearN + __popcll(has & ((1ull << lane) - 1ull))] =
-                            u32x2_t{(uint32_t)(rowI + lane), (uint32_t)(colW + c)};
+                            u32x2_t{(uint32_t)(rowI + lane) | (mirror ? NEAR_MIRROR : 0u), (uint32_t)(colW + c)};
                     }
                     nearN += __popcll(has);
                     if (nearN > NEAR_BUF - 32) flush_near();
@@ -540,6 +643,16 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             for (int j = 0; j < 2; ++j)
                 if (writer && colP[j] < nB) out[colP[j]] = tot[j];
         }
+        if (MODE == MODE_DENSITY && mirror) {
+            // row sums: two wavefronts side by side cover the 128 columns of one row of partials
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            const int half = tid_t >> 8, pair = (tid_t >> 7) & 1, row = tid_t & 127;
+            const double v = rowBuf[(half * 4 + pair * 2) * 128 + row] + rowBuf[(half * 4 + pair * 2 + 1) * 128 + row];
+            const int gRow = rowBase + half * 128 + row;
+            if (gRow < nA && colBase + pair * 128 < nB)
+                ga.rho_part[((size_t)b * bt.W + colBase / GRAM_RHO_ROWS + pair) * bt.n_max + gRow] = v;
+        }
         PACT_STAMP(4);
         if (tl + t_step < l_hi) {
             // the ring and sRinv are rewritten by the next tile: every wavefront must be done with
@@ -557,45 +670,58 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     }
 }
 
-template <int MODE, int MI, bool STAT>
+// Workgroups per sample: one per CU for a single sample, fewer for batches (the samples' grids
+// run side by side), a multiple of the 8 XCDs (see the tile order).
+static int gram_grid_x(const Batch& bt, long tiles) {
+    long grid_x = tiles;
+    const int cap = (bt.B >= 8) ? 32 : (bt.B >= 2 ? 128 : 256);   // one workgroup per CU, 256 CUs
+    if (grid_x > cap) grid_x = cap;
+    if (grid_x >= 8) grid_x &= ~7L;
+    return (int)grid_x;
+}
+
+template <int MODE, int MI, bool STAT, bool SYM>
 static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
                              const char* name, int* grid_out) {
     typedef Shape<MI> SH;
     const int tilesR = (bt.n_max + SH::TILE_R - 1) / SH::TILE_R, tilesC = (bt.n_max + TILE_C - 1) / TILE_C;
-    int grid_x = tilesR * tilesC;
-    const int cap = (bt.B >= 8) ? 32 : (bt.B >= 2 ? 128 : 256);   // one workgroup per CU, 256 CUs
-    if (grid_x > cap) grid_x = cap;
-    if (grid_x >= 8) grid_x &= ~7;                // a multiple of the 8 XCDs (see the tile order)
+    const int grid_x = gram_grid_x(bt, (long)tilesR * tilesC);
     dim3 grid(grid_x, bt.B);
     if (grid_out) *grid_out = grid_x;
     const size_t lds = SH::LDS_BYTES;
     static bool raised[2] = {false, false};
     const int di = k_dt == PACT_BF16 ? 1 : 0;
-    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI, STAT>
-                                         : (const void*)gram_kernel<PACT_F32, MODE, MI, STAT>;
+    const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI, STAT, SYM>
+                                         : (const void*)gram_kernel<PACT_F32, MODE, MI, STAT, SYM>;
     if (!raised[di]) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PACT_ERR_HIP;
         raised[di] = true;
     }
     if (k_dt == PACT_BF16)
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI, STAT>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI, STAT, SYM>), grid, dim3(512), lds, st, bt, ga);
     else
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI, STAT>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI, STAT, SYM>), grid, dim3(512), lds, st, bt, ga);
     return PACT_OK;
 }
 
 // 256 x 256 tiles when there are enough of them to occupy the chip, else 128 x 256.
+// mirrored: the kernel build that can let the tiles above the diagonal stand for those below
+// (it decides per sample, from the count of kept tokens it finds, whether to do so).
 template <int MODE>
 static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
-                       const char* name, long tiles256, int* grid_out) {
+                       const char* name, long tiles256, bool mirrored, int* grid_out) {
     const bool big = tiles256 * bt.B >= 256;
-    if (MODE == MODE_DENSITY && ga.stat) {        // with the key-distance statistic
-        if (big) return launch_gram_shape<MODE, 4, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
-        return launch_gram_shape<MODE, 2, MODE == MODE_DENSITY>(bt, ga, k_dt, st, name, grid_out);
+    if constexpr (MODE == MODE_DENSITY) {
+        if (ga.stat) {                            // with the key-distance statistic
+            if (big && mirrored) return launch_gram_shape<MODE, 4, true, true>(bt, ga, k_dt, st, name, grid_out);
+            if (big) return launch_gram_shape<MODE, 4, true, false>(bt, ga, k_dt, st, name, grid_out);
+            return launch_gram_shape<MODE, 2, true, false>(bt, ga, k_dt, st, name, grid_out);
+        }
+        if (big && mirrored) return launch_gram_shape<MODE, 4, false, true>(bt, ga, k_dt, st, name, grid_out);
     }
-    if (big) return launch_gram_shape<MODE, 4, false>(bt, ga, k_dt, st, name, grid_out);
-    return launch_gram_shape<MODE, 2, false>(bt, ga, k_dt, st, name, grid_out);
+    if (big) return launch_gram_shape<MODE, 4, false, false>(bt, ga, k_dt, st, name, grid_out);
+    return launch_gram_shape<MODE, 2, false, false>(bt, ga, k_dt, st, name, grid_out);
 }
 
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -605,8 +731,17 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
     ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.cbest = nullptr; ga.rho_part = w.rho_part;
     ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.stat = want_stat ? w.stat : nullptr; ga.margin = (float)cos_margin(dk);
     const long t1 = (bt.n_max + 255) / 256;
+    // The count of kept tokens is known on the device only; what the percentile will leave
+    // (n - floor(lambda n), more on ties) tells whether mirrored tiles are likely to pay for
+    // some sample.  The kernel decides again from the real count, so a wrong guess costs time only.
+    bool mirrored = false;
+    const int gx = gram_grid_x(bt, t1 * t1);
+    for (int b = 0; b < bt.B; ++b) {
+        const int q_est = bt.s[b].n - (int)floorf(bt.s[b].lambda * (float)bt.s[b].n);
+        mirrored = mirrored || mirrored_tiles_pay((q_est + 255) / 256, gx);
+    }
     int grid_x = 0;
-    const int rc = launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, &grid_x);
+    const int rc = launch_gram<MODE_DENSITY>(bt, ga, k_dt, st, "gram_density", t1 * t1, mirrored, &grid_x);
     if (stat_words) *stat_words = want_stat ? grid_x * 8 : 0;
     return rc;
 }
@@ -622,7 +757,7 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
     // rows: the centres, columns: the pruned tokens; neither count is known on the host, a
     // typical split (half pruned, a third of the rest centres) sizes the choice
     const long tr = (bt.n_max / 6 + 255) / 256, tc = (bt.n_max / 2 + 255) / 256;
-    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, nullptr);
+    return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, false, nullptr);
 }
 
 #ifdef PACT_GRAM_STAMPS

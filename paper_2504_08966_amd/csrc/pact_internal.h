@@ -35,6 +35,7 @@ constexpr int SCORE_TOK_PER_WG = 16;  // tokens (= wavefronts) per workgroup in 
 constexpr int PRED_CAP = 64;          // 16-bit slots per kept token: slot 0 = count, then up to 63 preceding neighbours
 constexpr int GRAM_RHO_ROWS = 128;    // kept rows summed into one row of the density partials
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
+constexpr uint32_t NEAR_MIRROR = 0x80000000u;   // flag in a listed pair's row: the pair (col, row) is meant as well
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
 
 struct WsLayout {
@@ -79,7 +80,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.preds = take(sizeof(uint16_t) * B * n_max * PRED_CAP);
     L.heads = take(sizeof(uint16_t) * 4 * B * n_max);
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
-    L.near_cnt = take(sizeof(int32_t) * B);
+    L.near_cnt = take(sizeof(int32_t) * 2 * B);   // per sample: list slots taken, ordered pairs they stand for
     L.stat = take(sizeof(uint32_t) * B);
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);

@@ -588,6 +588,73 @@ def test_odd_sizes_and_key_widths(n, dk_heads, d_h, dtype):
     assert_same(gu.trim(o, n), oracle_reduce(s, d_c), s, f"n={n} dk={dk_heads * d_h} {dtype}")
 
 
+# ------------------------------------------------------------------ mirrored tiles of the density pass
+# d_ij = d_ji: when a sample has more 256 x 256 tiles than it has workgroups, the density pass
+# computes the tiles above the diagonal only and lets them stand for their mirror images.
+
+@pytest.mark.parametrize("n,lam,dtype", [(4500, 0.0, "bf16"), (5200, 0.15, "f32")])
+def test_density_pass_with_mirrored_tiles_single_sample(n, lam, dtype):
+    # more than 4096 kept tokens: 18 x 18 tiles for 256 workgroups; the last tile row and column are ragged
+    s = _random_sample(40 + n, n, 2, 2, 32, 64, lam, dtype)
+    d_c = _gap_dc(s.keys.reshape(n, -1), frac=0.002)
+    hid, ks = gu.dev(s.hidden, dtype), gu.dev(s.keys.reshape(n, -1), dtype)
+    qs = gu.dev(s.queries.reshape(n, -1), dtype)
+    o = P.pact_reduce(hid, ks, ks, qs, 2, 32, 2, P.PactParams(s.lam, d_c, 2.0, 1.5))
+    torch.cuda.synchronize()
+    g = gu.trim(o, n)
+    assert g["rep"]["n_kept"] > 4096 and g["rep"]["refine_overflow"] == 0
+    assert_same(g, oracle_reduce(s, d_c), s, f"mirrored tiles n={n} {dtype}")
+
+
+def test_mirrored_tiles_densities_and_key_statistic():
+    # the stand-alone clustering call: densities, centres and the largest key distance
+    n = 4400
+    s = _random_sample(31, n, 2, 2, 32, 64, 0.0, "f32")
+    U = s.keys.reshape(n, -1).astype(np.float64)
+    d_c = _gap_dc(U, frac=0.002)
+    out = P.dbdpc_cluster(gu.dev(s.keys.reshape(n, -1), "f32"), d_c, 2.0, want_rho=True)
+    torch.cuda.synchronize()
+    rep = P.read_report(out["rep"])
+    ref = po.dbdpc(U, float(np.float32(d_c)), 2.0)
+    np.testing.assert_allclose(out["rho"].cpu().numpy(), ref["rho"], rtol=3e-6, atol=0)
+    assert np.array_equal(out["center_idx"][: rep["n_centers"]].cpu().numpy(), ref["centers"])
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["labels"])
+    assert abs(rep["max_key_distance"] - po.max_pairwise_distance(U)) <= (U.shape[1] + 16) / 2.0 ** 23 + 3e-6
+    assert rep["refine_overflow"] == 0 and rep["dc_checked_pairs"] > 0
+
+
+def test_mirrored_tiles_in_a_batch_and_the_pair_counters():
+    # 8 samples share the chip (32 workgroups each): 6 x 6 tiles and more are mirrored, the small
+    # samples of the same call are not.  Alone, sample 0 gets the 128 x 256 tiles, which are never
+    # mirrored: both routes re-evaluate the same near-threshold pairs, counted as ordered pairs (up to
+    # the few pairs whose fp32 cosine falls in the undecided band in one order only: the two norms
+    # are applied one after the other) and find the same ties.
+    sizes = [1400, 1290, 1537, 300, 1800, 1281, 2000, 1500]
+    lams = [0.0, 0.0, 0.1, 0.3, 0.2, 0.0, 0.25, 0.05]
+    samples = [_random_sample(500 + b, sizes[b], 2, 2, 32, 64, lams[b], "bf16") for b in range(8)]
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), "bf16")
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "bf16")
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "bf16")
+    dcs = [_gap_dc(sm.keys.reshape(sm.n, -1), frac=0.004) for sm in samples]
+    prms = [P.PactParams(sm.lam, d, 2.0, 1.5) for sm, d in zip(samples, dcs)]
+    o = P.pact_reduce_varlen(hid, ks, ks, qs, 2, 32, 2, cu, prms)
+    torch.cuda.synchronize()
+    res = [gu.trim(o, sm.n, base=cu[b], b=b) for b, sm in enumerate(samples)]
+    for b, sm in enumerate(samples):
+        assert_same(res[b], oracle_reduce(sm, dcs[b]), sm, f"sample {b} (n={sm.n})")
+    s0 = samples[0]
+    o0 = P.pact_reduce(gu.dev(s0.hidden, "bf16"), gu.dev(s0.keys.reshape(s0.n, -1), "bf16"), gu.dev(s0.keys.reshape(s0.n, -1), "bf16"),
+                       gu.dev(s0.queries.reshape(s0.n, -1), "bf16"), 2, 32, 2, prms[0])
+    torch.cuda.synchronize()
+    alone = gu.trim(o0, s0.n)["rep"]
+    assert alone["dc_checked_pairs"] > 0
+    assert abs(alone["dc_checked_pairs"] - res[0]["rep"]["dc_checked_pairs"]) <= 2 + alone["dc_checked_pairs"] // 20
+    assert alone["dc_near_ties"] == res[0]["rep"]["dc_near_ties"]
+
+
 def test_largest_batch_of_small_samples():
     # 64 samples (the batch limit) of ragged small sizes in one call
     r = np.random.default_rng(77)
