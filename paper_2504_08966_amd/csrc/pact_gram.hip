@@ -23,7 +23,10 @@
 //    number so that 16 consecutive rows read conflict-free; the fragments of the next k-group
 //    are read from LDS while the MFMAs of the current one run;
 //  * the grid is persistent (the tile count depends on counts only the device knows) and
-//    XCD-aware: each of the 8 XCDs (own L2) works on its own band of tile columns.
+//    XCD-aware: each of the 8 XCDs (own L2) works on its own band of tile columns;
+//  * density pass of a sample with more 256 x 256 tiles than workgroups: d_ij = d_ji, so only the
+//    tiles on and above the diagonal are computed, and a tile above it also leaves the row sums,
+//    the transposed bits and the flagged near-d_c pairs of its mirror image (template SYM).
 #include <type_traits>
 
 #include "pact_internal.h"
