@@ -211,8 +211,11 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const float* __restrict__ rinv = ga.rinv + sg.base;
     uint64_t* adj = ga.adj + (size_t)b * bt.n_max * bt.W;
 
-    // density constants: arg = cos * a - a = -(d / d_n) * log2(e)
+    // density constants: arg = cos * a - a = -(d / d_n) * log2(e); each of the two reciprocal norms
+    // carries sqrt(a), so that the factor of a pair is the same product whichever token is the
+    // row (pair (i, j) and pair (j, i) then get the same fp32 value, bit for bit)
     const float a_ = 1.4426950408889634f / sg.d_n;
+    const float sa_ = (MODE == MODE_DENSITY) ? sqrtf(a_) : 1.0f;
     const float thr_cos = (MODE == MODE_DENSITY) ? (1.0f - sg.d_c) : (1.0f - sg.alpha * sg.d_c);
     const float t_lo = (MODE == MODE_DENSITY) ? -(sg.d_c + ga.margin) * a_ : thr_cos - ga.margin;
     const float t_hi = -(sg.d_c - ga.margin) * a_;
@@ -282,7 +285,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             //  (row >> 1) & 7, and rows advance by 8 per block)
             ro[k] = (uint32_t)tok * (uint32_t)row_bytes + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
         }
-        if (tid_t < TILE_R) sRinv[tid_t] = rinv[idxR[min(rowBase + tid_t, nA - 1)]];
+        if (tid_t < TILE_R) sRinv[tid_t] = rinv[idxR[min(rowBase + tid_t, nA - 1)]] * sa_;
         float rj_pre[2];                                    // 1/|u_j| of this lane's two columns (used in the epilogue)
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
@@ -382,7 +385,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             colP[j] = colW + j * 32 + l32;
-            rj[j] = (MODE == MODE_DENSITY) ? rj_pre[j] * a_ : rj_pre[j];
+            rj[j] = rj_pre[j] * sa_;
             laneOk[j] = __ballot(colP[j] < nB);
         }
         double rho[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
@@ -471,8 +474,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 const bool pad = rowI + 8 * (r >> 2) + 4 * hh + (r & 3) >= nA;   // padded row: no term, no bit
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const float t = acc[i][j][r] * rs[r];
-                    float v = (MODE == MODE_DENSITY) ? fmaf(t, rj[j], -a_) : t * rj[j];
+                    const float v = fmaf(acc[i][j][r], rs[r] * rj[j], -a_);
                     acc[i][j][r] = pad ? -INFINITY : v;
                 }
             }
