@@ -168,8 +168,8 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
     if (blockIdx.x < REFINE_BLOCKS) {
         const int gw = blockIdx.x * 4 + wave;
         const int nw = REFINE_BLOCKS * 4;
-        const int raw = near_cnt[2 * b];
-        const int cnt = min(raw, NEAR_CAP);
+        const uint32_t raw = (uint32_t)near_cnt[2 * b];
+        const int cnt = (int)min(raw, (uint32_t)NEAR_CAP);
         if (gw == 0) {
             // largest key distance: the wavefronts of the density pass each left the bits of their
             // most negative exponent -(d / d_n) log2(e); negative floats order like those bits
@@ -179,8 +179,8 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
             for (int sft = 32; sft >= 1; sft >>= 1) fb = max(fb, (uint32_t)__shfl_xor((int)fb, sft, 64));
             if (lane == 0) {
                 // (a listed pair that stands for both orders counts twice)
-                rep[b].dc_checked_pairs = raw > NEAR_CAP ? cnt : near_cnt[2 * b + 1];
-                rep[b].refine_overflow = raw > NEAR_CAP;
+                rep[b].dc_checked_pairs = raw > (uint32_t)NEAR_CAP ? cnt : near_cnt[2 * b + 1];
+                rep[b].refine_overflow = raw > (uint32_t)NEAR_CAP;
                 rep[b].max_key_distance = fb ? fminf(-__uint_as_float(fb) * sg.d_n * 0.6931471805599453f, 2.0f) : 0.0f;
             }
         }

@@ -278,6 +278,33 @@ def test_exact_duplicates_and_orthonormal_keys():
         assert list(g["center_idx"]) == want
 
 
+def test_near_list_overflow_is_reported():
+    # two blocks of 200 identical keys whose mutual distance is d_c to within fp32 rounding: 80 000
+    # ordered pairs sit in the undecided band, more than the list of pairs to re-evaluate holds
+    # (65 536).  The call must say so (those pairs keep their fp32 decision) and stay well-formed.
+    n_half = 200
+    k = np.zeros((2 * n_half + 50, 1, 16), dtype=np.float32)
+    k[:n_half, 0, 0] = 1.0
+    k[n_half:2 * n_half, 0, 0] = 0.9
+    k[n_half:2 * n_half, 0, 1] = np.float32(np.sqrt(1.0 - 0.81))
+    k[2 * n_half:, 0, 2:] = np.random.default_rng(12).normal(size=(50, 14)).astype(np.float32)
+    a, b = k[0, 0].astype(np.float64), k[n_half, 0].astype(np.float64)
+    d_c = float(np.float32(1.0 - a @ b / np.sqrt((a @ a) * (b @ b))))
+    s = _mk(k)
+    g = gu.gpu_reduce(s, d_c, lam=0.0)
+    rep = g["rep"]
+    assert rep["refine_overflow"] == 1 and rep["dc_checked_pairs"] == 65536
+    C = rep["n_centers"]
+    assert rep["n_kept"] == s.n and 2 <= C <= 52
+    assert g["cluster_id"].min() >= 0 and g["cluster_id"].max() == C - 1
+    assert g["counts"].sum() == s.n and np.array_equal(np.bincount(g["cluster_id"], minlength=C), g["counts"])
+    # a cutoff clear of that distance: no overflow, and the oracle's result
+    for d_c2 in (d_c * 0.9, d_c * 1.1):
+        g2 = gu.gpu_reduce(s, float(np.float32(d_c2)), lam=0.0)
+        assert g2["rep"]["refine_overflow"] == 0
+        assert_same(g2, oracle_reduce(s, float(np.float32(d_c2)), lam=0.0), s, f"d_c={d_c2}")
+
+
 def test_equidistant_token_takes_lower_centre():
     k = np.zeros((3, 1, 8), dtype=np.float32)
     k[0, 0, 0] = 1.0            # centre a
