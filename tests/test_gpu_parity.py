@@ -681,6 +681,68 @@ def test_mirrored_tiles_in_a_batch_and_the_pair_counters():
     assert alone["dc_near_ties"] == res[0]["rep"]["dc_near_ties"]
 
 
+def test_maximum_token_count_block_by_block():
+    # n = 32768, the largest sample the library takes.  The full distance matrix of the kept tokens
+    # would be 2 GB: the oracle's routines run block by block, and the centre set is checked through
+    # the property that defines it (Alg. 2: a token is a centre iff no centre that precedes it in the
+    # density order lies within d_c), which has exactly one solution for a given order.
+    n, alpha = 32768, 1.5
+    s = _random_sample(4242, n, 2, 2, 32, 64, 0.5, "f32")
+    U = s.keys.reshape(n, -1).astype(np.float64)
+    sub = np.random.default_rng(1).choice(n, 2500, replace=False)
+    d_c = _gap_dc(U[np.sort(sub)], frac=4e-4, window=100)                # inside the blobs: ~11 neighbours per token
+    g = gu.gpu_reduce(s, d_c, alpha=alpha)
+    d_c, rep = float(np.float32(d_c)), g["rep"]
+    # scores and split
+    ref_scores = po.euti_scores(s.hidden, s.keys, s.queries)
+    np.testing.assert_allclose(g["scores"], ref_scores, rtol=1e-5, atol=0)
+    kept, pruned, _ = po.percentile_split(g["scores"], float(np.float32(s.lam)))
+    assert np.array_equal(g["kept_idx"], kept) and np.array_equal(g["pruned_idx"], pruned)
+    centres = g["center_idx"]
+    C = centres.size
+    assert rep["n_kept"] == kept.size and rep["n_centers"] == C and rep["refine_overflow"] == 0
+    Uk, Uc = U[kept], U[centres]
+    is_centre = np.isin(kept, centres)
+    assert is_centre.sum() == C                                            # centres are kept tokens
+    # densities (oracle, block by block) and the order they define
+    rho = np.concatenate([po.density(po.cosine_distance_cross(Uk[a:a + 1024], Uk), 2.0)
+                          for a in range(0, kept.size, 1024)])
+    order = po.density_order(rho)
+    rank = np.empty(kept.size, dtype=np.int64)
+    rank[order] = np.arange(kept.size)
+    rank_c = rank[is_centre]                                               # centres in ascending token index
+    labels_kept = np.empty(kept.size, dtype=np.int64)
+    near_ties = 0
+    for a in range(0, kept.size, 2048):
+        D = po.cosine_distance_cross(Uk[a:a + 2048], Uc)
+        labels_kept[a:a + 2048] = po.assign_to_centers(D)
+        within = D <= d_c
+        for k in range(D.shape[0]):
+            i = a + k
+            earlier = within[k] & (rank_c < rank[i])
+            if is_centre[i]:
+                assert within[k].sum() == 1, f"centre {kept[i]} has another centre within d_c"
+            elif not earlier.any():
+                # tolerated only if the density order itself is within fp32 term rounding there
+                cand = np.flatnonzero(within[k])
+                assert cand.size and np.min(np.abs(rho[is_centre][cand] - rho[i])) <= 3e-6 * rho[i], \
+                    f"token {kept[i]} has no earlier centre within d_c"
+                near_ties += 1
+    assert near_ties <= 2
+    assert np.array_equal(g["cluster_id"][kept], labels_kept)
+    # recovery of the pruned tokens
+    labels_pruned = np.concatenate([po.reincorporate(po.cosine_distance_cross(U[pruned[a:a + 2048]], Uc), d_c, alpha)
+                                    for a in range(0, pruned.size, 2048)])
+    assert np.array_equal(g["cluster_id"][pruned], labels_pruned)
+    assert rep["n_reincorporated"] == int((labels_pruned >= 0).sum()) and rep["n_dropped"] == int((labels_pruned < 0).sum())
+    # merge: counts everywhere, rows of a sample of clusters
+    assert np.array_equal(g["counts"], np.bincount(g["cluster_id"][g["cluster_id"] >= 0], minlength=C))
+    pick = np.random.default_rng(2).choice(C, 64, replace=False)
+    H = s.hidden.astype(np.float64)
+    for c in pick:
+        np.testing.assert_allclose(g["merged"][c], H[g["cluster_id"] == c].mean(axis=0), rtol=1e-5, atol=1e-30)
+
+
 def test_largest_batch_of_small_samples():
     # 64 samples (the batch limit) of ragged small sizes in one call
     r = np.random.default_rng(77)
