@@ -130,7 +130,7 @@ extern "C" {
 size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_q, int32_t d_h) {
     if (n_max < 1 || n_max > PACT_MAX_TOKENS || batch < 1 || batch > PACT_MAX_BATCH) return 0;
     if (dk < 1 || n_q < 1 || n_q > PACT_MAX_QHEADS || d_h < 1) return 0;
-    return make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q).total;
+    return make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, dk).total;
 }
 
 int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
@@ -148,7 +148,7 @@ int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_tensor(keys_pre, k_dt, (int64_t)n_kv * d_h))) return rc;
     if ((rc = check_tensor(q, q_dt, (int64_t)n_q * d_h))) return rc;
     if (((int64_t)d_h * esize(k_dt)) % 16 != 0 || ((int64_t)d_h * esize(q_dt)) % 16 != 0) return PACT_ERR_ALIGN;
-    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q);
+    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, 0);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     Batch bt;
@@ -198,7 +198,7 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if ((rc = check_tensor(keys, k_dt, dk))) return rc;
     if ((rc = check_params(0.0f, d_c, d_n, 0.0f))) return rc;
     if (fallback_T < 0) return PACT_ERR_PARAM;
-    const WsLayout L = make_layout(n, 1, n, 1, 1);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -225,7 +225,7 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     int rc;
     if ((rc = check_tensor(keys, k_dt, dk))) return rc;
     if ((rc = check_params(0.0f, d_c, 1.0f, alpha))) return rc;
-    const WsLayout L = make_layout(n, 1, n, 1, 1);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -251,7 +251,7 @@ int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_tensor(hidden, h_dt, h))) return rc;
     if (!dtype_ok(out_dt)) return PACT_ERR_DTYPE;
     if (!aligned16(merged) || ((int64_t)h * esize(out_dt)) % 16 != 0) return PACT_ERR_ALIGN;
-    const WsLayout L = make_layout(n, 1, n, 1, 1);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, 0);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -300,7 +300,7 @@ int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if (n < 1 || n > PACT_MAX_TOKENS || (q_rows != n && q_rows != 1)) return PACT_ERR_SHAPE;
     if ((rc = check_params(p->lambda, p->d_c, p->d_n, p->alpha))) return rc;
     if (p->fallback_T < 0) return PACT_ERR_PARAM;
-    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q);
+    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     Batch bt;
@@ -340,7 +340,7 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
     const int32_t total = cu_seqlens[batch];
     if (q_rows != total && q_rows != batch) return PACT_ERR_SHAPE;
     bt.B = batch; bt.n_max = n_max; bt.W = (n_max + 63) / 64; bt.total = total;
-    const WsLayout L = make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q);
+    const WsLayout L = make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     const Ws w = resolve(ws, L);

@@ -20,6 +20,7 @@ struct PrepArgs {
     uint32_t* status; int32_t* ident; int32_t* near_cnt;
     pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
     const int32_t* n_idx_dev; uint32_t* zeros;
+    uint16_t* ksplit;                        // fp32 keys only: [total][3][dk rounded up to 8] bf16 parts for the Gram passes
     int32_t mode; int32_t n_key_blocks;
 };
 
@@ -55,6 +56,30 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         const size_t g = (size_t)sg.base + i;
         const char* row = a.keys + g * (size_t)a.dk * Elem<KDT>::BYTES;
         const double v = wave_dot64<KDT>(row, row, a.dk, lane);
+        if constexpr (KDT == PACT_F32) {
+            // x = hi + mid + lo, each the bf16 nearest to what the parts before it leave (the
+            // differences are exact in fp32); together they carry the 24 bits of x
+            const int dkp = (a.dk + 7) & ~7;                   // plane pitch: whole 16-byte chunks, zero-padded
+            uint16_t* sp = a.ksplit + g * (size_t)(3 * dkp);
+            for (int e = lane * 4; e < dkp; e += 256) {
+                const float4 x4 = (e < a.dk) ? *(const float4*)(row + (size_t)e * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float x[4] = {x4.x, x4.y, x4.z, x4.w};
+                uint32_t part[3][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float r = x[i];
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl) {
+                        part[pl][i] = f32_to_bf16_rne(r);
+                        r -= __uint_as_float(part[pl][i] << 16);
+                    }
+                }
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl)
+                    *(uint2*)(sp + (size_t)pl * dkp + e) =
+                        make_uint2(part[pl][0] | (part[pl][1] << 16), part[pl][2] | (part[pl][3] << 16));
+            }
+        }
         uint64_t* arow = a.adj + ((size_t)b * bt.n_max + i) * bt.W;
         const int Wn = (sg.n + 63) >> 6;
         for (int k = lane; k < Wn; k += 64) arow[k] = 0ull;
@@ -578,7 +603,7 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
     a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
     a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt;
     a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
-    a.zeros = w.zeros;
+    a.zeros = w.zeros; a.ksplit = w.ksplit;
     a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;
     dim3 grid(a.n_key_blocks + (q ? QG_CHUNKS : 0), bt.B);
     return (k_dt == PACT_BF16) ? launch_prep_q<PACT_BF16>(bt, a, q_dt, grid, st)

@@ -14,7 +14,7 @@
 //    halves the L2 traffic per flop of 128x128 tiles (the L2 -> CU path is what limits this
 //    contraction at a key width of 512), 128x256 is for launches that would otherwise leave
 //    CUs without a tile; each wavefront computes (32*MI) x 64 of it as MI x 2
-//    v_mfma_f32_32x32x16_bf16 (or 32x32x2_f32) accumulators;
+//    v_mfma_f32_32x32x16_bf16 accumulators (fp32 keys: as three bf16 planes, six passes);
 //  * the key rows stream in 128-byte slices (whole cache lines: eight lanes fetch one row's
 //    line) straight from global memory into a ring of LDS stages (global_load_lds_dwordx4: no
 //    staging registers); waits on the ring are explicit (s_waitcnt vmcnt + s_barrier);
@@ -155,14 +155,7 @@ template <> struct Mfma<PACT_BF16> {
                                                     __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 };
-template <> struct Mfma<PACT_F32> {
-    __device__ static __forceinline__ void run(const u32x4_t& a, const u32x4_t& b, f32x16_t& c) {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
-    }
-};
+template <> struct Mfma<PACT_F32X3> : Mfma<PACT_BF16> {};
 
 // Density pass with t x t square tiles on g workgroups: do mirrored tiles (upper triangle only,
 // longer epilogue) save at least one turn in eight of a workgroup's tile loop?
@@ -203,9 +196,19 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     float* sRinv = (float*)((char*)s_ring + NSTAGE * STAGE_BYTES);   // [TILE_R]
     lds_f64* sRho = (lds_f64*)(ring + NSTAGE * STAGE_BYTES + TILE_R * sizeof(float));   // [4][64]
 
-    const int row_bytes = ga.dk * Elem<DT>::BYTES;
-    const int nSlices = (row_bytes + SLICE_BYTES - 1) / SLICE_BYTES;
-    const char* __restrict__ keys = ga.keys + (size_t)sg.base * row_bytes;
+    // A row is dk bf16 values; fp32 keys arrive as three such planes per token (hi, mid, lo:
+    // x = hi + mid + lo to 24 bits), each padded to whole 16-byte chunks.  Their product is then
+    // six passes over the key width, u.v = sum over the plane pairs below of plane_a(u).plane_b(v)
+    // (what is left out - mid.lo, lo.mid, lo.lo - is below 2^-23 |u||v|), smallest terms first:
+    // every fp32 rounding of the accumulator is relative to its size at that moment, so the
+    // five passes of small terms cost next to nothing in accuracy and the hi.hi pass at the end
+    // the same as a plain bf16 product.
+    constexpr bool SPLIT = DT == PACT_F32X3;
+    const int row_bytes = SPLIT ? ((ga.dk + 7) & ~7) * 2 : ga.dk * Elem<PACT_BF16>::BYTES;   // of one plane
+    const int tok_bytes = SPLIT ? 3 * row_bytes : row_bytes;
+    const int spp = (row_bytes + SLICE_BYTES - 1) / SLICE_BYTES;                             // slices per plane
+    const int nSlices = SPLIT ? 6 * spp : spp;
+    const char* __restrict__ keys = ga.keys + (size_t)sg.base * tok_bytes;
     const int32_t* __restrict__ idxR = ga.idx_rows + sg.base;
     const int32_t* __restrict__ idxC = ga.idx_cols + sg.base;
     const float* __restrict__ rinv = ga.rinv + sg.base;
@@ -283,28 +286,39 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             const int tok = (r >= TILE_R) ? idxC[min(colBase + r - TILE_R, nB - 1)] : idxR[min(rowBase + r, nA - 1)];
             // (with the lane's chunk: the swizzle term depends on the row only through
             //  (row >> 1) & 7, and rows advance by 8 per block)
-            ro[k] = (uint32_t)tok * (uint32_t)row_bytes + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
+            ro[k] = (uint32_t)tok * (uint32_t)tok_bytes + (uint32_t)(((lane & 7) ^ ((r >> 1) & 7)) * 16);
         }
         if (tid_t < TILE_R) sRinv[tid_t] = rinv[idxR[min(rowBase + tid_t, nA - 1)]] * sa_;
         float rj_pre[2];                                    // 1/|u_j| of this lane's two columns (used in the epilogue)
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
 
+        int next_pass = 0, next_ks = 0;                               // of the next slice to fetch (slices are fetched in order)
         auto issue = [&](int s) __attribute__((always_inline)) {      // slice s -> ring slot s % NSTAGE
             const uint32_t slot = dma_lds0 + (uint32_t)((s % NSTAGE) * STAGE_BYTES);
-            if ((s + 1) * SLICE_BYTES <= row_bytes) {
+            // slice within the plane, and the planes the row and the column operand take it from:
+            // (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi), two bits per pass
+            const int pass = SPLIT ? next_pass : 0;
+            const int ks = SPLIT ? next_ks : s;
+            if (SPLIT && ++next_ks == spp) { next_ks = 0; ++next_pass; }
+            const uint32_t offA = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? (uint32_t)(((0x118u >> (2 * pass)) & 3) * row_bytes) : 0u);
+            const uint32_t offB = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? (uint32_t)(((0x052u >> (2 * pass)) & 3) * row_bytes) : 0u);
+            if ((ks + 1) * SLICE_BYTES <= row_bytes) {
                 // a whole slice: scalar base + (row offset + chunk) + slice offset, one add per block.
                 // (These instructions sit between the barrier and the first MFMA of every
                 //  wavefront, i.e. the matrix cores idle meanwhile: they are kept few.)
 #pragma unroll
-                for (int k = 0; k < NB; ++k) dma16_off(keys, ro[k] + (uint32_t)(s * SLICE_BYTES), slot + k * 1024);
+                for (int k = 0; k < NB; ++k) {
+                    const bool colRows = wave * NB * 8 + 8 * k >= TILE_R;          // (wave-uniform)
+                    dma16_off(keys, ro[k] + (colRows ? offB : offA), slot + k * 1024);
+                }
             } else {
 #pragma unroll
                 for (int k = 0; k < NB; ++k) {
+                    const bool colRows = wave * NB * 8 + 8 * k >= TILE_R;
                     const int chunk = (lane & 7) ^ (((dma_row0 + 8 * k) >> 1) & 7);
-                    const int byte0 = s * SLICE_BYTES + chunk * 16;
-                    const bool ok = byte0 < row_bytes;                 // past the key width: zeros
-                    const char* src = ok ? keys + (ro[k] - (uint32_t)(chunk * 16) + (uint32_t)byte0) : ga.zeros;
+                    const bool ok = ks * SLICE_BYTES + chunk * 16 < row_bytes;     // past the key width: zeros
+                    const char* src = ok ? keys + (ro[k] + (colRows ? offB : offA)) : ga.zeros;
                     dma16(src, slot + k * 1024);
                 }
             }
@@ -339,7 +353,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) fb[buf][j] = *(const lds_u32x4*)(st + fragB0 + j * 32 * SLICE_BYTES + co);
             };
-            constexpr int MF = (DT == PACT_BF16) ? 1 : 4;       // MFMA instructions per fragment pair
+            constexpr int MF = 1;                               // MFMA instructions per fragment pair
             load_frags(0, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, MI + 2, 0);
             // (the next fetches are issued while the first fragments are on their way from the LDS:
@@ -697,7 +711,7 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
     static bool raised[2] = {false, false};
     const int di = k_dt == PACT_BF16 ? 1 : 0;
     const void* fn = (k_dt == PACT_BF16) ? (const void*)gram_kernel<PACT_BF16, MODE, MI, STAT, SYM>
-                                         : (const void*)gram_kernel<PACT_F32, MODE, MI, STAT, SYM>;
+                                         : (const void*)gram_kernel<PACT_F32X3, MODE, MI, STAT, SYM>;
     if (!raised[di]) {
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PACT_ERR_HIP;
@@ -706,7 +720,7 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
     if (k_dt == PACT_BF16)
         PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_BF16, MODE, MI, STAT, SYM>), grid, dim3(512), lds, st, bt, ga);
     else
-        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32, MODE, MI, STAT, SYM>), grid, dim3(512), lds, st, bt, ga);
+        PACT_LAUNCH_SHMEM(name, (gram_kernel<PACT_F32X3, MODE, MI, STAT, SYM>), grid, dim3(512), lds, st, bt, ga);
     return PACT_OK;
 }
 
@@ -716,6 +730,8 @@ static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_d
 template <int MODE>
 static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
                        const char* name, long tiles256, bool mirrored, int* grid_out) {
+    if (!ga.keys || !ga.idx_rows || !ga.idx_cols || !ga.rep || !ga.rinv || !ga.zeros || !ga.adj || ga.dk < 1)
+        return PACT_ERR_NULL;                     // (an argument block that was not filled in completely)
     const bool big = tiles256 * bt.B >= 256;
     if constexpr (MODE == MODE_DENSITY) {
         if (ga.stat) {                            // with the key-distance statistic
@@ -731,8 +747,10 @@ static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hip
 
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                         const int32_t* idx, pact_report* rep, bool want_stat, int* stat_words, hipStream_t st) {
-    GramArgs ga;
-    ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = idx; ga.idx_cols = idx; ga.rep = rep;
+    GramArgs ga = {};
+    // (fp32 keys: their three bf16 planes)
+    ga.keys = (k_dt == PACT_F32) ? (const char*)w.ksplit : (const char*)keys;
+    ga.dk = dk; ga.idx_rows = idx; ga.idx_cols = idx; ga.rep = rep;
     ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.cbest = nullptr; ga.rho_part = w.rho_part;
     ga.near_list = w.near_list; ga.near_cnt = w.near_cnt; ga.stat = want_stat ? w.stat : nullptr; ga.margin = (float)cos_margin(dk);
     const long t1 = (bt.n_max + 255) / 256;
@@ -754,8 +772,9 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
 int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                            const int32_t* pruned_idx, const int32_t* center_idx, pact_report* rep,
                            hipStream_t st) {
-    GramArgs ga;
-    ga.keys = (const char*)keys; ga.dk = dk; ga.idx_rows = center_idx; ga.idx_cols = pruned_idx;
+    GramArgs ga = {};
+    ga.keys = (k_dt == PACT_F32) ? (const char*)w.ksplit : (const char*)keys;
+    ga.dk = dk; ga.idx_rows = center_idx; ga.idx_cols = pruned_idx;
     ga.rep = rep; ga.rinv = w.rinv; ga.zeros = (const char*)w.zeros; ga.adj = w.adj; ga.cbest = w.cbest;
     ga.rho_part = nullptr;
     ga.near_list = nullptr; ga.near_cnt = nullptr; ga.stat = nullptr; ga.margin = (float)cos_margin(dk);

@@ -47,6 +47,7 @@ struct WsLayout {
     size_t rho_part;                                   // [B][W][n_max] f64
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
+    size_t ksplit;                                     // [total][3][dk rounded up to 8] bf16: fp32 clustering keys as three bf16 parts
     size_t near_list, near_cnt, stat;                  // refine list, counter; [B] most negative density exponent seen
     size_t offsets, members;                           // merge CSR (global row index)
     size_t zeros;                                      // 256 zero bytes
@@ -55,7 +56,8 @@ struct WsLayout {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qcols, int64_t n_q) {
+// dk: width of the clustering keys (0 for calls that run no Gram pass)
+inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qcols, int64_t n_q, int64_t dk) {
     WsLayout L;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -85,6 +87,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
     L.zeros = take(256);
+    L.ksplit = take(sizeof(uint16_t) * 3 * total * ((dk + 7) / 8 * 8));   // planes padded to whole 16-byte chunks
     L.total = off;
     return L;
 }
@@ -95,7 +98,7 @@ struct Ws {
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; float* cbest; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
-    int32_t* offsets; int32_t* members; uint32_t* zeros;
+    int32_t* offsets; int32_t* members; uint32_t* zeros; uint16_t* ksplit;
 };
 
 inline Ws resolve(void* base, const WsLayout& L) {
@@ -113,6 +116,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.near_cnt = (int32_t*)(p + L.near_cnt); w.stat = (uint32_t*)(p + L.stat);
     w.offsets = (int32_t*)(p + L.offsets);
     w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
+    w.ksplit = (uint16_t*)(p + L.ksplit);
     return w;
 }
 
@@ -178,9 +182,14 @@ int launch_handoff(const Batch& bt, const int32_t* center_idx, const int32_t* cl
 // init modes
 enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_SCORE = 4 };
 
-// Worst-case rounding error of an fp32 matrix-core cosine of two dk-long rows, plus slack for
-// the scaling multiplies; decisions closer than this to a threshold are re-made in fp64.
-inline double cos_margin(int dk) { return (double)(dk + 16) * (1.0 / 8388608.0) + 2e-6; }
+// Worst-case rounding error of an fp32-accumulated matrix-core cosine of two dk-long rows, plus
+// slack for the scaling multiplies and, for fp32 keys, for what their three-part bf16 form
+// leaves out (below 2^-22 of |u||v|); decisions closer than this to a threshold are re-made in fp64.
+inline double cos_margin(int dk) { return (double)(dk + 16) * (1.0 / 8388608.0) + 2.5e-6; }
+
+// Internal element type of the Gram kernel for fp32 keys: each value as the sum of three bf16
+// parts (hi + mid + lo, 24 significant bits), in three planes per token.
+enum { PACT_F32X3 = 2 };
 
 }  // namespace pact
 
@@ -204,6 +213,12 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) { return __uint
 // Counts read back from a device-side report are clamped to the sample size, so that a report
 // the caller never initialised cannot send a kernel out of bounds.
 __device__ __forceinline__ int clamp_count(int v, int n) { return v < 0 ? 0 : (v > n ? n : v); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
 
 // 16 bytes of a row -> up to 8 doubles.  EPL = elements per 16-byte load.
 template <int DT> struct Elem;

@@ -113,11 +113,6 @@ template <> struct StoreOut<PACT_F32> {
         for (int i = 0; i < N; i += 4) *(float4*)(o + i) = make_float4((float)v[i], (float)v[i + 1], (float)v[i + 2], (float)v[i + 3]);
     }
 };
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
 template <> struct StoreOut<PACT_BF16> {
     template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v) {
         uint16_t* o = (uint16_t*)out + e;
