@@ -37,7 +37,8 @@
  *    within alpha*d_c or not) are evaluated in fp64 whenever the fp32 matrix-core value is
  *    closer to the threshold than its worst-case rounding error, and always for the final
  *    nearest-centre choice, so those decisions are the fp64 ones.
- *  - Densities (Eq. 6) are fp64 sums of fp32 terms exp2-evaluated from matrix-core cosines.
+ *  - Densities (Eq. 6) are fp64 sums of fp32 terms exp2-evaluated from matrix-core cosines
+ *    (bf16 keys as they are; fp32 keys as three bf16 parts per value, all 24 bits of them).
  *  - Ties: equal scores at the percentile are all kept; equal densities are processed in
  *    ascending token index; equal distances pick the centre with the lower token index.
  *  - A zero-norm key has cosine 0 (distance 1) to every other token; d_ii = 0.
