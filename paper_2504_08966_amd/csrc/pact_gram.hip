@@ -204,6 +204,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     // five passes of small terms cost next to nothing in accuracy and the hi.hi pass at the end
     // the same as a plain bf16 product.
     constexpr bool SPLIT = DT == PACT_F32X3;
+    constexpr bool SHARE_RING = SPLIT && NSTAGE == 2;   // see the order of the slices below
     const int row_bytes = SPLIT ? ((ga.dk + 7) & ~7) * 2 : ga.dk * Elem<PACT_BF16>::BYTES;   // of one plane
     const int tok_bytes = SPLIT ? 3 * row_bytes : row_bytes;
     const int spp = (row_bytes + SLICE_BYTES - 1) / SLICE_BYTES;                             // slices per plane
@@ -293,16 +294,38 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) rj_pre[j] = rinv[idxC[min(colBase + wc * 64 + j * 32 + l32_, nB - 1)]];
 
-        int next_pass = 0, next_ks = 0;                               // of the next slice to fetch (slices are fetched in order)
+        // Order of the slices.  bf16 keys: along the key width.  fp32 keys (three planes): the five
+        // pairs of small terms first, then (hi,hi) along the key width (see above).  With two ring
+        // stages (256 x 256 tiles, where a wavefront fetches rows of one operand only) the small
+        // pairs of one slice of the key width follow each other so that each step changes one
+        // operand only - (hi,lo) (hi,mid) (mid,mid) (mid,hi) (lo,hi) - and the other half of the
+        // stage is reused instead of fetched again: the two halves of the ring then alternate
+        // independently (eight instead of twelve plane slices per slice of the key width).
+        constexpr bool SHARE = SHARE_RING;
+        static_assert(!SHARE || NB * 8 * 4 == TILE_R, "four wavefronts fetch the row operand, four the column operand");
+        int next_pass = 0, next_ks = 0;          // of the next slice to fetch (slices are fetched in order)
+        int slotA = 1, slotB = 1;                // SHARE: ring slot that holds the newest row / column operand
         auto issue = [&](int s) __attribute__((always_inline)) {      // slice s -> ring slot s % NSTAGE
-            const uint32_t slot = dma_lds0 + (uint32_t)((s % NSTAGE) * STAGE_BYTES);
-            // slice within the plane, and the planes the row and the column operand take it from:
-            // (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi), two bits per pass
-            const int pass = SPLIT ? next_pass : 0;
+            const int pass = SPLIT ? next_pass : 0;   // SHARE: position in the group of five small pairs, 5 = (hi,hi)
             const int ks = SPLIT ? next_ks : s;
-            if (SPLIT && ++next_ks == spp) { next_ks = 0; ++next_pass; }
-            const uint32_t offA = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? (uint32_t)(((0x118u >> (2 * pass)) & 3) * row_bytes) : 0u);
-            const uint32_t offB = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? (uint32_t)(((0x052u >> (2 * pass)) & 3) * row_bytes) : 0u);
+            uint32_t planeA, planeB;
+            bool fetchA = true, fetchB = true;
+            if constexpr (SHARE) {
+                planeA = (0x250u >> (2 * pass)) & 3;  planeB = (0x016u >> (2 * pass)) & 3;
+                fetchA = (0x35u >> pass) & 1;         fetchB = (0x2Bu >> pass) & 1;
+                if (pass == 5) { ++next_ks; }
+                else if (++next_pass == 5) { next_pass = 0; if (++next_ks == spp) { next_ks = 0; next_pass = 5; } }
+                slotA ^= fetchA ? 1 : 0;
+                slotB ^= fetchB ? 1 : 0;
+            } else {
+                // (hi,lo) (lo,hi) (mid,mid) (hi,mid) (mid,hi) (hi,hi), two bits per pass
+                planeA = (0x118u >> (2 * pass)) & 3;  planeB = (0x052u >> (2 * pass)) & 3;
+                if (SPLIT && ++next_ks == spp) { next_ks = 0; ++next_pass; }
+            }
+            const uint32_t offA = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? planeA * (uint32_t)row_bytes : 0u);
+            const uint32_t offB = (uint32_t)(ks * SLICE_BYTES) + (SPLIT ? planeB * (uint32_t)row_bytes : 0u);
+            const uint32_t ldsA = dma_lds0 + (uint32_t)((SHARE ? slotA : s % NSTAGE) * STAGE_BYTES);
+            const uint32_t ldsB = dma_lds0 + (uint32_t)((SHARE ? slotB : s % NSTAGE) * STAGE_BYTES);
             if ((ks + 1) * SLICE_BYTES <= row_bytes) {
                 // a whole slice: scalar base + (row offset + chunk) + slice offset, one add per block.
                 // (These instructions sit between the barrier and the first MFMA of every
@@ -310,7 +333,8 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 #pragma unroll
                 for (int k = 0; k < NB; ++k) {
                     const bool colRows = wave * NB * 8 + 8 * k >= TILE_R;          // (wave-uniform)
-                    dma16_off(keys, ro[k] + (colRows ? offB : offA), slot + k * 1024);
+                    if (colRows ? fetchB : fetchA)
+                        dma16_off(keys, ro[k] + (colRows ? offB : offA), (colRows ? ldsB : ldsA) + k * 1024);
                 }
             } else {
 #pragma unroll
@@ -319,7 +343,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                     const int chunk = (lane & 7) ^ (((dma_row0 + 8 * k) >> 1) & 7);
                     const bool ok = ks * SLICE_BYTES + chunk * 16 < row_bytes;     // past the key width: zeros
                     const char* src = ok ? keys + (ro[k] + (colRows ? offB : offA)) : ga.zeros;
-                    dma16(src, slot + k * 1024);
+                    if (colRows ? fetchB : fetchA) dma16(src, (colRows ? ldsB : ldsA) + k * 1024);
                 }
             }
         };
@@ -344,14 +368,16 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             __builtin_amdgcn_s_barrier();      // ... for every wavefront; and slot (s-1)%NSTAGE is free
 
             // the fragments of k-group g+1 are read from LDS while the MFMAs of group g run
-            const lds_char* st = ring + (s % NSTAGE) * STAGE_BYTES;
+            // (slotA / slotB still name the slots of this slice: the next fetch comes further down)
+            const lds_char* stA = ring + (SHARE ? slotA : s % NSTAGE) * STAGE_BYTES;
+            const lds_char* stB = ring + (SHARE ? slotB : s % NSTAGE) * STAGE_BYTES;
             u32x4_t fa[2][MI], fb[2][2];
             auto load_frags = [&](int g, int buf) __attribute__((always_inline)) {
                 const uint32_t co = (uint32_t)(((2 * g + hh_) ^ swz) << 4);
 #pragma unroll
-                for (int i = 0; i < MI; ++i) fa[buf][i] = *(const lds_u32x4*)(st + fragA0 + i * 32 * SLICE_BYTES + co);
+                for (int i = 0; i < MI; ++i) fa[buf][i] = *(const lds_u32x4*)(stA + fragA0 + i * 32 * SLICE_BYTES + co);
 #pragma unroll
-                for (int j = 0; j < 2; ++j) fb[buf][j] = *(const lds_u32x4*)(st + fragB0 + j * 32 * SLICE_BYTES + co);
+                for (int j = 0; j < 2; ++j) fb[buf][j] = *(const lds_u32x4*)(stB + fragB0 + j * 32 * SLICE_BYTES + co);
             };
             constexpr int MF = 1;                               // MFMA instructions per fragment pair
             load_frags(0, 0);
@@ -382,6 +408,11 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             }
         }
         PACT_STAMP(2);
+        // LDS the epilogue may use for its buffers: the ring stage that the last slice did not
+        // occupy; where the two halves of the ring alternate independently the last slice may
+        // occupy halves of both, so there every wavefront finishes its reads first.
+        const int freeStage = SHARE_RING ? 0 : (nSlices % NSTAGE);
+        if constexpr (SHARE_RING) __builtin_amdgcn_s_barrier();
 
         // ------------------------------------------------------------------ epilogue
         // acc[i][j][r] holds row  rowBase + wr*WROWS + i*32 + 8*(r/4) + 4*hh + (r%4)
@@ -404,10 +435,10 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         }
         double rho[2][2] = {{0.0, 0.0}, {0.0, 0.0}};
         // per-wavefront buffer of undecided pairs, in a ring slot no wavefront reads any more
-        lds_uint2* nearBuf = (lds_uint2*)(ring + (nSlices % NSTAGE) * STAGE_BYTES + wave * (NEAR_BUF * 8));
+        lds_uint2* nearBuf = (lds_uint2*)(ring + freeStage * STAGE_BYTES + wave * (NEAR_BUF * 8));
         int nearN = 0;
         // mirrored tiles: the wavefronts' row sums (128 rows x 64 columns each), behind the pair buffers
-        lds_f64* rowBuf = (lds_f64*)(ring + (nSlices % NSTAGE) * STAGE_BYTES + 8 * (NEAR_BUF * 8));
+        lds_f64* rowBuf = (lds_f64*)(ring + freeStage * STAGE_BYTES + 8 * (NEAR_BUF * 8));
         auto flush_near = [&]() __attribute__((always_inline)) {
             int base_slot = 0;
             // (one 64-bit atomic: slots in the low word, ordered pairs in the high word)
