@@ -170,7 +170,18 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     constexpr int TILE_R = SH::TILE_R, STAGE_BYTES = SH::STAGE_BYTES, NSTAGE = SH::NSTAGE;
     constexpr int AHEAD = SH::AHEAD, NB = SH::NB, WROWS = 32 * MI;
     extern __shared__ uint4 s_ring[];                         // NSTAGE stages, TILE_R floats, 256 doubles
-    const int b = blockIdx.y;
+    // Which sample, and which of its workgroups.  Workgroups are dealt to the 8 XCDs round-robin
+    // in launch order (XCD = linear workgroup id mod 8) and every XCD has its own L2.  With a
+    // multiple of 8 samples, all workgroups of a sample are taken from one XCD (sample mod 8), so
+    // that the sample's keys (a few MB) stay in that L2 instead of passing through all eight.
+    const bool by_xcd = (gridDim.y & 7) == 0 && (gridDim.x & 7) == 0;
+    int b = blockIdx.y, wg = blockIdx.x;
+    if (by_xcd) {
+        const int lin = (int)(blockIdx.x + gridDim.x * blockIdx.y);
+        const int in_xcd = lin >> 3;                          // 0 .. gridDim.x * gridDim.y / 8 - 1
+        b = (lin & 7) + 8 * (in_xcd / (int)gridDim.x);
+        wg = in_xcd % (int)gridDim.x;
+    }
     const Seg sg = bt.s[b];
     const int q_kept = clamp_count(ga.rep[b].n_kept, sg.n);
     // density pass: kept x kept; candidate pass: rows are the centres, columns the pruned tokens
@@ -179,7 +190,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_pruned, sg.n - q_kept);
     if (nA <= 0 || nB <= 0) {
         if (STAT && (threadIdx.x & 63) == 0)
-            ga.stat[((size_t)b * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)] = 0u;
+            ga.stat[((size_t)b * gridDim.x + wg) * 8 + (threadIdx.x >> 6)] = 0u;
         return;
     }
     PACT_STAMP(0);
@@ -239,16 +250,16 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     // transposed bits).  That epilogue is longer, and with a tile or less per workgroup the
     // kernel lasts as long as its slowest tile whatever their number: mirrored tiles are used
     // when they save at least one turn in eight of the workgroups' tile loop.
-    const int xcd = blockIdx.x & 7;
+    const int xcd = wg & 7;
     const long nFull = (long)tilesR * tilesC;
     const long nTri = (long)tilesR * (tilesR + 1) / 2;
     bool sym = false;
     if constexpr (SYM) sym = mirrored_tiles_pay(tilesR, (int)gridDim.x);
     const long nTiles = sym ? nTri : nFull;
-    const bool banded = nTiles >= 8 && (gridDim.x & 7) == 0;
+    const bool banded = !by_xcd && nTiles >= 8 && (gridDim.x & 7) == 0;   // (a sample on one XCD: one band)
     const int l_lo = banded ? (int)(xcd * nTiles / 8) : 0;
     const int l_hi = banded ? (int)((xcd + 1) * nTiles / 8) : (int)nTiles;
-    const int t_first = l_lo + (banded ? (int)(blockIdx.x >> 3) : (int)blockIdx.x);
+    const int t_first = l_lo + (banded ? (wg >> 3) : wg);
     const int t_step = banded ? (int)(gridDim.x >> 3) : (int)gridDim.x;
 
     float far = 0.0f;              // most negative density exponent seen = largest distance (density pass)
@@ -716,7 +727,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         // than the kernel); the kernel that finishes the densities takes the minimum
 #pragma unroll
         for (int sft = 32; sft >= 1; sft >>= 1) far = fminf(far, __shfl_xor(far, sft, 64));
-        if (lane == 0) ga.stat[((size_t)b * gridDim.x + blockIdx.x) * 8 + wave] = far < 0.0f ? __float_as_uint(far) : 0u;
+        if (lane == 0) ga.stat[((size_t)b * gridDim.x + wg) * 8 + wave] = far < 0.0f ? __float_as_uint(far) : 0u;
     }
 }
 
