@@ -237,6 +237,16 @@ int pact_profile_read(const char** names, float* ms, int32_t max_records);
  * WRITE_SIZE) a dispatch of known traffic to be scaled by.  Benchmarks only. */
 int pact_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Diagnostic (host only, nothing is enqueued): how a matrix pass of a batched call deals the
+ * chip's 256 workgroup slots to the samples, given the number of output tiles each sample is
+ * expected to have.  Slot i runs on XCD i mod 8.
+ *   tiles     [batch] host      expected tiles per sample (>= 1)
+ *   wg_map    [256] host out    (sample << 8) | (number of that workgroup within its sample), 0xFFFF = spare slot
+ *   wg_count  [batch] host out  workgroups per sample: at least 1, at most its tiles, so that the
+ *                               most loaded workgroup has as few tiles as 256 slots allow
+ * Returns PACT_OK, PACT_ERR_NULL or PACT_ERR_SHAPE. */
+int pact_plan_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, uint16_t* wg_count);
+
 const char* pact_strerror(int status);
 
 #ifdef __cplusplus

@@ -83,6 +83,8 @@ def load_library():
     lib.pact_attention_handoff.argtypes = [vp, vp, vp, vp, C.POINTER(i32), i32, i32, vp, vp, vp]
     lib.pact_calibration_copy.restype = C.c_int
     lib.pact_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.pact_plan_workgroups.restype = C.c_int
+    lib.pact_plan_workgroups.argtypes = [C.POINTER(i32), i32, C.POINTER(C.c_uint16), C.POINTER(C.c_uint16)]
     lib.pact_profile_enable.restype = C.c_int
     lib.pact_profile_enable.argtypes = [C.c_int]
     lib.pact_profile_reset.restype = C.c_int
@@ -277,6 +279,16 @@ def pact_calibration_copy(dst, src):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load_library().pact_calibration_copy(_p(dst), _p(src), nbytes, _stream()), "pact_calibration_copy")
+
+
+def pact_plan_workgroups(tiles):
+    """Diagnostic (host only): (wg_map [256], wg_count [batch]) for samples expected to have `tiles` tiles each."""
+    batch = len(tiles)
+    arr = (C.c_int32 * batch)(*[int(x) for x in tiles])
+    wg_map = (C.c_uint16 * 256)()
+    wg_count = (C.c_uint16 * batch)()
+    _check(load_library().pact_plan_workgroups(arr, batch, wg_map, wg_count), "pact_plan_workgroups")
+    return list(wg_map), list(wg_count)
 
 
 def pact_profile_enable(on: bool):

@@ -407,6 +407,10 @@ int pact_calibration_copy(void* dst, const void* src, size_t bytes, void* stream
     return hipGetLastError() == hipSuccess ? PACT_OK : PACT_ERR_HIP;
 }
 
+int pact_plan_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, uint16_t* wg_count) {
+    return plan_gram_workgroups(tiles, batch, wg_map, wg_count);
+}
+
 const char* pact_strerror(int status) {
     switch (status) {
         case PACT_OK: return "ok";

@@ -59,9 +59,16 @@ struct GramArgs {
     double* rho_part;          // [B][W][n_max], one row per GRAM_RHO_ROWS kept rows
     uint32_t* near_list;       // [B][NEAR_CAP][2]
     int32_t* near_cnt;         // [B][2]: list slots taken, ordered pairs they stand for (8-byte aligned)
-    uint32_t* stat;            // [B][gridDim.x * 8] per wavefront: bits of the most negative density exponent
+    uint32_t* stat;            // [B][stat_wgs * 8] per wavefront: bits of the most negative density exponent
                                // it saw (largest distance), or NULL when the statistic is not wanted
+    int32_t stat_wgs;          // workgroup slots per sample in `stat`
     float margin;              // worst-case fp32 error of a cosine
+    // Batches (mapped != 0): a one-dimensional grid of GRAM_MAX_WORKGROUPS workgroups, shared out
+    // among the samples by size; workgroup i serves sample wg_map[i] >> 8 as its workgroup number
+    // wg_map[i] & 255 of wg_count[sample] (0xFFFF: a spare workgroup).
+    int32_t mapped;
+    uint16_t wg_count[PACT_MAX_BATCH];
+    uint16_t wg_map[GRAM_MAX_WORKGROUPS];
 };
 
 constexpr int TILE_C = 256;
@@ -170,18 +177,21 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     constexpr int TILE_R = SH::TILE_R, STAGE_BYTES = SH::STAGE_BYTES, NSTAGE = SH::NSTAGE;
     constexpr int AHEAD = SH::AHEAD, NB = SH::NB, WROWS = 32 * MI;
     extern __shared__ uint4 s_ring[];                         // NSTAGE stages, TILE_R floats, 256 doubles
-    // Which sample, and which of its workgroups.  Workgroups are dealt to the 8 XCDs round-robin
-    // in launch order (XCD = linear workgroup id mod 8) and every XCD has its own L2.  With a
-    // multiple of 8 samples, all workgroups of a sample are taken from one XCD (sample mod 8), so
-    // that the sample's keys (a few MB) stay in that L2 instead of passing through all eight.
-    const bool by_xcd = (gridDim.y & 7) == 0 && (gridDim.x & 7) == 0;
-    int b = blockIdx.y, wg = blockIdx.x;
-    if (by_xcd) {
-        const int lin = (int)(blockIdx.x + gridDim.x * blockIdx.y);
-        const int in_xcd = lin >> 3;                          // 0 .. gridDim.x * gridDim.y / 8 - 1
-        b = (lin & 7) + 8 * (in_xcd / (int)gridDim.x);
-        wg = in_xcd % (int)gridDim.x;
+    // Which sample, which of its workgroups, and how many it has.  Batches: read from the map the
+    // host made.  Workgroups are dealt to the 8 XCDs round-robin in launch order (XCD = workgroup
+    // number mod 8) and every XCD has its own L2; the map gives a sample workgroups of one XCD
+    // where it can, so that the sample's keys (a few MB) stay in that L2 instead of passing
+    // through all eight, and it gives large samples more workgroups than small ones.
+    int b = blockIdx.y, wg = blockIdx.x, G = gridDim.x;
+    if (ga.mapped) {
+        const uint32_t e = ga.wg_map[blockIdx.x];
+        if (e == 0xFFFFu) return;
+        b = (int)(e >> 8);
+        wg = (int)(e & 255u);
+        G = ga.wg_count[b];
     }
+    if (STAT && wg == 0)                                      // slots no workgroup of this sample writes
+        for (int k = threadIdx.x; k < (ga.stat_wgs - G) * 8; k += 512) ga.stat[((size_t)b * ga.stat_wgs + G) * 8 + k] = 0u;
     const Seg sg = bt.s[b];
     const int q_kept = clamp_count(ga.rep[b].n_kept, sg.n);
     // density pass: kept x kept; candidate pass: rows are the centres, columns the pruned tokens
@@ -190,7 +200,7 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const int nB = (MODE == MODE_DENSITY) ? q_kept : clamp_count(ga.rep[b].n_pruned, sg.n - q_kept);
     if (nA <= 0 || nB <= 0) {
         if (STAT && (threadIdx.x & 63) == 0)
-            ga.stat[((size_t)b * gridDim.x + wg) * 8 + (threadIdx.x >> 6)] = 0u;
+            ga.stat[((size_t)b * ga.stat_wgs + wg) * 8 + (threadIdx.x >> 6)] = 0u;
         return;
     }
     PACT_STAMP(0);
@@ -254,13 +264,13 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
     const long nFull = (long)tilesR * tilesC;
     const long nTri = (long)tilesR * (tilesR + 1) / 2;
     bool sym = false;
-    if constexpr (SYM) sym = mirrored_tiles_pay(tilesR, (int)gridDim.x);
+    if constexpr (SYM) sym = mirrored_tiles_pay(tilesR, G);
     const long nTiles = sym ? nTri : nFull;
-    const bool banded = !by_xcd && nTiles >= 8 && (gridDim.x & 7) == 0;   // (a sample on one XCD: one band)
+    const bool banded = !ga.mapped && nTiles >= 8 && (G & 7) == 0;        // (a sample kept on one XCD: one band)
     const int l_lo = banded ? (int)(xcd * nTiles / 8) : 0;
     const int l_hi = banded ? (int)((xcd + 1) * nTiles / 8) : (int)nTiles;
     const int t_first = l_lo + (banded ? (wg >> 3) : wg);
-    const int t_step = banded ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int t_step = banded ? (G >> 3) : G;
 
     float far = 0.0f;              // most negative density exponent seen = largest distance (density pass)
     for (int tl = t_first; tl < l_hi; tl += t_step) {
@@ -727,27 +737,97 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
         // than the kernel); the kernel that finishes the densities takes the minimum
 #pragma unroll
         for (int sft = 32; sft >= 1; sft >>= 1) far = fminf(far, __shfl_xor(far, sft, 64));
-        if (lane == 0) ga.stat[((size_t)b * gridDim.x + wg) * 8 + wave] = far < 0.0f ? __float_as_uint(far) : 0u;
+        if (lane == 0) ga.stat[((size_t)b * ga.stat_wgs + wg) * 8 + wave] = far < 0.0f ? __float_as_uint(far) : 0u;
     }
 }
 
-// Workgroups per sample: one per CU for a single sample, fewer for batches (the samples' grids
-// run side by side), a multiple of the 8 XCDs (see the tile order).
+// One sample: a workgroup per tile, at most one per CU, a multiple of the 8 XCDs (see the tile order).
 static int gram_grid_x(const Batch& bt, long tiles) {
     long grid_x = tiles;
-    const int cap = (bt.B >= 8) ? 32 : (bt.B >= 2 ? 128 : 256);   // one workgroup per CU, 256 CUs
-    if (grid_x > cap) grid_x = cap;
+    static_assert(GRAM_MAX_WORKGROUPS == 256, "one workgroup per CU, 256 CUs");
+    if (grid_x > GRAM_MAX_WORKGROUPS) grid_x = GRAM_MAX_WORKGROUPS;
     if (grid_x >= 8) grid_x &= ~7L;
     return (int)grid_x;
 }
 
+// Batches: the chip's 256 workgroup slots are shared out among the samples by the number of
+// tiles each is expected to have (tiles[b] >= 1): the fewest turns R of a workgroup's tile loop
+// such that ceil(tiles[b] / R) workgroups per sample fit, spare slots to the samples with the
+// most tiles per workgroup.  Each sample then gets slots of one XCD where it can (slot i belongs
+// to XCD i mod 8), the largest samples first.  The counts are estimates (the real ones are on the
+// device): a sample with more tiles than expected just takes more turns.
+// Fills ga.wg_map / ga.wg_count, returns the largest count.
+static int build_wg_map(int B, const long* tiles, GramArgs& ga) {
+    constexpr int S = GRAM_MAX_WORKGROUPS;
+    int g[PACT_MAX_BATCH], order[PACT_MAX_BATCH];
+    long most_tiles = 1;
+    for (int b = 0; b < B; ++b) most_tiles = tiles[b] > most_tiles ? tiles[b] : most_tiles;
+    long R = 1;
+    for (;; ++R) {                            // (R = most_tiles needs one workgroup per sample, B <= 64 < S)
+        long need = 0;
+        for (int b = 0; b < B; ++b) need += (tiles[b] + R - 1) / R;
+        if (need <= S || R >= most_tiles) break;
+    }
+    int used = 0;
+    for (int b = 0; b < B; ++b) { g[b] = (int)((tiles[b] + R - 1) / R); if (g[b] < 1) g[b] = 1; used += g[b]; }
+    while (used < S) {
+        int best = -1;
+        for (int b = 0; b < B; ++b)
+            if (g[b] < tiles[b] && (best < 0 || (double)tiles[b] / g[b] > (double)tiles[best] / g[best])) best = b;
+        if (best < 0) break;
+        ++g[best]; ++used;
+    }
+    for (int b = 0; b < B; ++b) order[b] = b;
+    for (int i = 1; i < B; ++i)              // by workgroup count, largest first (insertion sort, B <= 64)
+        for (int j = i; j > 0 && g[order[j]] > g[order[j - 1]]; --j) { const int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t; }
+    int freeSlots[8];
+    for (int x = 0; x < 8; ++x) freeSlots[x] = S / 8;
+    for (int i = 0; i < S; ++i) ga.wg_map[i] = 0xFFFFu;
+    int most = 0;
+    for (int k = 0; k < B; ++k) {
+        const int b = order[k];
+        ga.wg_count[b] = (uint16_t)g[b];
+        if (g[b] > most) most = g[b];
+        int left = g[b], rank = 0;
+        while (left > 0) {
+            int x = 0;
+            for (int y = 1; y < 8; ++y) if (freeSlots[y] > freeSlots[x]) x = y;
+            const int take = left < freeSlots[x] ? left : freeSlots[x];
+            for (int t = 0; t < take; ++t) {
+                const int slot = (S / 8 - freeSlots[x]) + t;       // this XCD's next unused slot
+                ga.wg_map[slot * 8 + x] = (uint16_t)((b << 8) | rank++);
+            }
+            freeSlots[x] -= take;
+            left -= take;
+        }
+    }
+    return most;
+}
+
 template <int MODE, int MI, bool STAT, bool SYM>
-static int launch_gram_shape(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hipStream_t st,
+static int launch_gram_shape(const Batch& bt, const GramArgs& ga_in, pact_dtype k_dt, hipStream_t st,
                              const char* name, int* grid_out) {
     typedef Shape<MI> SH;
     const int tilesR = (bt.n_max + SH::TILE_R - 1) / SH::TILE_R, tilesC = (bt.n_max + TILE_C - 1) / TILE_C;
-    const int grid_x = gram_grid_x(bt, (long)tilesR * tilesC);
-    dim3 grid(grid_x, bt.B);
+    GramArgs ga = ga_in;
+    int grid_x = gram_grid_x(bt, (long)tilesR * tilesC);
+    dim3 grid(grid_x, 1);
+    ga.mapped = bt.B > 1;
+    if (ga.mapped) {
+        // tiles a sample is expected to have: kept tokens n - floor(lambda n); density pass
+        // kept x kept (square tiles: the triangle); candidate pass about kept / 2 centres x pruned
+        long tiles[PACT_MAX_BATCH];
+        for (int b = 0; b < bt.B; ++b) {
+            const long n = bt.s[b].n, q = n - (long)floorf(bt.s[b].lambda * (float)n);
+            const long rows = (MODE == MODE_DENSITY) ? q : (q + 1) / 2, cols = (MODE == MODE_DENSITY) ? q : n - q;
+            const long tr = (rows + SH::TILE_R - 1) / SH::TILE_R, tc = (cols + TILE_C - 1) / TILE_C;
+            tiles[b] = (MODE == MODE_DENSITY && SYM) ? tr * (tr + 1) / 2 : tr * tc;
+            if (tiles[b] < 1) tiles[b] = 1;
+        }
+        grid_x = build_wg_map(bt.B, tiles, ga);                // (from here on: the largest count of a sample)
+        grid = dim3(GRAM_MAX_WORKGROUPS, 1);
+    }
+    ga.stat_wgs = grid_x;
     if (grid_out) *grid_out = grid_x;
     const size_t lds = SH::LDS_BYTES;
     static bool raised[2] = {false, false};
@@ -799,7 +879,9 @@ int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dty
     // The count of kept tokens is known on the device only; what the percentile will leave
     // (n - floor(lambda n), more on ties) tells whether mirrored tiles are likely to pay for
     // some sample.  The kernel decides again from the real count, so a wrong guess costs time only.
-    bool mirrored = false;
+    // (In a batch every sample has its own number of workgroups: the build that can mirror is
+    //  used there whenever the tiles are square.)
+    bool mirrored = bt.B > 1;
     const int gx = gram_grid_x(bt, t1 * t1);
     for (int b = 0; b < bt.B; ++b) {
         const int q_est = bt.s[b].n - (int)floorf(bt.s[b].lambda * (float)bt.s[b].n);
@@ -824,6 +906,21 @@ int launch_gram_candidates(const Batch& bt, const Ws& w, const void* keys, pact_
     // typical split (half pruned, a third of the rest centres) sizes the choice
     const long tr = (bt.n_max / 6 + 255) / 256, tc = (bt.n_max / 2 + 255) / 256;
     return launch_gram<MODE_CAND>(bt, ga, k_dt, st, "gram_candidates", tr * tc, false, nullptr);
+}
+
+int plan_gram_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, uint16_t* wg_count) {
+    if (!tiles || !wg_map || !wg_count) return PACT_ERR_NULL;
+    if (batch < 1 || batch > PACT_MAX_BATCH) return PACT_ERR_SHAPE;
+    GramArgs ga = {};
+    long t[PACT_MAX_BATCH];
+    for (int b = 0; b < batch; ++b) {
+        if (tiles[b] < 1) return PACT_ERR_SHAPE;
+        t[b] = tiles[b];
+    }
+    build_wg_map(batch, t, ga);
+    for (int i = 0; i < GRAM_MAX_WORKGROUPS; ++i) wg_map[i] = ga.wg_map[i];
+    for (int b = 0; b < batch; ++b) wg_count[b] = ga.wg_count[b];
+    return PACT_OK;
 }
 
 #ifdef PACT_GRAM_STAMPS

@@ -34,6 +34,7 @@ constexpr int QG_CHUNKS = 512;        // row chunks of the global-query column s
 constexpr int SCORE_TOK_PER_WG = 16;  // tokens (= wavefronts) per workgroup in the logits kernel
 constexpr int PRED_CAP = 64;          // 16-bit slots per kept token: slot 0 = count, then up to 63 preceding neighbours
 constexpr int GRAM_RHO_ROWS = 128;    // kept rows summed into one row of the density partials
+constexpr int GRAM_MAX_WORKGROUPS = 256; // workgroups of 8 wavefronts per sample in a Gram pass (one per CU)
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
 constexpr uint32_t NEAR_MIRROR = 0x80000000u;   // flag in a listed pair's row: the pair (col, row) is meant as well
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
@@ -48,7 +49,7 @@ struct WsLayout {
     size_t rho, rank, status, cnum, cmask;             // per sample, pitch n_max (cmask: W)
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
     size_t ksplit;                                     // [total][3][dk rounded up to 8] bf16: fp32 clustering keys as three bf16 parts
-    size_t near_list, near_cnt, stat;                  // refine list, counter; [B] most negative density exponent seen
+    size_t near_list, near_cnt, stat;                  // refine list, counter; [B][workgroups * 8] most negative density exponent seen
     size_t offsets, members;                           // merge CSR (global row index)
     size_t zeros;                                      // 256 zero bytes
     size_t total;
@@ -83,7 +84,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.heads = take(sizeof(uint16_t) * 4 * B * n_max);
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
     L.near_cnt = take(sizeof(int32_t) * 2 * B);   // per sample: list slots taken, ordered pairs they stand for
-    L.stat = take(sizeof(uint32_t) * B);
+    L.stat = take(sizeof(uint32_t) * B * GRAM_MAX_WORKGROUPS * 8);   // one word per wavefront of the density pass
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
     L.zeros = take(256);
@@ -162,6 +163,8 @@ int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, 
 // wrote to w.stat (0 if not wanted), to be handed to launch_centres.
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                         const int32_t* idx, pact_report* rep, bool want_stat, int* stat_words, hipStream_t st);
+// (diagnostic) the map of workgroup slots to samples that the Gram passes of a batch use
+int plan_gram_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, uint16_t* wg_count);
 int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
                    const int32_t* idx, int32_t* center_idx, int32_t* cluster_id,
                    int32_t* cluster_counts, pact_report* rep, double* rho_opt, int32_t* rank_opt,

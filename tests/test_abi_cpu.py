@@ -108,3 +108,40 @@ def test_valid_call_without_gpu_reports_no_device():
     lib = P.load_library()
     fake = C.c_void_p(0x1000)
     assert lib.pact_prune(fake, 10, 0.5, fake, fake, fake, None, 0, None) == 8
+
+
+def test_workgroup_plan_of_a_batch():
+    """Host logic behind batched calls: the 256 workgroup slots are dealt to the samples by their tiles."""
+    import numpy as np
+    import paper_2504_08966_amd as P
+    rng = np.random.default_rng(5)
+    cases = [[105] * 8, [6, 6, 15, 15, 15, 3, 21, 21, 78, 6, 15, 3, 15, 3, 21, 21], [1] * 64, [2080, 1], [3, 3],
+             [300] * 64, [int(x) for x in rng.integers(1, 500, 37)]]
+    for tiles in cases:
+        wg_map, wg_count = P.pact_plan_workgroups(tiles)
+        B = len(tiles)
+        assert len(wg_map) == 256 and len(wg_count) == B
+        assert all(1 <= c <= t for c, t in zip(wg_count, tiles)) and sum(wg_count) <= 256
+        seen = {}
+        for slot, e in enumerate(wg_map):
+            if e == 0xFFFF:
+                continue
+            b, rank = e >> 8, e & 255
+            assert b < B and rank < wg_count[b] and (b, rank) not in seen
+            seen[(b, rank)] = slot
+        assert len(seen) == sum(wg_count)                          # every workgroup of every sample has a slot
+        # the most loaded workgroup has as few tiles as the slots allow
+        turns = max(-(-t // c) for t, c in zip(tiles, wg_count))
+        if turns > 1:
+            assert sum(-(-t // (turns - 1)) for t in tiles) > 256
+        # all slots are used unless every sample already has a workgroup per tile
+        assert sum(wg_count) == min(256, sum(tiles))
+    # equal samples, a multiple of 8 of them: each sample's workgroups all on one XCD (slot mod 8)
+    wg_map, wg_count = P.pact_plan_workgroups([105] * 8)
+    assert wg_count == [32] * 8
+    for b in range(8):
+        assert len({slot % 8 for slot, e in enumerate(wg_map) if e != 0xFFFF and e >> 8 == b}) == 1
+    with pytest.raises(P.PactError):
+        P.pact_plan_workgroups([0, 5])
+    with pytest.raises(P.PactError):
+        P.pact_plan_workgroups([5] * 65)
