@@ -743,6 +743,24 @@ def test_maximum_token_count_block_by_block():
         np.testing.assert_allclose(g["merged"][c], H[g["cluster_id"] == c].mean(axis=0), rtol=1e-5, atol=1e-30)
 
 
+@pytest.mark.parametrize("sizes,dtype", [([700, 50, 1300], "bf16"), ([300, 2100, 1, 64, 900], "f32"), ([1500, 1500], "f32")])
+def test_small_ragged_batches(sizes, dtype):
+    # batches of 2 to 7 samples: the matrix passes deal their workgroups to the samples by size
+    samples = [_random_sample(900 + 7 * b, n, 2, 2, 32, 64, 0.3 if n > 1 else 0.0, dtype) for b, n in enumerate(sizes)]
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), dtype)
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), dtype)
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), dtype)
+    dcs = [_gap_dc(sm.keys.reshape(sm.n, -1), frac=0.01, window=min(300, max(2, sm.n))) if sm.n > 2 else 0.1 for sm in samples]
+    prms = [P.PactParams(sm.lam, d, 2.0, 1.5) for sm, d in zip(samples, dcs)]
+    o = P.pact_reduce_varlen(hid, ks, ks, qs, 2, 32, 2, cu, prms)
+    torch.cuda.synchronize()
+    for b, sm in enumerate(samples):
+        assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b]), sm, f"sample {b} (n={sm.n})")
+
+
 def test_largest_batch_of_small_samples():
     # 64 samples (the batch limit) of ragged small sizes in one call
     r = np.random.default_rng(77)
