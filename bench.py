@@ -7,7 +7,7 @@ synthetic LLaVA-OneVision-7B-shaped anyres image: N = 7290 tokens, hidden 3584, 
 outputs and workspace are resident in HBM before the timed region; the timed region is K
 back-to-back calls bracketed by device synchronisation.
 
-Prints ONE JSON line (see README): whole-job images/s, ms per step, the roofline
+Prints ONE JSON line: whole-job images/s, ms per step, the roofline
 record of the dominant kernel (per-kernel durations measured with HIP events recorded by the
 library on the launch stream, in a separate pass right after the timed one) and the CPU
 oracle timed on this machine's host cores on the same input.
@@ -163,8 +163,8 @@ def main():
                          "(a dispatch of known HBM traffic for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (samples are independent; "
-              "see DESIGN.md, 'How it would shard'). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (samples are independent and "
+              "would be sharded one group per GPU, with no communication). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
