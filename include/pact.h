@@ -144,7 +144,9 @@ int pact_prune(const float* scores, int32_t n, float lambda,
 
 /* Alg. 2 on the subset `idx` of the n tokens (Eq. 5, Eq. 6, density order, centre selection
  * with the bound d_c, nearest-centre assignment).
- *   keys       [n, dk] k_dt   keys after rotary embedding, heads concatenated (u_i of Sec. 3.2)
+ *   keys       [n, dk] k_dt   keys after rotary embedding, heads concatenated (u_i of Sec. 3.2);
+ *                             n * dk is limited (PACT_ERR_SHAPE beyond): n * dk * 2 < 2^32 for bf16 keys,
+ *                             n * dk * 6 < 2^32 for fp32 keys (the same for every call with clustering keys)
  *   idx        [*n_idx_dev] ascending token indices to cluster, or NULL = all n tokens
  *   n_idx_dev  device int32 holding the subset size (ignored when idx is NULL)
  *   center_idx [n] out: token indices of the C centres, ascending (first C written)

@@ -51,6 +51,12 @@ static int check_tensor(const void* p, int dt, int64_t cols) {
     if (!aligned16(p) || (cols * esize(dt)) % 16 != 0) return PACT_ERR_ALIGN;
     return PACT_OK;
 }
+// The matrix passes address a sample's clustering keys with 32-bit byte offsets (fp32 keys in
+// their three-part bf16 form, 6 bytes per value).
+static int check_key_extent(int64_t n_max, int64_t dk, int k_dt) {
+    const uint64_t tok_bytes = (k_dt == PACT_F32) ? 3ull * (((uint64_t)dk + 7) & ~7ull) * 2 : (uint64_t)dk * 2;
+    return (uint64_t)n_max * tok_bytes > 0xFFFFFFFFull ? PACT_ERR_SHAPE : PACT_OK;
+}
 static int check_ws(const void* ws, size_t ws_bytes, size_t need) {
     if (!ws || ((uintptr_t)ws & 255u) != 0 || ws_bytes < need) return PACT_ERR_WORKSPACE;
     return PACT_OK;
@@ -196,6 +202,7 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if (n < 1 || n > PACT_MAX_TOKENS) return keys ? PACT_ERR_SHAPE : PACT_ERR_NULL;
     int rc;
     if ((rc = check_tensor(keys, k_dt, dk))) return rc;
+    if ((rc = check_key_extent(n, dk, k_dt))) return rc;
     if ((rc = check_params(0.0f, d_c, d_n, 0.0f))) return rc;
     if (fallback_T < 0) return PACT_ERR_PARAM;
     const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
@@ -224,6 +231,7 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if (n < 1 || n > PACT_MAX_TOKENS) return keys ? PACT_ERR_SHAPE : PACT_ERR_NULL;
     int rc;
     if ((rc = check_tensor(keys, k_dt, dk))) return rc;
+    if ((rc = check_key_extent(n, dk, k_dt))) return rc;
     if ((rc = check_params(0.0f, d_c, 1.0f, alpha))) return rc;
     const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
@@ -298,6 +306,7 @@ int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
                                     cluster_counts, rep);
     if (rc) return rc;
     if (n < 1 || n > PACT_MAX_TOKENS || (q_rows != n && q_rows != 1)) return PACT_ERR_SHAPE;
+    if ((rc = check_key_extent(n, (int64_t)n_kv * d_h, k_dt))) return rc;
     if ((rc = check_params(p->lambda, p->d_c, p->d_n, p->alpha))) return rc;
     if (p->fallback_T < 0) return PACT_ERR_PARAM;
     const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
@@ -339,6 +348,7 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
     }
     const int32_t total = cu_seqlens[batch];
     if (q_rows != total && q_rows != batch) return PACT_ERR_SHAPE;
+    if ((rc = check_key_extent(n_max, (int64_t)n_kv * d_h, k_dt))) return rc;
     bt.B = batch; bt.n_max = n_max; bt.W = (n_max + 63) / 64; bt.total = total;
     const WsLayout L = make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;

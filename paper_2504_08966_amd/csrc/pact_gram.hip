@@ -854,6 +854,9 @@ static int launch_gram(const Batch& bt, const GramArgs& ga, pact_dtype k_dt, hip
                        const char* name, long tiles256, bool mirrored, int* grid_out) {
     if (!ga.keys || !ga.idx_rows || !ga.idx_cols || !ga.rep || !ga.rinv || !ga.zeros || !ga.adj || ga.dk < 1)
         return PACT_ERR_NULL;                     // (an argument block that was not filled in completely)
+    // the kernel addresses a sample's key rows with 32-bit byte offsets
+    const uint64_t tok_bytes = (k_dt == PACT_F32) ? 3ull * (((uint64_t)ga.dk + 7) & ~7ull) * 2 : (uint64_t)ga.dk * 2;
+    if ((uint64_t)bt.n_max * tok_bytes > 0xFFFFFFFFull) return PACT_ERR_SHAPE;
     const bool big = tiles256 * bt.B >= 256;
     if constexpr (MODE == MODE_DENSITY) {
         if (ga.stat) {                            // with the key-distance statistic

@@ -75,6 +75,9 @@ def test_argument_validation_is_host_side():
     assert db(d_c=-0.1) == PARAM and db(d_n=0.0) == PARAM and db(T=-1) == PARAM
     assert db(d_c=float("inf")) == PARAM
     assert db(dk=4) == ALIGN and db(dt=5) == DTYPE and db(n=-3) == SHAPE and db(ws_bytes=1000) == WS
+    # a sample's keys are addressed with 32-bit byte offsets (fp32 keys: 6 bytes per value)
+    assert db(n=32768, dk=65536, dt=1) == SHAPE and db(n=32768, dk=24576, dt=0) == SHAPE
+    assert db(n=32768, dk=16384, dt=0, ws_bytes=1000) == WS          # within the limit: the next check answers
     # pact_reincorporate / pact_merge
     assert lib.pact_reincorporate(fake, 1, 16, 64, None, fake, 0.1, 1.5, fake, fake, fake, ws_bytes, None) == NULL
     assert lib.pact_reincorporate(fake, 1, 16, 64, fake, fake, 0.1, -1.0, fake, fake, fake, ws_bytes, None) == PARAM
