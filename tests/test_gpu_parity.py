@@ -761,6 +761,27 @@ def test_small_ragged_batches(sizes, dtype):
         assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b]), sm, f"sample {b} (n={sm.n})")
 
 
+def test_key_distance_statistic_in_a_ragged_batch():
+    # samples of a batch have different numbers of workgroups in the density pass; each sample's
+    # largest key distance is the maximum over its own workgroups' words only
+    sizes = [1400, 60, 2300, 500, 1, 900, 1800, 130]
+    samples = [_random_sample(300 + b, n, 2, 2, 32, 64, 0.25 if n > 1 else 0.0, "bf16") for b, n in enumerate(sizes)]
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), "bf16")
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "bf16")
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "bf16")
+    prms = [P.PactParams(sm.lam, 0.05, 2.0, 1.5, flags=P.PACT_FLAG_KEY_STATS) for sm in samples]
+    o = P.pact_reduce_varlen(hid, ks, ks, qs, 2, 32, 2, cu, prms)
+    torch.cuda.synchronize()
+    for b, sm in enumerate(samples):
+        g = gu.trim(o, sm.n, base=cu[b], b=b)
+        U = sm.keys.reshape(sm.n, -1).astype(np.float64)[g["kept_idx"]]
+        tol = (U.shape[1] + 16) / 2.0 ** 23 + 3e-6
+        assert abs(g["rep"]["max_key_distance"] - po.max_pairwise_distance(U)) <= tol, f"sample {b} (n={sm.n})"
+
+
 def test_largest_batch_of_small_samples():
     # 64 samples (the batch limit) of ragged small sizes in one call
     r = np.random.default_rng(77)
