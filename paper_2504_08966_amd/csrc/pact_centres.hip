@@ -919,7 +919,10 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
 
 // grid (assign_blocks + recovery blocks, B), block 256: the assignment blocks first (their
 // wavefronts live longest).
-template <int DT>
+// PART: NEAREST_BOTH, or a build that holds one of the two searches only (the assignment alone
+// needs fewer registers and runs four wavefronts per SIMD instead of three).
+enum { NEAREST_BOTH = 0, NEAREST_ASSIGN = 1, NEAREST_RECOVER = 2 };
+template <int DT, int PART>
 __global__ __launch_bounds__(256) void nearest_centre_kernel(Batch bt, NearArgs a) {
     __shared__ int s_cand[4][CAND_BUF], s_ctok[4][CAND_BUF];
     __shared__ float s_ccos[4][CAND_BUF];
@@ -928,16 +931,25 @@ __global__ __launch_bounds__(256) void nearest_centre_kernel(Batch bt, NearArgs 
     lds_i32* cand = (lds_i32*)s_cand[wave];
     lds_i32* ctok = (lds_i32*)s_ctok[wave];
     lds_f32* ccos = (lds_f32*)s_ccos[wave];
-    if ((int)blockIdx.x < a.assign_blocks) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
+    if constexpr (PART == NEAREST_ASSIGN) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
+    else if constexpr (PART == NEAREST_RECOVER) recover_body<DT>(bt, a, blockIdx.x, gridDim.x, (lds_i32*)s_list);
+    else if ((int)blockIdx.x < a.assign_blocks) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
     else recover_body<DT>(bt, a, blockIdx.x - a.assign_blocks, gridDim.x - a.assign_blocks, (lds_i32*)s_list);
 }
 
+template <int PART>
+static int launch_nearest_part(const Batch& bt, const NearArgs& a, int blocks, pact_dtype k_dt, const char* name,
+                               hipStream_t st) {
+    dim3 grid(blocks, bt.B);
+    if (k_dt == PACT_BF16) PACT_LAUNCH(name, (nearest_centre_kernel<PACT_BF16, PART>), grid, dim3(256), st, bt, a);
+    else PACT_LAUNCH(name, (nearest_centre_kernel<PACT_F32, PART>), grid, dim3(256), st, bt, a);
+    return PACT_OK;
+}
 static int launch_nearest(const Batch& bt, const NearArgs& a, int recover_blocks, pact_dtype k_dt, const char* name,
                           hipStream_t st) {
-    dim3 grid(a.assign_blocks + recover_blocks, bt.B);
-    if (k_dt == PACT_BF16) PACT_LAUNCH(name, nearest_centre_kernel<PACT_BF16>, grid, dim3(256), st, bt, a);
-    else PACT_LAUNCH(name, nearest_centre_kernel<PACT_F32>, grid, dim3(256), st, bt, a);
-    return PACT_OK;
+    if (recover_blocks == 0) return launch_nearest_part<NEAREST_ASSIGN>(bt, a, a.assign_blocks, k_dt, name, st);
+    if (a.assign_blocks == 0) return launch_nearest_part<NEAREST_RECOVER>(bt, a, recover_blocks, k_dt, name, st);
+    return launch_nearest_part<NEAREST_BOTH>(bt, a, a.assign_blocks + recover_blocks, k_dt, name, st);
 }
 
 // Stand-alone pact_reincorporate: totals of recovered / dropped tokens (the fused path gets
@@ -1021,7 +1033,15 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
         a.idx = kept_idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
         a.assign_blocks = (bt.n_max + 3) / 4;
     }
-    if ((rc = launch_nearest(bt, a, (bt.n_max + 15) / 16, k_dt, "reinc_assign", st))) return rc;
+    if (kept_idx && bt.total >= 20000) {
+        // Large batches are bound by how many wavefronts of these searches the chip holds: the two
+        // searches then go out as two launches, the assignment in its leaner build.  (One image:
+        // one launch, the second launch floor would cost more than the occupancy gives.)
+        NearArgs only = a;
+        only.assign_blocks = 0;
+        if ((rc = launch_nearest(bt, a, 0, k_dt, "assign", st))) return rc;
+        if ((rc = launch_nearest(bt, only, (bt.n_max + 15) / 16, k_dt, "reincorporate", st))) return rc;
+    } else if ((rc = launch_nearest(bt, a, (bt.n_max + 15) / 16, k_dt, "reinc_assign", st))) return rc;
     if (count_totals)
         PACT_LAUNCH("count_recovered", count_recovered_kernel, dim3(bt.B), dim3(1024), st, bt, rep,
                     pruned_idx, cluster_id);
