@@ -782,6 +782,41 @@ def test_key_distance_statistic_in_a_ragged_batch():
         assert abs(g["rep"]["max_key_distance"] - po.max_pairwise_distance(U)) <= tol, f"sample {b} (n={sm.n})"
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_dtypes_and_batches(seed):
+    # 20 random calls per seed: 1 to 16 samples of 1 to ~1800 tokens (a few single samples beyond
+    # 4096 kept tokens), both dtypes, key widths with ragged slices, all lambda / alpha corners
+    rng = np.random.default_rng(seed)
+    for case in range(20):
+        dtype = str(rng.choice(["f32", "bf16"]))
+        n_kv, d_h = int(rng.choice([1, 2, 4])), int(rng.choice([8, 16, 32, 40, 64, 128]))
+        if dtype == "bf16" and (n_kv * d_h) % 8:
+            d_h = 16
+        B = int(rng.choice([1, 1, 2, 3, 8, 9, 16]))
+        top = 4600 if (B <= 2 and rng.random() < 0.25) else (1800 if B <= 8 else 700)
+        sizes = [int(rng.integers(1, top)) for _ in range(B)]
+        alpha = float(rng.choice([0.0, 1.0, 1.5, 3.0]))
+        samples = [_random_sample(int(rng.integers(1 << 30)), n, n_kv, n_kv, d_h, 64,
+                                  float(rng.choice([0.0, 0.2, 0.45, 0.7])) if n > 1 else 0.0, dtype) for n in sizes]
+        dcs = [_gap_dc(sm.keys.reshape(sm.n, -1), frac=float(rng.choice([0.002, 0.01, 0.05])), window=min(200, max(2, sm.n)))
+               if sm.n > 3 else 0.1 for sm in samples]
+        cu = [0]
+        for sm in samples:
+            cu.append(cu[-1] + sm.n)
+        hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), dtype)
+        ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), dtype)
+        qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), dtype)
+        prms = [P.PactParams(sm.lam, d, 2.0, alpha) for sm, d in zip(samples, dcs)]
+        if B == 1:
+            o = P.pact_reduce(hid, ks, ks, qs, n_kv, d_h, n_kv, prms[0])
+        else:
+            o = P.pact_reduce_varlen(hid, ks, ks, qs, n_kv, d_h, n_kv, cu, prms)
+        torch.cuda.synchronize()
+        for b, sm in enumerate(samples):
+            assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b], alpha=alpha), sm,
+                        f"seed {seed} case {case} ({dtype}, dk={n_kv * d_h}, sizes={sizes}) sample {b}")
+
+
 def test_largest_batch_of_small_samples():
     # 64 samples (the batch limit) of ragged small sizes in one call
     r = np.random.default_rng(77)
