@@ -63,8 +63,9 @@ def measured_traffic(kernel: str):
     return None
 
 
-def other_configs(P, gen, torch, np):
-    """us per call of the other workload shapes (warm, back to back), with their counts."""
+def other_configs(P, gen, torch, np, only=None, steps_override=None):
+    """us per call of the other workload shapes (warm, back to back), with their counts.
+    only: run just that shape (for a profiler run of one shape), steps_override calls of it."""
     with open(os.path.join(ROOT, "pact_synth", "manifest.json")) as f:
         man = json.load(f)
 
@@ -102,6 +103,9 @@ def other_configs(P, gen, torch, np):
 
     out = {}
     for name, steps in (("img_0p5b", 200), ("vid_long", 20)):
+        if only is not None and name != only:
+            continue
+        steps = steps_override or steps
         cfg = gen.CONFIGS[name]
         sm = gen.make_sample(cfg, 0)
         m = entry(sm)
@@ -119,8 +123,12 @@ def other_configs(P, gen, torch, np):
                      "kernels_us": kernel_table(lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv,
                                                                       prm, ws=ws, out=o))}
         del hid, ks, qs, ws, o
-    for name, samples, steps in (("vid_7b_batch8", gen.make_batch("vid_7b", 0), 30),
-                                 ("varlen16", gen.make_varlen_batch(0), 30)):
+    for name, make, steps in (("vid_7b_batch8", lambda: gen.make_batch("vid_7b", 0), 30),
+                              ("varlen16", lambda: gen.make_varlen_batch(0), 30)):
+        if only is not None and name != only:
+            continue
+        steps = steps_override or steps
+        samples = make()
         cu = [0]
         for sm in samples:
             cu.append(cu[-1] + sm.n)
@@ -161,6 +169,9 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel once over this many MiB "
                          "(a dispatch of known HBM traffic for rocprofv3 --pmc runs)")
+    ap.add_argument("--only-config", choices=["img_0p5b", "vid_long", "vid_7b_batch8", "varlen16"], default=None,
+                    help="run --steps calls of that workload shape alone and print its record (a profiler run of "
+                         "one shape; the benchmark line is not printed)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (samples are independent and "
@@ -176,6 +187,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     P.load_library()
+
+    if args.only_config:
+        rec = other_configs(P, gen, torch, np, only=args.only_config, steps_override=args.steps)
+        print(json.dumps({"workload": args.only_config, **rec[args.only_config]}))
+        return
 
     cfg = gen.CONFIGS["img_7b"]
     s = gen.make_sample(cfg, args.seed)
