@@ -660,7 +660,7 @@ struct NearArgs {
     int32_t* cluster_id; int32_t* cluster_counts;
     // assignment of kept tokens (Alg. 2 last loop); assign_blocks == 0: not in this launch
     const int32_t* idx; const uint64_t* cmask; const uint32_t* status; const int32_t* cnum; int assign_blocks;
-    // recovery of pruned tokens (Eq. 8/9): the blocks after the assignment ones
+    // recovery of pruned tokens (Eq. 8/9): the blocks before the assignment ones
     const int32_t* pruned_idx; const int32_t* center_idx; const float* cbest;
 };
 
@@ -917,8 +917,10 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
     }
 }
 
-// grid (assign_blocks + recovery blocks, B), block 256: the assignment blocks first (their
-// wavefronts live longest).
+// grid (recovery blocks + assign_blocks, B), block 256: the recovery blocks first - their chain of
+// dependent accesses is the longest, and behind the assignment blocks (two turns of what the
+// chip holds, the last ones idle: their number is sized by n, not by the kept tokens) they
+// started 3 us late.
 // PART: NEAREST_BOTH, or a build that holds one of the two searches only (the assignment alone
 // needs fewer registers and runs four wavefronts per SIMD instead of three).
 enum { NEAREST_BOTH = 0, NEAREST_ASSIGN = 1, NEAREST_RECOVER = 2 };
@@ -933,8 +935,9 @@ __global__ __launch_bounds__(256) void nearest_centre_kernel(Batch bt, NearArgs 
     lds_f32* ccos = (lds_f32*)s_ccos[wave];
     if constexpr (PART == NEAREST_ASSIGN) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
     else if constexpr (PART == NEAREST_RECOVER) recover_body<DT>(bt, a, blockIdx.x, gridDim.x, (lds_i32*)s_list);
-    else if ((int)blockIdx.x < a.assign_blocks) assign_body<DT>(bt, a, blockIdx.x, cand, ctok, ccos);
-    else recover_body<DT>(bt, a, blockIdx.x - a.assign_blocks, gridDim.x - a.assign_blocks, (lds_i32*)s_list);
+    else if ((int)blockIdx.x >= (int)gridDim.x - a.assign_blocks)
+        assign_body<DT>(bt, a, blockIdx.x - (gridDim.x - a.assign_blocks), cand, ctok, ccos);
+    else recover_body<DT>(bt, a, blockIdx.x, gridDim.x - a.assign_blocks, (lds_i32*)s_list);
 }
 
 template <int PART>
