@@ -113,7 +113,7 @@ typedef struct {
     int32_t zero_norm_seen;    /* kept or pruned tokens with a zero-norm clustering key */
     float   max_key_distance;  /* largest Eq. 5 distance between two clustered keys, from the fp32 pass
                                 * (the statistic Sec. "Selecting the layer L" looks at)  (dbdpc_cluster) */
-    int32_t reserved[5];
+    int32_t reserved[5];       /* library use (reserved[0]: clusters the merge takes first) */
 } pact_report;
 
 /* Scratch bytes needed for one call on samples of at most n_max tokens each, `batch`

@@ -50,7 +50,7 @@ struct WsLayout {
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
     size_t ksplit;                                     // [total][3][dk rounded up to 8] bf16: fp32 clustering keys as three bf16 parts
     size_t near_list, near_cnt, stat;                  // refine list, counter; [B][workgroups * 8] most negative density exponent seen
-    size_t offsets, members;                           // merge CSR (global row index)
+    size_t offsets, members, big;                      // merge CSR (global row index); ids of the large clusters
     size_t zeros;                                      // 256 zero bytes
     size_t total;
 };
@@ -87,6 +87,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.stat = take(sizeof(uint32_t) * B * GRAM_MAX_WORKGROUPS * 8);   // one word per wavefront of the density pass
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
+    L.big = take(sizeof(int32_t) * total);
     L.zeros = take(256);
     L.ksplit = take(sizeof(uint16_t) * 3 * total * ((dk + 7) / 8 * 8));   // planes padded to whole 16-byte chunks
     L.total = off;
@@ -99,7 +100,7 @@ struct Ws {
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; float* cbest; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
-    int32_t* offsets; int32_t* members; uint32_t* zeros; uint16_t* ksplit;
+    int32_t* offsets; int32_t* members; int32_t* big; uint32_t* zeros; uint16_t* ksplit;
 };
 
 inline Ws resolve(void* base, const WsLayout& L) {
@@ -115,7 +116,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.preds = (uint16_t*)(p + L.preds); w.heads = (uint2*)(p + L.heads);
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
     w.near_cnt = (int32_t*)(p + L.near_cnt); w.stat = (uint32_t*)(p + L.stat);
-    w.offsets = (int32_t*)(p + L.offsets);
+    w.offsets = (int32_t*)(p + L.offsets); w.big = (int32_t*)(p + L.big);
     w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
     w.ksplit = (uint16_t*)(p + L.ksplit);
     return w;

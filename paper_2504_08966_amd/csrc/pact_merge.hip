@@ -7,6 +7,11 @@
 
 namespace pact {
 
+// Clusters of at least this many rows are merged first (a cluster of 30 rows takes several times
+// as long as one of 2, and started in the last turn it alone would be the end of the kernel);
+// the others follow in cluster order, i.e. in token order, which their reads profit from.
+constexpr int MERGE_BIG = 12;
+
 // Member lists (CSR) of all clusters of a sample, by one workgroup: cluster sizes (taken from
 // cluster_counts, or recounted from cluster_id for a stand-alone merge), their exclusive scan,
 // and the fill with LDS cursors.  grid (B), block 1024, dynamic LDS n_max * 4 bytes.
@@ -15,9 +20,10 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
                                                          pact_report* rep,
                                                          int32_t* cluster_counts, int recount,
                                                          int write_totals, int32_t* offsets,
-                                                         int32_t* members) {
+                                                         int32_t* members, int32_t* big) {
     extern __shared__ int s_cur[];          // [C]: sizes, then running fill cursors
     __shared__ int s_wtot[16];
+    __shared__ int s_nbig;
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -60,6 +66,7 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
             if (tid + 1024 * k < C) s_cur[tid + 1024 * k] = cnt_pre[k];
         for (int c = tid + 4096; c < C; c += 1024) s_cur[c] = cnt[c];
     }
+    if (tid == 0) s_nbig = 0;
     __syncthreads();
     const int chunk = (C + 1023) / 1024;
     const int c0 = min(C, tid * chunk), c1 = min(C, c0 + chunk);
@@ -72,7 +79,21 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
         if (lane >= d) inc += v;
     }
     if (lane == 63) s_wtot[wave] = inc;
+    // the large clusters (sizes are still in s_cur), appended a wavefront at a time
+    int32_t* bigl = big + sg.base;
+    for (int cb = 0; cb < C; cb += 1024) {                   // (wave-uniform trip count)
+        const int c = cb + tid;
+        const bool isbig = c < C && s_cur[c] >= MERGE_BIG;
+        const uint64_t m = __ballot(isbig);
+        if (m) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_nbig, __popcll(m));
+            base = __shfl(base, 0, 64);
+            if (isbig) bigl[base + __popcll(m & ((1ull << lane) - 1ull))] = c;
+        }
+    }
     __syncthreads();
+    if (tid == 0) rep[b].reserved[0] = s_nbig;               // read by the merge together with the cluster count
     int run = inc - loc;
     for (int w = 0; w < wave; ++w) run += s_wtot[w];
     for (int c = c0; c < c1; ++c) {
@@ -134,6 +155,7 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
                                                      const int32_t* __restrict__ cluster_counts,
                                                      const int32_t* __restrict__ offsets,
                                                      const int32_t* __restrict__ members,
+                                                     const int32_t* __restrict__ big,
                                                      char* __restrict__ merged) {
     __shared__ int s_raw[MERGE_LDS_MEMBERS];
     __shared__ int s_sorted[MERGE_LDS_MEMBERS];
@@ -142,12 +164,16 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
     const Seg sg = bt.s[b];
     const int tid = threadIdx.x;
     const int C = clamp_count(rep[b].n_centers, sg.n);
+    const int nbig = clamp_count(rep[b].reserved[0], C);      // (same cache line as the cluster count)
     const size_t hrow = (size_t)h * Elem<HDT>::BYTES;
     const char* hb = hidden + (size_t)sg.base * hrow;
     const bool no_merge = (sg.flags & PACT_FLAG_NO_MERGE) != 0;
 
-    for (int c = blockIdx.x; c < C; c += gridDim.x) {
+    // work items 0 .. nbig-1: the large clusters; then all clusters in order, the large ones skipped
+    for (int k = blockIdx.x; k < nbig + C; k += gridDim.x) {
+        const int c = (k < nbig) ? big[sg.base + k] : k - nbig;
         int m = cluster_counts[sg.base + c];
+        if (k >= nbig && m >= MERGE_BIG) continue;                 // (uniform over the workgroup)
         bool in_lds = true;
         __syncthreads();                       // previous cluster's readers are done with the LDS lists
         if (no_merge) {
@@ -219,10 +245,10 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
     dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
     if (out_dt == PACT_BF16)
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged);
     else
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, (char*)merged);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged);
     return PACT_OK;
 }
 
@@ -266,7 +292,7 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
     }
     PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id,
                       const_cast<pact_report*>(rep), cluster_counts, recount ? 1 : 0, recount ? 0 : 1,
-                      w.offsets, w.members);
+                      w.offsets, w.members, w.big);
     if (h_dt == PACT_BF16)
         return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
                                          cluster_counts, st);
