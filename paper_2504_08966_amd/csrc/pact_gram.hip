@@ -289,11 +289,18 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
 
         int tr = tl % tilesR, tc = tl / tilesR;
         if (sym) {
-            // upper triangle, column by column: tile tl is (tr, tc) with tr <= tc, tl = tc (tc + 1) / 2 + tr
-            tc = (int)((sqrtf(8.0f * (float)tl + 1.0f) - 1.0f) * 0.5f);
-            while ((tc + 1) * (tc + 2) / 2 <= tl) ++tc;
-            while (tc * (tc + 1) / 2 > tl) --tc;
-            tr = tl - tc * (tc + 1) / 2;
+            // the tiles above the diagonal, column by column: tile tl is (tr, tc) with tr < tc,
+            // tl = tc (tc - 1) / 2 + tr; then the tiles on the diagonal, whose epilogue is the
+            // shorter one (the last turn of a workgroup's tile loop is then a short one)
+            const int nOff = tilesR * (tilesR - 1) / 2;
+            if (tl < nOff) {
+                tc = (int)((sqrtf(8.0f * (float)tl + 1.0f) + 1.0f) * 0.5f);
+                while ((tc + 1) * tc / 2 <= tl) ++tc;
+                while (tc * (tc - 1) / 2 > tl) --tc;
+                tr = tl - tc * (tc - 1) / 2;
+            } else {
+                tr = tc = tl - nOff;
+            }
         }
         const int rowBase = tr * TILE_R;
         const int colBase = tc * TILE_C;
