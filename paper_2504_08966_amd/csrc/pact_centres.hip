@@ -148,7 +148,8 @@ __device__ __forceinline__ void nearest_candidate(lds_i32* cand, lds_i32* ctok, 
 //   the other blocks: Eq. 6 completed, rho_p = sum over the row blocks of the column
 //       partials (64 tokens x 4 slices per block).  With d_n = 2 every term is an fp32 value
 //       in [e^-1, 1], so these fp64 additions are exact whatever their order.
-constexpr int REFINE_BLOCKS = 256;
+constexpr int REFINE_BLOCKS = 768;     // 3072 wavefronts: one pair each on the benchmark image (2 200 pairs), so that no
+                                       // wavefront evaluates two or three rows one after the other (256: 1.2 us longer)
 
 template <int DT>
 __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __restrict__ keys, int dk,
