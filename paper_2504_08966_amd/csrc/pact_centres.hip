@@ -317,6 +317,7 @@ struct BitPop {
 // workgroup - then has 8 bytes per token to fetch instead of 32.
 // One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
 constexpr int HEAD_PREDS = 3;
+constexpr int PREDS_SPREAD = 256;      // set bits of 64 row words that are spread over the lanes through LDS
 __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
                                                           const uint64_t* __restrict__ adj,
                                                           const double* __restrict__ rho,
@@ -334,19 +335,57 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
     uint16_t* head = (uint16_t*)(heads + (size_t)b * bt.n_max + p);
     const int Wq = (q + 63) >> 6;
     int total = 0;
+    // A token's neighbours are mostly close to it in the sequence, i.e. their bits sit in one or
+    // two words of the row: lane by lane, a word's bits would be looked up one after the other,
+    // each look-up (the neighbour's density) a trip to memory.  So the set bits of 64 words are
+    // first spread over the lanes - the k-th set bit to lane k, through a small LDS list - and
+    // the densities of up to 64 neighbours are fetched in one trip.
+    __shared__ uint16_t s_nb[4][PREDS_SPREAD];
+    volatile uint16_t* nb = s_nb[threadIdx.x >> 6];
     for (int w0 = 0; w0 < Wq; w0 += 64) {
         const int w = w0 + lane;
-        BitPop bp{(w < Wq) ? row[w] : 0ull};
-        while (bp.any()) {
-            int bit;
-            const bool has = bp.pop(bit);
-            const int j = (w << 6) + bit;
-            const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
-            const uint64_t m = __ballot(pre);
-            const int slot = total + lanes_below(m, lane);
-            if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
-            if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
-            total += __popcll(m);
+        uint64_t word = (w < Wq) ? row[w] : 0ull;
+        const int cnt = __popcll(word);
+        int inc = cnt;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += t;
+        }
+        const int nbits = __shfl(inc, 63, 64);
+        if (nbits <= PREDS_SPREAD) {
+            int at = inc - cnt;
+            while (word) {                                   // (no memory access in this loop)
+                nb[at++] = (uint16_t)((w << 6) + __builtin_ctzll(word));
+                word &= word - 1;
+            }
+            __builtin_amdgcn_wave_barrier();
+            for (int k0 = 0; k0 < nbits; k0 += 64) {        // (wave-uniform trip count)
+                const int k = k0 + lane;
+                const bool has = k < nbits;
+                const int j = has ? nb[k] : p;
+                const bool pre = has && j < q && precedes(r[j], j, rp, p);
+                const uint64_t m = __ballot(pre);
+                const int slot = total + lanes_below(m, lane);
+                if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
+                if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
+                total += __popcll(m);
+            }
+            __builtin_amdgcn_wave_barrier();                 // the list is rewritten for the next 64 words
+        } else {
+            // a very dense row: word by word, one bit per lane and turn
+            BitPop bp{word};
+            while (bp.any()) {
+                int bit;
+                const bool has = bp.pop(bit);
+                const int j = (w << 6) + bit;
+                const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
+                const uint64_t m = __ballot(pre);
+                const int slot = total + lanes_below(m, lane);
+                if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
+                if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
+                total += __popcll(m);
+            }
         }
     }
     if (lane == 0) {
