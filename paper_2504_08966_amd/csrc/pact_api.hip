@@ -104,8 +104,7 @@ static int run_reduce(const Batch& bt, const Ws& w, const ReduceIO& io, hipStrea
                io.q_per_token, io.n_q};
     if ((rc = launch_score(bt, w, si, st))) return rc;
     if ((rc = launch_score_only(bt, w, io.n_q, io.scores, st))) return rc;
-    if ((rc = launch_score_prune(bt, w, io.n_q, true, io.scores, io.kept_idx, io.pruned_idx, io.rep, st)))
-        return rc;
+    if ((rc = launch_score_prune(bt, io.scores, w.adj, io.kept_idx, io.pruned_idx, io.rep, st))) return rc;
     bool want_stat = false;                  // the key-distance statistic: only if a sample asks for it
     for (int b = 0; b < bt.B; ++b) want_stat = want_stat || (bt.s[b].flags & PACT_FLAG_KEY_STATS);
     int stat_words = 0;
@@ -185,10 +184,7 @@ int pact_prune(const float* scores, int32_t n, float lambda,
     p.lambda = lambda;
     Batch bt;
     fill_single(bt, n, p);
-    Ws none;
-    std::memset(&none, 0, sizeof(none));
-    return launch_score_prune(bt, none, 1, true, const_cast<float*>(scores), kept_idx, pruned_idx, rep,
-                              (hipStream_t)stream);
+    return launch_score_prune(bt, scores, nullptr, kept_idx, pruned_idx, rep, (hipStream_t)stream);
 }
 
 int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,

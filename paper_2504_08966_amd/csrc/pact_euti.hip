@@ -14,7 +14,7 @@ namespace pact {
 //   blocks [0, nQ = QG_CHUNKS or 0)   : Eq. 1 pass 1, column sums of one row chunk of Q.
 // grid (nKeyBlocks + (do_q ? QG_CHUNKS : 0), B), block 256.
 struct PrepArgs {
-    const char* keys; int32_t dk; int32_t key_dt_unused;
+    const char* keys; int32_t dk;
     const char* q; int32_t qcols;            // q == nullptr: no query pass
     double* nn; float* rinv; uint64_t* adj; double* qg_part;
     uint32_t* status; int32_t* ident; int32_t* near_cnt;
@@ -80,8 +80,12 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
                         make_uint2(part[pl][0] | (part[pl][1] << 16), part[pl][2] | (part[pl][3] << 16));
             }
         }
+        // The bitmap is used over (kept tokens) x (kept tokens).  In a full reduction that is
+        // n - m rows and columns unless scores tie at the threshold (Eq. 3 / 4); the split
+        // clears the rest itself in that case.
         uint64_t* arow = a.adj + ((size_t)b * bt.n_max + i) * bt.W;
-        const int Wn = (sg.n + 63) >> 6;
+        const int side = (a.mode == INIT_REDUCE) ? sg.n - prune_rank(sg.lambda, sg.n) : sg.n;
+        const int Wn = (i < side) ? (side + 63) >> 6 : 0;
         for (int k = lane; k < Wn; k += 64) arow[k] = 0ull;
         if (lane == 0) {
             a.nn[g] = v;
@@ -366,8 +370,7 @@ __device__ __forceinline__ void combine_softmax_partials(const double* part, int
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 2, pass 2 on its own (stand-alone pact_score): combine the partials into (max,
-// normaliser) per head, then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
+// Eq. 2, pass 2: combine the partials into (max, normaliser) per head, then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
 // grid (ceil(n_max/256), B), block 256.
 __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
                                                           const double* __restrict__ logits,
@@ -411,28 +414,24 @@ __global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 2 pass 2 + Eq. 3/4, one workgroup of 1024 per sample:
-//   (a) combine the softmax partials into (max, normaliser) per head;
-//   (b) s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j, rounded to fp32, written out and
-//       kept in LDS as order-preserving integer keys;          [skipped when scores are given]
-//   (c) exact radix select of the (m+1)-th smallest key, m = min(floor(lambda n), n-1);
-//   (d) ordered compaction into the kept / pruned index lists.
+// Eq. 3/4, one workgroup of 1024 per sample, on the finished fp32 scores:
+//   (a) the scores become order-preserving integer keys in LDS;
+//   (b) exact radix select of the (m+1)-th smallest key, m = min(floor(lambda n), n-1);
+//   (c) ordered compaction into the kept / pruned index lists.
+// (Finishing the scores here as well - one launch fewer - was slower: one compute unit then
+// evaluates all n * n_q fp64 exponentials.)
 // Dynamic LDS: n_max * 4 bytes.
 __device__ __forceinline__ uint32_t ordered_key(float f) {
     const uint32_t u = __float_as_uint(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, int have_scores,
-                                                           const double* __restrict__ logits,
-                                                           const double* __restrict__ hnorm,
-                                                           const double* __restrict__ sm_part,
-                                                           float* scores,
+__global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float* __restrict__ scores,
+                                                           uint64_t* __restrict__ adj,
                                                            int32_t* __restrict__ kept_idx,
                                                            int32_t* __restrict__ pruned_idx,
                                                            pact_report* __restrict__ rep) {
     extern __shared__ uint32_t s_key[];
-    __shared__ double s_M[PACT_MAX_QHEADS], s_Z[PACT_MAX_QHEADS];
     __shared__ int s_hist[256 * 16];
     __shared__ int s_bin[256];
     __shared__ int s_sel[2][2];
@@ -443,35 +442,13 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    float* s = scores + sg.base;
+    const float* s = scores + sg.base;
 
-    if (!have_scores) {
-        const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
-        const int nwg = (n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
-        for (int j = wave; j < n_q; j += 16) {
-            double m, z;
-            combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
-            if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
-        }
-        __syncthreads();
-        for (int i = tid; i < n; i += 1024) {
-            const size_t g = (size_t)sg.base + i;
-            double p = 1.0 / (double)n;
-            if (!(sg.flags & PACT_FLAG_SCORE_NORM_ONLY)) {
-                double acc = 0.0;
-                for (int j = 0; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
-                p = acc / (double)n_q;
-            }
-            const float v = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hnorm[g] * p);
-            s[i] = v;
-            s_key[i] = ordered_key(v);
-        }
-    }
     // this thread's first keys stay in registers for the select (its passes then issue their
     // histogram updates back to back instead of waiting for an LDS read before each)
     constexpr int KREG = 8;
     uint32_t kreg[KREG];
-    if (have_scores) {
+    {
         float sv[KREG];
 #pragma unroll
         for (int u = 0; u < KREG; ++u) sv[u] = (tid + 1024 * u < n) ? s[tid + 1024 * u] : 0.0f;   // all in flight
@@ -482,15 +459,10 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
         }
         for (int i = tid + 1024 * KREG; i < n; i += 1024) s_key[i] = ordered_key(s[i]);
         __syncthreads();
-    } else {
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < KREG; ++u) kreg[u] = (tid + 1024 * u < n) ? s_key[tid + 1024 * u] : 0u;
     }
 
-    int k = (int)floor((double)sg.lambda * (double)n);
-    if (k > n - 1) k = n - 1;
-    if (k < 0) k = 0;
+    const int m_rank = prune_rank(sg.lambda, n);
+    int k = m_rank;
     // Radix select, 8 bits per pass from the top.  Scores of one image share their leading bits,
     // so a plain histogram would serialise thousands of atomics on a handful of LDS words: every
     // bin has 16 copies (one per lane & 15, in 16 different banks), summed after the pass.
@@ -578,6 +550,14 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, int n_q, in
         rep[b].n_kept = total;
         rep[b].n_pruned = n - total;
     }
+    // Scores tied at the threshold: more tokens are kept than the n - m whose bitmap rows and
+    // words were cleared along with the key norms; clear what the clustering will use.
+    if (adj && total > n - m_rank) {
+        uint64_t* rows = adj + (size_t)b * bt.n_max * bt.W;
+        const int Wq = (total + 63) >> 6;
+        for (int r = wave; r < total; r += 16)
+            for (int w = lane; w < Wq; w += 64) rows[(size_t)r * bt.W + w] = 0ull;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -598,7 +578,7 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
                 const void* q, pact_dtype q_dt, int32_t qcols, pact_report* rep, int32_t* cluster_id,
                 int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st) {
     PrepArgs a;
-    a.keys = (const char*)keys; a.dk = dk; a.key_dt_unused = 0;
+    a.keys = (const char*)keys; a.dk = dk;
     a.q = (const char*)q; a.qcols = qcols;
     a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
     a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt;
@@ -667,17 +647,19 @@ int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipS
     return PACT_OK;
 }
 
-// Finishes the scores (unless have_scores) and splits them.
-int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, float* scores,
-                       int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep, hipStream_t st) {
+// Splits the finished scores of every sample (Eq. 3 / 4).
+// adj: the samples' neighbour bitmaps as launch_prep(INIT_REDUCE) left them, or nullptr when no
+// clustering follows.
+int launch_score_prune(const Batch& bt, const float* scores, uint64_t* adj, int32_t* kept_idx,
+                       int32_t* pruned_idx, pact_report* rep, hipStream_t st) {
     const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(uint32_t);
     static size_t raised = 0;
     if (lds > 48 * 1024 && lds > raised) {
         if (raise_lds_limit((const void*)score_prune_kernel, lds) != hipSuccess) return PACT_ERR_HIP;
         raised = lds;
     }
-    PACT_LAUNCH_SHMEM("score_prune", score_prune_kernel, dim3(bt.B), dim3(1024), lds, st, bt, n_q,
-                      have_scores ? 1 : 0, w.logits, w.hnorm, w.sm_part, scores, kept_idx, pruned_idx, rep);
+    PACT_LAUNCH_SHMEM("score_prune", score_prune_kernel, dim3(bt.B), dim3(1024), lds, st, bt, scores, adj,
+                      kept_idx, pruned_idx, rep);
     return PACT_OK;
 }
 

@@ -158,8 +158,8 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
                 int32_t* cluster_counts, int mode, const int32_t* n_idx_dev, hipStream_t st);
 int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st);
 int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st);
-int launch_score_prune(const Batch& bt, const Ws& w, int n_q, bool have_scores, float* scores,
-                       int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep, hipStream_t st);
+int launch_score_prune(const Batch& bt, const float* scores, uint64_t* adj, int32_t* kept_idx,
+                       int32_t* pruned_idx, pact_report* rep, hipStream_t st);
 // want_stat: also record the largest key distance; *stat_words = words per sample the kernel
 // wrote to w.stat (0 if not wanted), to be handed to launch_centres.
 int launch_gram_density(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt, int32_t dk,
@@ -184,6 +184,14 @@ int launch_handoff(const Batch& bt, const int32_t* center_idx, const int32_t* cl
                    float* log_weight, hipStream_t st);
 
 // init modes
+// m of Eq. 3 / 4: the threshold is the (m+1)-th smallest score, m = min(floor(lambda n), n-1);
+// the m tokens below it are pruned, all of them when no other score equals the threshold.
+__host__ __device__ inline int prune_rank(float lambda, int n) {
+    int m = (int)floor((double)lambda * (double)n);
+    if (m > n - 1) m = n - 1;
+    return m < 0 ? 0 : m;
+}
+
 enum { INIT_REDUCE = 0, INIT_DBDPC_ALL = 1, INIT_DBDPC_SUBSET = 2, INIT_REINC = 3, INIT_SCORE = 4 };
 
 // Worst-case rounding error of an fp32-accumulated matrix-core cosine of two dk-long rows, plus

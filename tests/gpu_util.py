@@ -64,11 +64,11 @@ def trim(o, n, base=0, b=0):
 
 
 def gpu_reduce(s: gen.Sample, d_c, d_n=2.0, alpha=1.5, lam=None, out_dtype=torch.float32, flags=0,
-               fallback_T=10):
+               fallback_T=10, ws=None):
     cfg = s.config
     d = sample_to_dev(s)
     prm = P.PactParams(s.lam if lam is None else lam, d_c, d_n, alpha, fallback_T, flags)
     o = P.pact_reduce(d["hidden"], d["keys"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, cfg.n_kv, prm,
-                      out_dtype=out_dtype)
+                      out_dtype=out_dtype, ws=ws)
     torch.cuda.synchronize()
     return trim(o, s.n)

@@ -385,6 +385,33 @@ def test_many_equal_scores_around_the_percentile():
         assert_same(g, o, s, f"equal scores lam={lam}")
 
 
+def test_ties_at_the_threshold_in_a_workspace_that_holds_an_earlier_dense_bitmap():
+    # With scores tied at the threshold more tokens are kept than n - m, so the neighbour bitmap
+    # needs more rows and words than are cleared ahead of the split.  The workspace is reused:
+    # an earlier call (nothing pruned, a cutoff that joins every pair) leaves every bit set.
+    r = np.random.default_rng(14)
+    n = 1500
+    k = r.normal(size=(n, 2, 16)).astype(np.float32)
+    levels = np.array([1.0, 1.0 + 2.0 ** -12, 1.0 + 2.0 ** -11], dtype=np.float32)
+    h = r.normal(size=(1, 32)).astype(np.float32) * levels[r.integers(0, 3, n)][:, None]
+    s = _mk(k, hidden=h, queries=np.zeros_like(k))            # uniform softmax: score = norm / n
+    cfg = s.config
+    ws = P.alloc_workspace(n, 1, cfg.n_kv * cfg.d_h, cfg.n_kv, cfg.d_h)
+    g = gu.gpu_reduce(s, 1.99, lam=0.0, ws=ws)
+    assert g["rep"]["n_kept"] == n and g["rep"]["n_centers"] == 1
+    for lam, d_c in ((0.2, 0.8), (0.5, 0.9), (0.9, 0.8), (0.5, 1.99)):
+        g = gu.gpu_reduce(s, d_c, lam=lam, ws=ws)
+        o = oracle_reduce(s, d_c, lam=lam)
+        assert g["rep"]["n_kept"] > n - int(np.floor(lam * n))
+        assert_same(g, o, s, f"ties, reused workspace lam={lam} d_c={d_c}")
+    # and without ties in the same workspace, after the dense bitmap again
+    gu.gpu_reduce(s, 1.99, lam=0.0, ws=ws)
+    s2 = _random_sample(15, n, 2, 2, 16, 32, 0.4, "f32")
+    g = gu.gpu_reduce(s2, 0.9, ws=ws)
+    o = oracle_reduce(s2, 0.9)
+    assert_same(g, o, s2, "reused workspace, no ties")
+
+
 # ------------------------------------------------------------------ targeted cases
 
 def test_nearest_centre_may_come_later_in_the_density_order():
