@@ -106,15 +106,21 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     const int r1 = min(sg.n, r0 + rows_per);
     const size_t row_bytes = (size_t)a.qcols * Elem<QDT>::BYTES;
     double* out = a.qg_part + ((size_t)b * QG_CHUNKS + chunk) * a.qcols;
-    for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
-        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    // Four columns per thread.  Rows of at most 512 (256) columns leave half (three quarters) of
+    // the threads without columns: they take every second (fourth) row of the chunk instead, and
+    // the row groups' sums meet in LDS.
+    const int RG = a.qcols <= 256 ? 4 : a.qcols <= 512 ? 2 : 1;
+    const int tpg = 256 / RG;
+    const int rg = threadIdx.x / tpg, ct = threadIdx.x % tpg;
+    __shared__ double s_part[192 * 4];
+    auto sum_rows = [&](int c, double (&acc)[4]) __attribute__((always_inline)) {
         const char* base = a.q + (size_t)sg.base * row_bytes + (size_t)c * Elem<QDT>::BYTES;
-        for (int r = r0; r < r1; r += 8) {
+        for (int r = r0 + rg; r < r1; r += 8 * RG) {
             float f[8][4];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const bool ok = r + u < r1;
-                const char* p = base + (size_t)(ok ? r + u : r0) * row_bytes;
+                const bool ok = r + u * RG < r1;
+                const char* p = base + (size_t)(ok ? r + u * RG : r0) * row_bytes;
                 if (QDT == PACT_BF16) {
                     const uint2 v = *(const uint2*)p;
                     f[u][0] = __uint_as_float(v.x << 16); f[u][1] = __uint_as_float(v.x & 0xFFFF0000u);
@@ -130,6 +136,29 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[i] += (double)f[u][i];
         }
+    };
+    if (RG == 1) {
+        for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            sum_rows(c, acc);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) out[c + i] = acc[i];
+        }
+        return;
+    }
+    const int c = ct * 4;
+    const bool act = c < a.qcols;
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    if (act) sum_rows(c, acc);
+    if (act && rg > 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s_part[((rg - 1) * tpg + ct) * 4 + i] = acc[i];
+    }
+    __syncthreads();
+    if (act && rg == 0) {
+        for (int g = 1; g < RG; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[i] += s_part[((g - 1) * tpg + ct) * 4 + i];
 #pragma unroll
         for (int i = 0; i < 4; ++i) out[c + i] = acc[i];
     }

@@ -813,7 +813,10 @@ def test_key_distance_statistic_in_a_ragged_batch():
 def test_random_shapes_dtypes_and_batches(seed):
     # 20 random calls per seed: 1 to 16 samples of 1 to ~1800 tokens (a few single samples beyond
     # 4096 kept tokens), both dtypes, key widths with ragged slices, all lambda / alpha corners
+    # One workspace serves all calls (it grows when a call needs more), so every call finds the
+    # previous calls' contents laid out for other shapes.
     rng = np.random.default_rng(seed)
+    ws = None
     for case in range(20):
         dtype = str(rng.choice(["f32", "bf16"]))
         n_kv, d_h = int(rng.choice([1, 2, 4])), int(rng.choice([8, 16, 32, 40, 64, 128]))
@@ -834,10 +837,13 @@ def test_random_shapes_dtypes_and_batches(seed):
         ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), dtype)
         qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), dtype)
         prms = [P.PactParams(sm.lam, d, 2.0, alpha) for sm, d in zip(samples, dcs)]
+        need = P.pact_workspace_bytes(max(sizes), B, n_kv * d_h, n_kv, d_h)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(2 * need, dtype=torch.uint8, device="cuda")
         if B == 1:
-            o = P.pact_reduce(hid, ks, ks, qs, n_kv, d_h, n_kv, prms[0])
+            o = P.pact_reduce(hid, ks, ks, qs, n_kv, d_h, n_kv, prms[0], ws=ws)
         else:
-            o = P.pact_reduce_varlen(hid, ks, ks, qs, n_kv, d_h, n_kv, cu, prms)
+            o = P.pact_reduce_varlen(hid, ks, ks, qs, n_kv, d_h, n_kv, cu, prms, ws=ws)
         torch.cuda.synchronize()
         for b, sm in enumerate(samples):
             assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b], alpha=alpha), sm,
