@@ -42,8 +42,8 @@ def algorithmic_work(kernel: str, n, h, dk, q, C, n_reinc, key_bytes, hid_bytes,
         return "hbm", n * n_q * d_h * key_bytes, "B"
     if kernel == "merge_mean":            # read member rows once, write C merged rows
         return "hbm", (q + n_reinc) * h * hid_bytes + C * h * out_bytes, "B"
-    if kernel == "key_prep":
-        return "hbm", n * dk * key_bytes + n * ((n + 63) // 64) * 8, "B"
+    if kernel == "key_prep":              # read the keys, clear the bitmap of the kept tokens
+        return "hbm", n * dk * key_bytes + q * ((q + 63) // 64) * 8, "B"
     return None, 0.0, ""
 
 
@@ -328,7 +328,7 @@ def main():
         kk = "key_prep" if k == "prep" else k
         bound, work, unit = algorithmic_work(kk, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
         if k == "prep":
-            work = n * dk * 2 * 2 + n * ((n + 63) // 64) * 8     # keys + queries read, bitmap rows cleared
+            work = n * dk * 2 * 2 + q_kept * ((q_kept + 63) // 64) * 8     # keys + queries read, kept x kept bitmap cleared
         if k not in per_launch:
             continue
         ent = {"bytes_algorithmic": work, "traffic_measured": measured_traffic(k)}
