@@ -660,6 +660,17 @@ def test_density_pass_with_mirrored_tiles_single_sample(n, lam, dtype):
     assert_same(g, oracle_reduce(s, d_c), s, f"mirrored tiles n={n} {dtype}")
 
 
+@pytest.mark.parametrize("n,lam,dtype", [(4000, 0.0, "bf16"), (5000, 0.2, "f32")])
+def test_density_pass_with_one_tile_per_workgroup(n, lam, dtype):
+    # 3841 to 4096 kept tokens: 16 x 16 full tiles (no mirroring), one per workgroup, each
+    # XCD's band two whole tile columns; the last tile row and column are ragged
+    s = _random_sample(60 + n, n, 2, 2, 32, 64, lam, dtype)
+    d_c = _gap_dc(s.keys.reshape(n, -1), frac=0.002)
+    g = gu.gpu_reduce(s, d_c)
+    assert 3840 < g["rep"]["n_kept"] <= 4096 and g["rep"]["refine_overflow"] == 0
+    assert_same(g, oracle_reduce(s, d_c), s, f"16 x 16 tiles n={n} {dtype}")
+
+
 def test_mirrored_tiles_densities_and_key_statistic():
     # the stand-alone clustering call: densities, centres and the largest key distance
     n = 4400
