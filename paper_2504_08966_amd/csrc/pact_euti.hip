@@ -167,7 +167,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
 // |h_g|_2 in fp64 by one wavefront (8 independent 16-byte loads in flight per lane).
 template <int HDT>
 __device__ __forceinline__ void hnorm_row(const char* __restrict__ hidden, int h, size_t g, int lane,
-                                          double* __restrict__ hnorm) {
+                                          double* __restrict__ hnorm, bool stream) {
     const char* hp = hidden + g * (size_t)h * Elem<HDT>::BYTES;
     constexpr int HE = Elem<HDT>::EPL;
     double ss[4] = {0.0, 0.0, 0.0, 0.0};
@@ -176,7 +176,9 @@ __device__ __forceinline__ void hnorm_row(const char* __restrict__ hidden, int h
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int e = e0 + u * 64 * HE;
-            v[u] = (e < h) ? *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES) : make_uint4(0, 0, 0, 0);
+            v[u] = (e >= h) ? make_uint4(0, 0, 0, 0)
+                 : stream ? load_once16(hp + (size_t)e * Elem<HDT>::BYTES)
+                          : *(const uint4*)(hp + (size_t)e * Elem<HDT>::BYTES);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols
                                                              const char* __restrict__ q_given,
                                                              double* __restrict__ qg,
                                                              const char* __restrict__ hidden, int h,
-                                                             double* __restrict__ hnorm, int hshare) {
+                                                             double* __restrict__ hnorm, int hshare, int stream) {
     __shared__ double s_p[16][64];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols
     }
     const int i = (blockIdx.x - nq_blocks) * SCORE_TOK_PER_WG + (threadIdx.x >> 6);
     if (i >= hnorm_split(sg.n, hshare)) return;
-    hnorm_row<HDT>(hidden, h, (size_t)sg.base + i, threadIdx.x & 63, hnorm);
+    hnorm_row<HDT>(hidden, h, (size_t)sg.base + i, threadIdx.x & 63, hnorm, stream != 0);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
                                                             double* __restrict__ logits,
                                                             double* __restrict__ sm_part, int n_logit_blocks,
                                                             const char* __restrict__ hidden, int h,
-                                                            double* __restrict__ hnorm, int hshare) {
+                                                            double* __restrict__ hnorm, int hshare, int stream) {
     __shared__ double s_l[SCORE_TOK_PER_WG][PACT_MAX_QHEADS];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
@@ -272,7 +274,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
     if ((int)blockIdx.x >= n_logit_blocks) {
         // the rest of the hidden-state norms (independent of the logits; rides in this launch)
         const int i = hnorm_split(sg.n, hshare) + ((int)blockIdx.x - n_logit_blocks) * SCORE_TOK_PER_WG + wave;
-        if (i < sg.n) hnorm_row<HDT>(hidden, h, (size_t)sg.base + i, lane, hnorm);
+        if (i < sg.n) hnorm_row<HDT>(hidden, h, (size_t)sg.base + i, lane, hnorm, stream != 0);
         return;
     }
     const int t0 = blockIdx.x * SCORE_TOK_PER_WG;
@@ -630,15 +632,16 @@ static int launch_qglobal_hnorm(const Batch& bt, const Ws& w, const ScoreIn& in,
     const int qcols = in.n_q * in.d_h;
     const int nq_blocks = in.q_per_token ? (qcols + 63) / 64 : (qcols + 1023) / 1024;
     const int share = hnorm_share(bt);
+    const int stream = hidden_streams(bt.total, in.h, Elem<HDT>::BYTES) ? 1 : 0;
     dim3 grid(nq_blocks + (hnorm_split(bt.n_max, share) + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
     if (in.q_dt == PACT_BF16)
         PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_BF16>), grid, dim3(1024), st, bt, qcols,
                     in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
-                    in.h, w.hnorm, share);
+                    in.h, w.hnorm, share, stream);
     else
         PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_F32>), grid, dim3(1024), st, bt, qcols,
                     in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
-                    in.h, w.hnorm, share);
+                    in.h, w.hnorm, share, stream);
     return PACT_OK;
 }
 
@@ -646,17 +649,18 @@ template <int HDT>
 static int launch_logits_hnorm(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st) {
     const int n_logit_blocks = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     const int share = hnorm_share(bt);
+    const int stream = hidden_streams(bt.total, in.h, Elem<HDT>::BYTES) ? 1 : 0;
     // tokens past the split: n - split(n) <= n - floor(n * share / 256), which grows with n
     const int rest = bt.n_max - ((bt.n_max * share) >> 8);
     dim3 grid(n_logit_blocks + (rest + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
     if (in.k_dt == PACT_BF16)
         PACT_LAUNCH("score_logits", (score_logits_kernel<PACT_BF16, HDT>), grid, dim3(1024), st, bt,
                     (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part, n_logit_blocks,
-                    (const char*)in.hidden, in.h, w.hnorm, share);
+                    (const char*)in.hidden, in.h, w.hnorm, share, stream);
     else
         PACT_LAUNCH("score_logits", (score_logits_kernel<PACT_F32, HDT>), grid, dim3(1024), st, bt,
                     (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part, n_logit_blocks,
-                    (const char*)in.hidden, in.h, w.hnorm, share);
+                    (const char*)in.hidden, in.h, w.hnorm, share, stream);
     return PACT_OK;
 }
 

@@ -297,6 +297,23 @@ __device__ __forceinline__ double wave_dot64(const char* ra, const char* rb, int
     return wave_sum_f64(acc);
 }
 
+// 16 bytes that this launch touches once: loads and stores with the streaming hint.  Used when a
+// call's hidden states are larger than what the 256 MB last-level cache can keep between the norm
+// pass and the merge anyway; for smaller calls the hint costs those later hits (one 7290-token
+// image: +4 us per call with it, 8 videos of 6272 tokens: -30 us).
+inline bool hidden_streams(long total_tokens, int h, int elem_bytes) {
+    return (double)total_tokens * (double)h * (double)elem_bytes > 192.0 * 1024.0 * 1024.0;
+}
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_once16(const void* p) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_once16(void* p, uint4 w) {
+    const u32x4_t v = {w.x, w.y, w.z, w.w};
+    __builtin_nontemporal_store(v, (u32x4_t*)p);
+}
+
 // Eq. 5 in fp64 from a dot product and the two squared norms; zero vector -> cosine 0.
 __device__ __forceinline__ double cos_dist64(double dot, double nna, double nnb) {
     const double den = sqrt(nna * nnb);

@@ -128,21 +128,29 @@ constexpr int MERGE_LDS_MEMBERS = 1024;
 
 template <int ODT> struct StoreOut;
 template <> struct StoreOut<PACT_F32> {
-    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v) {
+    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v, bool stream) {
         float* o = (float*)out + e;
 #pragma unroll
-        for (int i = 0; i < N; i += 4) *(float4*)(o + i) = make_float4((float)v[i], (float)v[i + 1], (float)v[i + 2], (float)v[i + 3]);
+        for (int i = 0; i < N; i += 4) {
+            const float4 f = make_float4((float)v[i], (float)v[i + 1], (float)v[i + 2], (float)v[i + 3]);
+            if (stream) store_once16(o + i, make_uint4(__float_as_uint(f.x), __float_as_uint(f.y), __float_as_uint(f.z), __float_as_uint(f.w)));
+            else *(float4*)(o + i) = f;
+        }
     }
 };
 template <> struct StoreOut<PACT_BF16> {
-    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v) {
+    template <int N> __device__ static __forceinline__ void put(char* out, size_t e, const double* v, bool stream) {
         uint16_t* o = (uint16_t*)out + e;
         uint32_t w[N / 2];
 #pragma unroll
         for (int i = 0; i < N; i += 2)
             w[i / 2] = f32_to_bf16_rne((float)v[i]) | (f32_to_bf16_rne((float)v[i + 1]) << 16);
-        if (N == 8) *(uint4*)o = make_uint4(w[0], w[1], w[2], w[3]);
-        else *(uint2*)o = make_uint2(w[0], w[1]);
+        if (N == 8) {
+            if (stream) store_once16(o, make_uint4(w[0], w[1], w[2], w[3]));
+            else *(uint4*)o = make_uint4(w[0], w[1], w[2], w[3]);
+        } else {
+            *(uint2*)o = make_uint2(w[0], w[1]);
+        }
     }
 };
 
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
                                                      const int32_t* __restrict__ offsets,
                                                      const int32_t* __restrict__ members,
                                                      const int32_t* __restrict__ big,
-                                                     char* __restrict__ merged) {
+                                                     char* __restrict__ merged, int stream) {
     __shared__ int s_raw[MERGE_LDS_MEMBERS];
     __shared__ int s_sorted[MERGE_LDS_MEMBERS];
     constexpr int EPL = Elem<HDT>::EPL;
@@ -204,8 +212,9 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
                     uint4 v[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        v[u] = (k + u < m_eff) ? *(const uint4*)(hcol + (size_t)s_sorted[k + u] * hrow)
-                                               : make_uint4(0, 0, 0, 0);
+                        v[u] = (k + u >= m_eff) ? make_uint4(0, 0, 0, 0)
+                             : stream ? load_once16(hcol + (size_t)s_sorted[k + u] * hrow)   // (their last use in a call)
+                                      : *(const uint4*)(hcol + (size_t)s_sorted[k + u] * hrow);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         if (k + u < m_eff) {          // (skipping keeps -0.0 rows exact)
@@ -233,7 +242,7 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
 #pragma unroll
             for (int i = 0; i < EPL; ++i) outv[i] = (m_eff == 1) ? acc[i] : (m_eff == 0 ? 0.0 : acc[i] * inv_m);
             StoreOut<ODT>::template put<EPL>(merged + ((size_t)sg.base + c) * (size_t)h * (ODT == PACT_BF16 ? 2 : 4),
-                                             (size_t)e, outv);
+                                             (size_t)e, outv, stream != 0);
         }
     }
 }
@@ -243,12 +252,16 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
                           const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
                           void* merged, pact_dtype out_dt, const int32_t* cluster_counts, hipStream_t st) {
     dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
+    // (the member rows are read for the last time and the merged rows are not read again by this
+    //  library: both with the streaming hint when the hidden states alone exceed what the
+    //  last-level cache keeps)
+    const int stream = hidden_streams(bt.total, h, Elem<HDT>::BYTES) ? 1 : 0;
     if (out_dt == PACT_BF16)
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged, stream);
     else
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged, stream);
     return PACT_OK;
 }
 

@@ -799,6 +799,25 @@ def test_small_ragged_batches(sizes, dtype):
         assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b]), sm, f"sample {b} (n={sm.n})")
 
 
+def test_fp32_hidden_states_larger_than_the_last_level_cache():
+    # 15000 tokens x 3584 fp32 = 215 MB of hidden states: the norm pass reads them and the merge
+    # writes its rows with the streaming hint (as the full-size bf16 batches do)
+    sizes = [3750, 3600, 3900, 3750]
+    samples = [_random_sample(500 + b, n, 2, 2, 16, 3584, 0.4, "f32") for b, n in enumerate(sizes)]
+    cu = [0]
+    for sm in samples:
+        cu.append(cu[-1] + sm.n)
+    hid = gu.dev(np.concatenate([sm.hidden for sm in samples]), "f32")
+    ks = gu.dev(np.concatenate([sm.keys.reshape(sm.n, -1) for sm in samples]), "f32")
+    qs = gu.dev(np.concatenate([sm.queries.reshape(sm.n, -1) for sm in samples]), "f32")
+    dcs = [_gap_dc(sm.keys.reshape(sm.n, -1), frac=0.01, window=300) for sm in samples]
+    prms = [P.PactParams(sm.lam, d, 2.0, 1.5) for sm, d in zip(samples, dcs)]
+    o = P.pact_reduce_varlen(hid, ks, ks, qs, 2, 16, 2, cu, prms)
+    torch.cuda.synchronize()
+    for b, sm in enumerate(samples):
+        assert_same(gu.trim(o, sm.n, base=cu[b], b=b), oracle_reduce(sm, dcs[b]), sm, f"sample {b} (n={sm.n})")
+
+
 def test_key_distance_statistic_in_a_ragged_batch():
     # samples of a batch have different numbers of workgroups in the density pass; each sample's
     # largest key distance is the maximum over its own workgroups' words only
