@@ -28,7 +28,12 @@
  *    (zero-norm keys, non-finite values) are not errors: they follow the rules below and
  *    are flagged in pact_report.
  *  - `ws` is scratch of at least pact_workspace_bytes(...) bytes, 256-byte aligned.  Calls
- *    that share a workspace must be ordered on one stream.
+ *    that share a workspace must be ordered on one stream.  Its contents on entry are
+ *    arbitrary (every call initialises what it reads).
+ *  - Cache use: a call whose hidden states are larger than 192 MiB reads them, and writes
+ *    its merged rows, with the non-temporal hint (they would not stay in the 256 MB
+ *    last-level cache anyway); smaller calls use plain loads and stores.  Results do not
+ *    depend on this.
  *
  * Arithmetic (what "the same result as the definition" means here)
  *  - Scores (Eq. 2) are evaluated in fp64 and rounded once to fp32; the percentile split
