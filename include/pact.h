@@ -30,7 +30,7 @@
  *  - `ws` is scratch of at least pact_workspace_bytes(...) bytes, 256-byte aligned.  Calls
  *    that share a workspace must be ordered on one stream.  Its contents on entry are
  *    arbitrary (every call initialises what it reads).
- *  - Cache use: a call whose hidden states are larger than 192 MiB reads them, and writes
+ *  - Cache use: a call whose hidden states are larger than 150 MiB reads them, and writes
  *    its merged rows, with the non-temporal hint (they would not stay in the 256 MB
  *    last-level cache anyway); smaller calls use plain loads and stores.  Results do not
  *    depend on this.

@@ -300,9 +300,10 @@ __device__ __forceinline__ double wave_dot64(const char* ra, const char* rb, int
 // 16 bytes that this launch touches once: loads and stores with the streaming hint.  Used when a
 // call's hidden states are larger than what the 256 MB last-level cache can keep between the norm
 // pass and the merge anyway; for smaller calls the hint costs those later hits (one 7290-token
-// image: +4 us per call with it, 8 videos of 6272 tokens: -30 us).
+// image: +4 us per call with it, 8 videos of 6272 tokens: -30 us; batches of 2 to 6 such videos,
+// 43 MiB each: +8, +4, -6, -13, -20 us, hence the 150 MiB).
 inline bool hidden_streams(long total_tokens, int h, int elem_bytes) {
-    return (double)total_tokens * (double)h * (double)elem_bytes > 192.0 * 1024.0 * 1024.0;
+    return (double)total_tokens * (double)h * (double)elem_bytes > 150.0 * 1024.0 * 1024.0;
 }
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_once16(const void* p) {
