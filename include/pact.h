@@ -23,10 +23,15 @@
  *    rows and `center_idx` are in sequence order and the position id of merged row s is
  *    the caller's P[center_idx[s]] (Alg. 3 step 4).  cluster_id[i] = -1 means token i
  *    was pruned and not recovered.
- *  - Return value: PACT_OK, or an error code; on error nothing was enqueued and no output
- *    was touched.  Data anomalies that cannot be seen without reading device memory
- *    (zero-norm keys, non-finite values) are not errors: they follow the rules below and
- *    are flagged in pact_report.
+ *  - Return value: PACT_OK, or an error code.  Every code except PACT_ERR_HIP comes from a
+ *    check of the arguments on the host, made before anything is enqueued: no output was
+ *    touched.  PACT_ERR_HIP means a launch failed part-way through a call: kernels of that
+ *    call enqueued before it still run, and the outputs are then undefined.
+ *  - Data anomalies that cannot be seen without reading device memory are not errors and are
+ *    counted in pact_report: a zero-norm clustering key follows the rule below
+ *    (zero_norm_seen); non-finite values (NaN, Inf) in the hidden states, keys or queries
+ *    make the results unspecified - every index written still lies inside its sample - and
+ *    are counted in nonfinite_seen.
  *  - `ws` is scratch of at least pact_workspace_bytes(...) bytes, 256-byte aligned.  Calls
  *    that share a workspace must be ordered on one stream.  Its contents on entry are
  *    arbitrary (every call initialises what it reads).
@@ -44,6 +49,10 @@
  *    nearest-centre choice, so those decisions are the fp64 ones.
  *  - Densities (Eq. 6) are fp64 sums of fp32 terms exp2-evaluated from matrix-core cosines
  *    (bf16 keys as they are; fp32 keys as three bf16 parts per value, all 24 bits of them).
+ *    The density order (Alg. 2) only matters between tokens within d_c of each other; where
+ *    two such tokens have densities closer than a band of about fifty standard errors of
+ *    that fp32 sum, both densities are evaluated again entirely in fp64 (Eq. 5 and Eq. 6 as
+ *    written) and those decide (pact_report.rho_rechecked, rho_near_ties).
  *  - Ties: equal scores at the percentile are all kept; equal densities are processed in
  *    ascending token index; equal distances pick the centre with the lower token index.
  *  - A zero-norm key has cosine 0 (distance 1) to every other token; d_ii = 0.
@@ -114,16 +123,31 @@ typedef struct {
     int32_t rounds;            /* parallel centre rounds run, the last one confirming that no token is left */
     int32_t dc_checked_pairs;  /* ordered kept pairs re-evaluated in fp64 near d_c */
     int32_t dc_near_ties;      /* of those, pairs with |d - d_c| <= 1e-6 (each pair counted twice) */
-    int32_t refine_overflow;   /* 1 if the near-d_c list overflowed (pairs then keep fp32 decisions) */
+    int32_t refine_overflow;   /* bit 0: the near-d_c list overflowed (those pairs keep their fp32 decision);
+                                * bit 1: more than PACT_MAX_RHO_RECHECK tokens had a neighbour with a
+                                * density inside the band (none was re-evaluated: fp32-term densities decide) */
     int32_t zero_norm_seen;    /* kept or pruned tokens with a zero-norm clustering key */
     float   max_key_distance;  /* largest Eq. 5 distance between two clustered keys, from the fp32 pass
                                 * (the statistic Sec. "Selecting the layer L" looks at)  (dbdpc_cluster) */
-    int32_t reserved[5];       /* library use (reserved[0]: clusters the merge takes first) */
+    int32_t rho_rechecked;     /* kept tokens whose density was evaluated again in fp64 because a token
+                                * within d_c had a density inside the band              (dbdpc_cluster) */
+    int32_t rho_near_ties;     /* pairs of those whose fp64 densities differ, but by less than 1e-11 of
+                                * their sum: an order even fp64 cannot vouch for        (dbdpc_cluster) */
+    int32_t score_near_ties;   /* tokens whose score differs from the percentile threshold tau by at
+                                * most 1e-6 * tau without being equal to it              (pact_prune) */
+    int32_t nonfinite_seen;    /* tokens with a non-finite score, plus kept or pruned tokens whose
+                                * clustering key has a non-finite norm        (pact_prune, dbdpc_cluster,
+                                * pact_reincorporate) */
+    int32_t reserved[1];       /* library use (clusters the merge takes first) */
 } pact_report;
 
+/* At most this many tokens of a sample have their density evaluated again in fp64. */
+#define PACT_MAX_RHO_RECHECK 1024
+
 /* Scratch bytes needed for one call on samples of at most n_max tokens each, `batch`
- * samples, key width dk, n_q query heads of width d_h.  0 if an argument is out of range. */
-size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_q, int32_t d_h);
+ * samples, clustering keys of width dk and type k_dt (fp32 keys need room for their three-part
+ * bf16 form), n_q query heads of width d_h.  0 if an argument is out of range. */
+size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, pact_dtype k_dt, int32_t n_q, int32_t d_h);
 
 /* Eq. 1 + Eq. 2 (Alg. 1 steps 1-2): importance score of every token.
  *   hidden   [n, h]           h_dt   hidden states at the reduction layer
@@ -142,7 +166,7 @@ int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
 /* Eq. 3/4 (Alg. 1 step 3): tau = the (m+1)-th smallest score, m = min(floor(lambda*n), n-1);
  * kept = {s_i >= tau}, pruned = {s_i < tau}.
  *   kept_idx [n], pruned_idx [n] out, ascending; only the first n_kept / n_pruned are written
- *   rep      out: n_kept, n_pruned */
+ *   rep      out: n_kept, n_pruned, score_near_ties, nonfinite_seen (scores only) */
 int pact_prune(const float* scores, int32_t n, float lambda,
                int32_t* kept_idx, int32_t* pruned_idx, pact_report* rep,
                void* ws, size_t ws_bytes, void* stream);
@@ -156,10 +180,12 @@ int pact_prune(const float* scores, int32_t n, float lambda,
  *   n_idx_dev  device int32 holding the subset size (ignored when idx is NULL)
  *   center_idx [n] out: token indices of the C centres, ascending (first C written)
  *   cluster_id [n] out: 0..C-1 for tokens in idx, -1 for the others
- *   rep        out: n_centers, rounds, dc_* counters, zero_norm_seen; when idx is NULL also
- *              n_kept = n, n_pruned = 0
- *   rho_opt    [n] fp64 out or NULL: density of idx[p] at position p
- *   rank_opt   [n] int32 out or NULL: position of idx[p] in the density order (0 = densest) */
+ *   rep        out: n_centers, rounds, dc_* and rho_* counters, refine_overflow, zero_norm_seen,
+ *              nonfinite_seen, max_key_distance; when idx is NULL also n_kept = n, n_pruned = 0
+ *   rho_opt    [n] fp64 out or NULL: density of idx[p] at position p, as it was used (fp64 sum of
+ *              fp32 terms, or the fp64 value for the tokens counted in rho_rechecked)
+ *   rank_opt   [n] int32 out or NULL: position of idx[p] in the descending order of those
+ *              densities (0 = densest, equal densities by ascending index) */
 int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
                   const int32_t* idx, const int32_t* n_idx_dev,
                   float d_c, float d_n, int32_t fallback_T,
@@ -168,10 +194,10 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
                   void* ws, size_t ws_bytes, void* stream);
 
 /* Eq. 8/9 (Alg. 3 step 3): each pruned token joins its nearest centre s iff d_is < alpha*d_c.
- *   pruned_idx [rep->n_pruned], center_idx [rep->n_centers]  (counts are read on the device
- *   from `rep`, as pact_prune and dbdpc_cluster left them)
+ *   pruned_idx [rep->n_pruned], center_idx [rep->n_centers]  (n_kept, n_pruned and n_centers
+ *   are read on the device from `rep`, as pact_prune and dbdpc_cluster left them)
  *   cluster_id [n] in/out: entries of pruned tokens are overwritten (cluster or -1)
- *   rep        in/out: n_reincorporated, n_dropped written */
+ *   rep        in/out: n_reincorporated, n_dropped written; zero_norm_seen, nonfinite_seen added to */
 int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
                        const int32_t* pruned_idx, const int32_t* center_idx,
                        float d_c, float alpha, int32_t* cluster_id, pact_report* rep,
@@ -179,12 +205,13 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
 
 /* Eq. 10 (Alg. 3 step 4): merged[s] = mean of hidden[i] over cluster_id[i] == s.
  *   cluster_id     [n] values in -1..C-1, C = rep->n_centers (read on the device)
+ *   rep            in/out: n_centers read; the library keeps a count of its own in reserved[]
  *   center_idx     [C] needed only with PACT_FLAG_NO_MERGE (may be NULL otherwise)
  *   merged         [n, h] out_dt, worst case; rows 0..C-1 written (a cluster id nobody carries
  *                  gives a row of zeros)
  *   cluster_counts [n] out: members per cluster (the weights W of Eq. 11) */
 int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
-               const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+               const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                uint32_t flags, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
                void* ws, size_t ws_bytes, void* stream);
 
@@ -228,31 +255,6 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
 int pact_attention_handoff(const int32_t* center_idx, const int32_t* cluster_counts, const pact_report* rep,
                            const int32_t* positions, const int32_t* cu_seqlens, int32_t batch, int32_t n,
                            int32_t* positions_out, float* log_weight, void* stream);
-
-/* Optional per-kernel timing (for benchmarks; Sec. "Algo. Time" is what it decomposes).
- * While enabled, every kernel the library enqueues is bracketed by events on its stream.
- * pact_profile_read synchronises those events and returns the number of records since the
- * last pact_profile_reset; names[i] points to a static string, ms[i] is the kernel's
- * duration.  Host pointers.  Not thread-safe; leave disabled in production. */
-int pact_profile_enable(int on);
-int pact_profile_reset(void);
-int pact_profile_read(const char** names, float* ms, int32_t max_records);
-
-/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; src and dst 16-byte aligned,
- * not overlapping) by one kernel named pact::calibration_copy_kernel: it reads and writes
- * exactly `bytes` bytes, which gives hardware byte counters (rocprofv3's FETCH_SIZE and
- * WRITE_SIZE) a dispatch of known traffic to be scaled by.  Benchmarks only. */
-int pact_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
-
-/* Diagnostic (host only, nothing is enqueued): how a matrix pass of a batched call deals the
- * chip's 256 workgroup slots to the samples, given the number of output tiles each sample is
- * expected to have.  Slot i runs on XCD i mod 8.
- *   tiles     [batch] host      expected tiles per sample (>= 1)
- *   wg_map    [256] host out    (sample << 8) | (number of that workgroup within its sample), 0xFFFF = spare slot
- *   wg_count  [batch] host out  workgroups per sample: at least 1, at most its tiles, so that the
- *                               most loaded workgroup has as few tiles as 256 slots allow
- * Returns PACT_OK, PACT_ERR_NULL or PACT_ERR_SHAPE. */
-int pact_plan_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, uint16_t* wg_count);
 
 const char* pact_strerror(int status);
 

@@ -3,7 +3,8 @@ sample, chosen with the oracle so that the total reduction 1 - C/n hits the
 configuration's target.
 
 TEST INFRASTRUCTURE ONLY: calls oracle/ and the input generator, nothing else.
-Run from the repository root:   python -m oracle.calibrate_dc [group ...]
+Run from the repository root:   python -m oracle.calibrate_dc [--missing] [group ...]
+(--missing: only the samples that have no entry yet)
 
 For each sample: scores, percentile split and the kept tokens' distance matrix and
 density order are computed once; d_c is bisected on the number of centres Alg. 2
@@ -95,15 +96,19 @@ def groups():
         "tiny_f32": lambda: [gen.make_sample("tiny_f32", s) for s in range(10)],
         "tiny_bf16": lambda: [gen.make_sample("tiny_bf16", s) for s in range(10)],
         "img_0p5b": lambda: [gen.make_sample("img_0p5b", s) for s in range(10)],
-        "img_7b": lambda: [gen.make_sample("img_7b", s) for s in range(3)],
-        "vid_7b": lambda: gen.make_batch("vid_7b", 0),
-        "varlen": lambda: gen.make_varlen_batch(0),
-        "vid_long": lambda: [gen.make_sample("vid_long", 0)],
+        "img_7b": lambda: [gen.make_sample("img_7b", s) for s in range(10)],
+        "vid_7b": lambda: [s for b in range(3) for s in gen.make_batch("vid_7b", b)],
+        "varlen": lambda: [s for b in range(3) for s in gen.make_varlen_batch(b)],
+        "vid_long": lambda: [gen.make_sample("vid_long", s) for s in range(3)],
+        # the long video with nothing pruned: all 16384 tokens are clustered
+        "vid_long_all": lambda: [gen.make_sample("vid_long", 0, lam=0.0)],
     }
     return g
 
 
 def main(argv):
+    only_missing = "--missing" in argv
+    argv = [a for a in argv if a != "--missing"]
     want = argv or list(groups().keys())
     manifest = {}
     if os.path.exists(MANIFEST):
@@ -111,8 +116,13 @@ def main(argv):
             manifest = json.load(f)
     for name in want:
         for s in groups()[name]():
+            if only_missing and sample_key(s) in manifest:
+                continue
             t = time.time()
             entry = calibrate(s, s.config.target_reduction)
+            if os.path.exists(MANIFEST):           # (another run may have added entries meanwhile)
+                with open(MANIFEST) as f:
+                    manifest = json.load(f)
             manifest[sample_key(s)] = entry
             print(f"{sample_key(s)}: d_c={entry['d_c']:.6f} q={entry['q']} C={entry['C']} "
                   f"reduction={entry['reduction']:.4f} gap={entry['min_gap_to_dc']:.2e} "

@@ -14,8 +14,10 @@ PACT_FLAG_SCORE_NO_NORM = 2
 PACT_FLAG_SCORE_NORM_ONLY = 4
 PACT_FLAG_KEY_STATS = 8
 REPORT_FIELDS = ("n_kept", "n_pruned", "n_centers", "n_reincorporated", "n_dropped", "rounds",
-                 "dc_checked_pairs", "dc_near_ties", "refine_overflow", "zero_norm_seen")
+                 "dc_checked_pairs", "dc_near_ties", "refine_overflow", "zero_norm_seen", "max_key_distance",
+                 "rho_rechecked", "rho_near_ties", "score_near_ties", "nonfinite_seen")
 REPORT_INTS = 16
+_REPORT_FLOAT = REPORT_FIELDS.index("max_key_distance")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -59,7 +61,7 @@ def load_library():
     lib = C.CDLL(path)
     vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
     lib.pact_workspace_bytes.restype = sz
-    lib.pact_workspace_bytes.argtypes = [i32] * 5
+    lib.pact_workspace_bytes.argtypes = [i32, i32, i32, C.c_int, i32, i32]
     lib.pact_score.restype = C.c_int
     lib.pact_score.argtypes = [vp, C.c_int, i32, i32, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
                                C.c_uint32, vp, vp, sz, vp]
@@ -119,19 +121,28 @@ def _out_dt(dtype) -> int:
 
 
 def _p(t):
-    return None if t is None else C.c_void_p(t.data_ptr())
+    """Device address of a tensor (None -> NULL).  The library reads rows back to back: a view with
+    other strides would be read as if it were contiguous, so it is refused here."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise PactError("tensor arguments must be contiguous (row-major)")
+    return C.c_void_p(t.data_ptr())
 
 
 def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def pact_workspace_bytes(n_max: int, batch: int, dk: int, n_q: int, d_h: int) -> int:
-    return int(load_library().pact_workspace_bytes(n_max, batch, dk, n_q, d_h))
+def pact_workspace_bytes(n_max: int, batch: int, dk: int, n_q: int, d_h: int, key_dtype=PACT_F32) -> int:
+    """key_dtype: PACT_F32 / PACT_BF16 or a torch dtype (fp32 keys, the default, need the larger workspace)."""
+    if not isinstance(key_dtype, int):
+        key_dtype = PACT_BF16 if key_dtype == torch.bfloat16 else PACT_F32
+    return int(load_library().pact_workspace_bytes(n_max, batch, dk, key_dtype, n_q, d_h))
 
 
-def alloc_workspace(n_max: int, batch: int, dk: int, n_q: int, d_h: int, device="cuda") -> torch.Tensor:
-    nbytes = pact_workspace_bytes(n_max, batch, dk, n_q, d_h)
+def alloc_workspace(n_max: int, batch: int, dk: int, n_q: int, d_h: int, device="cuda", key_dtype=PACT_F32) -> torch.Tensor:
+    nbytes = pact_workspace_bytes(n_max, batch, dk, n_q, d_h, key_dtype)
     if nbytes == 0:
         raise PactError("pact_workspace_bytes: arguments out of range")
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -148,7 +159,7 @@ def read_report(rep: torch.Tensor):
     out = [dict(zip(REPORT_FIELDS, row)) for row in h]
     fl = hc.view(torch.float32)
     for b, d in enumerate(out):
-        d["max_key_distance"] = float(fl[b, len(REPORT_FIELDS)])
+        d["max_key_distance"] = float(fl[b, _REPORT_FLOAT])
     return out[0] if len(out) == 1 else out
 
 
@@ -177,7 +188,7 @@ def dbdpc_cluster(keys, d_c: float, d_n: float = 2.0, fallback_T: int = 10, idx=
                   rep=None, ws=None, want_rho=False, want_rank=False):
     n, dk = keys.shape
     dev = keys.device
-    ws = ws if ws is not None else alloc_workspace(n, 1, dk, 1, 1, dev)
+    ws = ws if ws is not None else alloc_workspace(n, 1, dk, 1, 1, dev, keys.dtype)
     center_idx = torch.empty(n, dtype=torch.int32, device=dev)
     cluster_id = torch.empty(n, dtype=torch.int32, device=dev)
     rep = rep if rep is not None else new_report(1, dev)
@@ -191,7 +202,7 @@ def dbdpc_cluster(keys, d_c: float, d_n: float = 2.0, fallback_T: int = 10, idx=
 
 def pact_reincorporate(keys, pruned_idx, center_idx, d_c: float, alpha: float, cluster_id, rep, ws=None):
     n, dk = keys.shape
-    ws = ws if ws is not None else alloc_workspace(n, 1, dk, 1, 1, keys.device)
+    ws = ws if ws is not None else alloc_workspace(n, 1, dk, 1, 1, keys.device, keys.dtype)
     _check(load_library().pact_reincorporate(_p(keys), _dt(keys), n, dk, _p(pruned_idx), _p(center_idx), d_c,
                                              alpha, _p(cluster_id), _p(rep), _p(ws), ws.numel(), _stream()),
            "pact_reincorporate")
@@ -225,7 +236,7 @@ def pact_reduce(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int, params
     valid lengths are in out['rep'], on the device)."""
     n, h = hidden.shape
     dev = hidden.device
-    ws = ws if ws is not None else alloc_workspace(n, 1, n_kv * d_h, n_q, d_h, dev)
+    ws = ws if ws is not None else alloc_workspace(n, 1, n_kv * d_h, n_q, d_h, dev, keys.dtype)
     o = out if out is not None else _alloc_outputs(n, h, 1, out_dtype, dev)
     pc = params.c()
     _check(load_library().pact_reduce(
@@ -244,7 +255,7 @@ def pact_reduce_varlen(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int,
     batch = len(cu_seqlens) - 1
     dev = hidden.device
     n_max = max(cu_seqlens[b + 1] - cu_seqlens[b] for b in range(batch))
-    ws = ws if ws is not None else alloc_workspace(n_max, batch, n_kv * d_h, n_q, d_h, dev)
+    ws = ws if ws is not None else alloc_workspace(n_max, batch, n_kv * d_h, n_q, d_h, dev, keys.dtype)
     o = out if out is not None else _alloc_outputs(total, h, batch, out_dtype, dev)
     cu = (C.c_int32 * (batch + 1))(*cu_seqlens)
     pa = (_Params * batch)(*[p.c() for p in params])

@@ -132,10 +132,10 @@ using namespace pact;
 
 extern "C" {
 
-size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, int32_t n_q, int32_t d_h) {
+size_t pact_workspace_bytes(int32_t n_max, int32_t batch, int32_t dk, pact_dtype k_dt, int32_t n_q, int32_t d_h) {
     if (n_max < 1 || n_max > PACT_MAX_TOKENS || batch < 1 || batch > PACT_MAX_BATCH) return 0;
-    if (dk < 1 || n_q < 1 || n_q > PACT_MAX_QHEADS || d_h < 1) return 0;
-    return make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, dk).total;
+    if (dk < 1 || !dtype_ok(k_dt) || n_q < 1 || n_q > PACT_MAX_QHEADS || d_h < 1) return 0;
+    return make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, dk, k_dt).total;
 }
 
 int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
@@ -153,7 +153,7 @@ int pact_score(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_tensor(keys_pre, k_dt, (int64_t)n_kv * d_h))) return rc;
     if ((rc = check_tensor(q, q_dt, (int64_t)n_q * d_h))) return rc;
     if (((int64_t)d_h * esize(k_dt)) % 16 != 0 || ((int64_t)d_h * esize(q_dt)) % 16 != 0) return PACT_ERR_ALIGN;
-    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, 0);
+    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, 0, PACT_BF16);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     Batch bt;
@@ -201,7 +201,7 @@ int dbdpc_cluster(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if ((rc = check_key_extent(n, dk, k_dt))) return rc;
     if ((rc = check_params(0.0f, d_c, d_n, 0.0f))) return rc;
     if (fallback_T < 0) return PACT_ERR_PARAM;
-    const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, dk, k_dt);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -229,7 +229,7 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
     if ((rc = check_tensor(keys, k_dt, dk))) return rc;
     if ((rc = check_key_extent(n, dk, k_dt))) return rc;
     if ((rc = check_params(0.0f, d_c, 1.0f, alpha))) return rc;
-    const WsLayout L = make_layout(n, 1, n, 1, 1, dk);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, dk, k_dt);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -245,7 +245,7 @@ int pact_reincorporate(const void* keys, pact_dtype k_dt, int32_t n, int32_t dk,
 }
 
 int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
-               const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+               const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                uint32_t flags, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
                void* ws, size_t ws_bytes, void* stream) {
     if (!cluster_id || !rep || !merged || !cluster_counts) return PACT_ERR_NULL;
@@ -255,7 +255,7 @@ int pact_merge(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_tensor(hidden, h_dt, h))) return rc;
     if (!dtype_ok(out_dt)) return PACT_ERR_DTYPE;
     if (!aligned16(merged) || ((int64_t)h * esize(out_dt)) % 16 != 0) return PACT_ERR_ALIGN;
-    const WsLayout L = make_layout(n, 1, n, 1, 1, 0);
+    const WsLayout L = make_layout(n, 1, n, 1, 1, 0, PACT_BF16);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     pact_params p = default_params();
@@ -305,7 +305,7 @@ int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_key_extent(n, (int64_t)n_kv * d_h, k_dt))) return rc;
     if ((rc = check_params(p->lambda, p->d_c, p->d_n, p->alpha))) return rc;
     if (p->fallback_T < 0) return PACT_ERR_PARAM;
-    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
+    const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h, k_dt);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     Batch bt;
@@ -346,7 +346,7 @@ int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
     if (q_rows != total && q_rows != batch) return PACT_ERR_SHAPE;
     if ((rc = check_key_extent(n_max, (int64_t)n_kv * d_h, k_dt))) return rc;
     bt.B = batch; bt.n_max = n_max; bt.W = (n_max + 63) / 64; bt.total = total;
-    const WsLayout L = make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h);
+    const WsLayout L = make_layout(n_max, batch, (int64_t)n_max * batch, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h, k_dt);
     if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
     const Ws w = resolve(ws, L);

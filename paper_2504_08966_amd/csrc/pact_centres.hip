@@ -23,6 +23,13 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
     return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
+// A clustering key whose squared norm is zero, or not a finite number, is counted in the report.
+__device__ __forceinline__ void note_odd_norm(pact_report* rp, double nn) {
+    if (nn > 0.0 && nn < INFINITY) return;
+    if (nn == 0.0) atomicAdd(&rp->zero_norm_seen, 1);
+    else atomicAdd(&rp->nonfinite_seen, 1);
+}
+
 __device__ __forceinline__ bool precedes(double rho_j, int j, double rho_i, int i) {
     return rho_j > rho_i || (rho_j == rho_i && j < i);
 }
@@ -309,39 +316,53 @@ struct BitPop {
     }
 };
 
+// Density order between neighbours (Alg. 2 sorts by density; only the order of tokens within
+// d_c of each other can change which of them becomes a centre).  The densities summed by the
+// matrix pass are fp64 sums of fp32 terms: each term carries the rounding of its exponent
+// (matrix-core accumulation, scaling products, one fused multiply-add; a = log2(e) / d_n is the
+// factor that turns a cosine error into an exponent error) and of the hardware exponential,
+// independent from term to term, so the error of a sum grows like the square root of the number
+// of terms that matter.  Measured against fp64 on 7290-token images: standard error of the
+// difference of two neighbours' densities 2.1e-6 at d_n = 2 (rho = 2 400), 4.9e-6 at d_n = 0.5
+// (rho = 570), 1.6e-6 at d_n = 8; largest seen 8e-6 / 3.2e-5 / 1.2e-5.  Two neighbours whose
+// sums differ by less than
+//     2^-20 (1 + 4a) sqrt(max(rho_i, rho_j))          (1.8e-4 / 2.8e-4 / 9.8e-5 for those cases)
+// are both listed, and their densities are evaluated again entirely in fp64 before the order
+// between them is used.  This is a statistical bound (fifty and more standard errors), not a
+// worst-case one: the worst-case error of an fp32 cosine would list half the tokens of an image.
+__device__ __forceinline__ double recheck_band2(float d_n) {
+    const double a = 1.4426950408889634 / (double)d_n;
+    const double c = (1.0 / 1048576.0) * (1.0 + 4.0 * a);
+    return c * c;                          // compared with (rho_i - rho_j)^2 / max(rho_i, rho_j)
+}
+
 // For every kept token: the list of its neighbours (bitmap row) that precede it in the
 // density order, as 16-bit positions in slots 1..KP of its PRED_CAP-slot record; slot 0 holds
 // the list length, or KP+1 if the list did not fit (the token is then evaluated from its
 // bitmap row).  The first four slots are also written to the token's 8-byte head: most tokens
 // have at most three preceding neighbours, and the kernel that runs the rounds - a single
 // workgroup - then has 8 bytes per token to fetch instead of 32.
-// One wavefront per kept token; grid (ceil(n_max/4), B), block 256.
+// One wavefront per kept token p.  `odd` counts, wave-wide, the neighbours whose density is
+// too close to this token's: DETECT: inside the band above; otherwise (second pass, on fp64
+// densities): lower-numbered neighbours with a different density within 1e-11 of the sum.
 constexpr int HEAD_PREDS = 3;
 constexpr int PREDS_SPREAD = 256;      // set bits of 64 row words that are spread over the lanes through LDS
-__global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
-                                                          const uint64_t* __restrict__ adj,
-                                                          const double* __restrict__ rho,
-                                                          uint16_t* __restrict__ preds,
-                                                          uint2* __restrict__ heads) {
-    const int b = blockIdx.y;
-    const int lane = threadIdx.x & 63;
-    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
-    if (p >= q) return;
-    const double* r = rho + (size_t)b * bt.n_max;
+template <bool DETECT>
+__device__ __forceinline__ int preds_of_row(int p, int q, const double* r, const uint64_t* row, uint16_t* out,
+                                            uint16_t* head, volatile uint16_t* nb, int lane, double band2) {
     const double rp = r[p];
-    const uint64_t* row = adj + ((size_t)b * bt.n_max + p) * bt.W;
-    uint16_t* out = preds + ((size_t)b * bt.n_max + p) * PRED_CAP;
-    uint16_t* head = (uint16_t*)(heads + (size_t)b * bt.n_max + p);
     const int Wq = (q + 63) >> 6;
-    int total = 0;
+    int total = 0, odd = 0;
+    auto too_close = [&](bool has, int j, double rj) __attribute__((always_inline)) {
+        const double d = rj - rp;
+        if constexpr (DETECT) return has && j < q && j != p && d * d <= band2 * fmax(rj, rp);
+        else return has && j < p && d != 0.0 && fabs(d) <= 1e-11 * (rj + rp);
+    };
     // A token's neighbours are mostly close to it in the sequence, i.e. their bits sit in one or
     // two words of the row: lane by lane, a word's bits would be looked up one after the other,
     // each look-up (the neighbour's density) a trip to memory.  So the set bits of 64 words are
     // first spread over the lanes - the k-th set bit to lane k, through a small LDS list - and
     // the densities of up to 64 neighbours are fetched in one trip.
-    __shared__ uint16_t s_nb[4][PREDS_SPREAD];
-    volatile uint16_t* nb = s_nb[threadIdx.x >> 6];
     for (int w0 = 0; w0 < Wq; w0 += 64) {
         const int w = w0 + lane;
         uint64_t word = (w < Wq) ? row[w] : 0ull;
@@ -364,12 +385,14 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
                 const int k = k0 + lane;
                 const bool has = k < nbits;
                 const int j = has ? nb[k] : p;
-                const bool pre = has && j < q && precedes(r[j], j, rp, p);
+                const double rj = r[j < q ? j : p];
+                const bool pre = has && j < q && precedes(rj, j, rp, p);
                 const uint64_t m = __ballot(pre);
                 const int slot = total + lanes_below(m, lane);
                 if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
                 if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
                 total += __popcll(m);
+                odd += __popcll(__ballot(too_close(has, j, rj)));
             }
             __builtin_amdgcn_wave_barrier();                 // the list is rewritten for the next 64 words
         } else {
@@ -379,12 +402,14 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
                 int bit;
                 const bool has = bp.pop(bit);
                 const int j = (w << 6) + bit;
-                const bool pre = has && j < q && precedes(r[has ? j : p], j, rp, p);
+                const double rj = r[(has && j < q) ? j : p];
+                const bool pre = has && j < q && precedes(rj, j, rp, p);
                 const uint64_t m = __ballot(pre);
                 const int slot = total + lanes_below(m, lane);
                 if (pre && slot < KP) out[1 + slot] = (uint16_t)j;
                 if (pre && slot < HEAD_PREDS) head[1 + slot] = (uint16_t)j;
                 total += __popcll(m);
+                odd += __popcll(__ballot(too_close(has, j, rj)));
             }
         }
     }
@@ -392,6 +417,33 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
         const uint16_t c = (uint16_t)(total > KP ? KP + 1 : total);
         out[0] = c;
         head[0] = c;
+    }
+    return odd;
+}
+
+// grid (ceil(n_max/4), B), block 256: one wavefront per kept token.  Tokens with a neighbour
+// inside the band are appended to the sample's list (tie_cnt[4b] counts them, also past the
+// list's end: the re-evaluation is then skipped and reported).
+__global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
+                                                          const uint64_t* __restrict__ adj,
+                                                          const double* __restrict__ rho,
+                                                          uint16_t* __restrict__ preds,
+                                                          uint2* __restrict__ heads,
+                                                          int32_t* __restrict__ tie_list,
+                                                          int32_t* __restrict__ tie_cnt) {
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int q = clamp_count(rep[b].n_kept, bt.s[b].n);
+    if (p >= q) return;
+    __shared__ uint16_t s_nb[4][PREDS_SPREAD];
+    const int odd = preds_of_row<true>(p, q, rho + (size_t)b * bt.n_max, adj + ((size_t)b * bt.n_max + p) * bt.W,
+                                       preds + ((size_t)b * bt.n_max + p) * PRED_CAP,
+                                       (uint16_t*)(heads + (size_t)b * bt.n_max + p), s_nb[threadIdx.x >> 6], lane,
+                                       recheck_band2(bt.s[b].d_n));
+    if (odd && lane == 0) {
+        const int slot = atomicAdd(&tie_cnt[4 * b], 1);
+        if (slot < RHO_RECHECK_MAX) tie_list[(size_t)b * RHO_RECHECK_MAX + slot] = p;
     }
 }
 
@@ -782,7 +834,7 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
     if (lane == 0) {
         cluster_id[sg.base + tok] = cid;
         if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
-        if (!(nnb[tok] > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
+        note_odd_norm(rep + b, nnb[tok]);
     }
 }
 
@@ -819,6 +871,145 @@ __device__ __forceinline__ double group_dot64(const char* mine, const char* othe
 #pragma unroll
     for (int sft = 1; sft <= 8; sft <<= 1) acc += __shfl_xor(acc, sft, 64);
     return acc;
+}
+
+// group_dot64 for the row pair (mine, other) and, in the same pass and the same order of
+// operations, for (other, other): rows that are bit-identical then give bit-identical dot products
+// and norms, i.e. a cosine of exactly 1.
+template <int DT>
+__device__ __forceinline__ void group_dot64_with_norm(const char* mine, const char* other, int nchunk, int part,
+                                                      double& dot, double& nn_other) {
+    constexpr int EPL = Elem<DT>::EPL;
+    double acc = 0.0, acc2 = 0.0;
+#pragma unroll 1
+    for (int k0 = part; k0 < nchunk; k0 += 64) {
+        uint4 va[4], vb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t o = (size_t)(k0 + 16 * u < nchunk ? k0 + 16 * u : k0) * 16;
+            va[u] = *(const uint4*)(mine + o);
+            vb[u] = *(const uint4*)(other + o);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (k0 + 16 * u < nchunk) {
+                double a[8], x[8];
+                Elem<DT>::widen(va[u], a);
+                Elem<DT>::widen(vb[u], x);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) { acc = fma(a[i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
+            }
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft <= 8; sft <<= 1) { acc += __shfl_xor(acc, sft, 64); acc2 += __shfl_xor(acc2, sft, 64); }
+    dot = acc;
+    nn_other = acc2;
+}
+
+// Densities of the listed tokens again, entirely in fp64 (Eq. 5 and Eq. 6 as they are written:
+// dot product, two norms - recomputed here by the routine that computes the dot product, so
+// that a copy of the token is at distance exactly 0 -, one division, one exponential per pair,
+// the term of the token itself exactly 1), then the predecessor lists of those tokens again
+// from the new values.
+// Work items are (listed token, chunk of RHO_RECHECK_CHUNK kept tokens): one workgroup per item
+// and turn, 16 lanes per pair; a chunk's terms are summed in a fixed order, a token's chunks
+// likewise.  The sum itself is exact, hence the same in any order and for any two tokens with
+// the same terms (two tokens at equal distances from everything else tie exactly, as they do
+// for a correctly rounded sum, and the index decides): every term t in (0, 1] is split into
+// hi = t rounded to a multiple of 2^-30 and lo = t - hi; sums of at most 32768 such hi, and of
+// such lo as long as t >= 2^-17 (d_n >= 0.17), fit the 53 bits of an fp64 whatever their order,
+// and the density is hi_total + lo_total, rounded once.  The workgroup that finishes last (one
+// counter per sample) adds the chunks up and rebuilds the lists; nobody waits for anybody.
+// grid (blocks per sample, B), block 256.
+template <int DT>
+__global__ __launch_bounds__(256) void rho_recheck_kernel(Batch bt, const char* keys, int dk, const int32_t* idx,
+                                                           const uint64_t* adj, pact_report* rep,
+                                                           double* rho, double* rho_opt, double* part,
+                                                           const int32_t* tie_list, int32_t* tie_cnt,
+                                                           uint16_t* preds, uint2* heads) {
+    __shared__ double s_hi[RHO_RECHECK_CHUNK], s_lo[RHO_RECHECK_CHUNK];
+    __shared__ uint16_t s_nb[4][PREDS_SPREAD];
+    __shared__ int s_last;
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int T = tie_cnt[4 * b];                      // (the same for every workgroup of the sample)
+    if (T <= 0) return;
+    if (T > RHO_RECHECK_MAX) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&rep[b].refine_overflow, OVERFLOW_RHO_RECHECK);
+        return;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = clamp_count(rep[b].n_kept, sg.n);
+    const int nch = (q + RHO_RECHECK_CHUNK - 1) / RHO_RECHECK_CHUNK;
+    const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
+    const int nchunk = (int)(row_bytes / 16);
+    const char* kb = keys + (size_t)sg.base * row_bytes;
+    const int32_t* ix = idx + sg.base;
+    const int32_t* list = tie_list + (size_t)b * RHO_RECHECK_MAX;
+    double* part_b = part + (size_t)b * 2 * rho_fix_tokens(bt.n_max) * rho_fix_chunks(bt.n_max);   // [T][nch][2], T <= q <= n_max
+    double* rho_b = rho + (size_t)b * bt.n_max;
+    const double d_n = (double)sg.d_n;
+    const int g = tid >> 4, part16 = tid & 15;
+    for (int item = blockIdx.x; item < T * nch; item += gridDim.x) {
+        const int t = item / nch, c = item - t * nch;
+        const int p = min(max(list[t], 0), q - 1);
+        const int tok = ix[p];
+        const char* mine = kb + (size_t)tok * row_bytes;
+        double nnp, dot, nnk;
+        group_dot64_with_norm<DT>(mine, mine, nchunk, part16, dot, nnp);
+#pragma unroll 1
+        for (int s = 0; s < RHO_RECHECK_CHUNK / 16; ++s) {
+            const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
+            const bool valid = pk < q;
+            const int tk = ix[valid ? pk : p];
+            group_dot64_with_norm<DT>(mine, kb + (size_t)tk * row_bytes, nchunk, part16, dot, nnk);
+            const double d = cos_dist64(dot, nnp, nnk);
+            const double term = !valid ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
+            const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
+            if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            static_assert(RHO_RECHECK_CHUNK == 128, "two terms per lane");
+            const double vh = wave_sum_f64(s_hi[lane] + s_hi[lane + 64]);
+            const double vl = wave_sum_f64(s_lo[lane] + s_lo[lane + 64]);
+            if (lane == 0) *(double2*)(part_b + ((size_t)t * nch + c) * 2) = make_double2(vh, vl);
+        }
+        __syncthreads();
+    }
+    // the last workgroup of the sample to get here finishes the job
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_last = atomicAdd(&tie_cnt[4 * b + 1], 1) == (int)gridDim.x - 1;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    for (int t = wave; t < T; t += 4) {
+        double ah = 0.0, al = 0.0;
+        for (int c = lane; c < nch; c += 64) {
+            const double2 v = *(const double2*)(part_b + ((size_t)t * nch + c) * 2);
+            ah += v.x;
+            al += v.y;
+        }
+        const double acc = wave_sum_f64(ah) + wave_sum_f64(al);
+        if (lane == 0) {
+            const int p = min(max(list[t], 0), q - 1);
+            rho_b[p] = acc;
+            if (rho_opt) rho_opt[sg.base + p] = acc;
+        }
+    }
+    __threadfence();
+    __syncthreads();
+    int fine = 0;
+    for (int t = wave; t < T; t += 4) {
+        const int p = min(max(list[t], 0), q - 1);
+        fine += preds_of_row<false>(p, q, rho_b, adj + ((size_t)b * bt.n_max + p) * bt.W,
+                                    preds + ((size_t)b * bt.n_max + p) * PRED_CAP,
+                                    (uint16_t*)(heads + (size_t)b * bt.n_max + p), s_nb[wave], lane, 0.0);
+    }
+    if (lane == 0 && fine) atomicAdd(&rep[b].rho_near_ties, fine);
+    if (tid == 0) rep[b].rho_rechecked = T;
 }
 
 // Eq. 8/9: every pruned token joins the nearest centre iff its fp64 distance is below
@@ -952,7 +1143,7 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
             // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
             //  counter that every wavefront hits would serialise at one L2 address)
             if (res >= 0 && cluster_counts) atomicAdd(&cluster_counts[res], 1);
-            if (!(nnb[tok] > 0.0)) atomicAdd(&rep[b].zero_norm_seen, 1);
+            note_odd_norm(rep + b, nnb[tok]);
         }
     }
 }
@@ -1027,12 +1218,20 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     else
         PACT_LAUNCH("post_gram", post_gram_kernel<PACT_F32>, gpost, dim3(256), st, bt, k, dk, idx, w.nn,
                     w.near_list, w.near_cnt, w.stat, stat_words, w.adj, rep, w.rho_part, w.rho, rho_opt);
+    dim3 gtok((bt.n_max + 3) / 4, bt.B);
+    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
+                w.heads, w.tie_list, w.tie_cnt);
+    // neighbours whose densities the fp32 terms cannot order: fp64 (a few tokens of an image)
+    const int rb = 512 / bt.B < 4 ? 4 : (512 / bt.B > 256 ? 256 : 512 / bt.B);
+    if (k_dt == PACT_BF16)
+        PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
+                    w.adj, rep, w.rho, rho_opt, w.rho_fix, w.tie_list, w.tie_cnt, w.preds, w.heads);
+    else
+        PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_F32>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
+                    w.adj, rep, w.rho, rho_opt, w.rho_fix, w.tie_list, w.tie_cnt, w.preds, w.heads);
     if (rank_opt)
         PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
                     w.rho, rank_opt);
-    dim3 gtok((bt.n_max + 3) / 4, bt.B);
-    PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
-                w.heads);
     const size_t qpad = (size_t)((bt.n_max + 63) / 64 * 64);
     const size_t lds = qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4;
     static size_t raised = 0;

@@ -17,7 +17,7 @@ struct PrepArgs {
     const char* keys; int32_t dk;
     const char* q; int32_t qcols;            // q == nullptr: no query pass
     double* nn; float* rinv; uint64_t* adj; double* qg_part;
-    uint32_t* status; int32_t* ident; int32_t* near_cnt;
+    uint32_t* status; int32_t* ident; int32_t* near_cnt; int32_t* tie_cnt;
     pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
     const int32_t* n_idx_dev; uint32_t* zeros;
     uint16_t* ksplit;                        // fp32 keys only: [total][3][dk rounded up to 8] bf16 parts for the Gram passes
@@ -35,6 +35,8 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         if (kblk == 0 && b == 0 && threadIdx.x < 64) a.zeros[threadIdx.x] = 0u;
         if (kblk == 0 && threadIdx.x == 0) {
             a.near_cnt[2 * b] = 0; a.near_cnt[2 * b + 1] = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) a.tie_cnt[4 * b + k] = 0;
             pact_report* rp = a.rep + b;
             const int mode = a.mode;
             if (mode == INIT_REDUCE || mode == INIT_DBDPC_ALL || mode == INIT_DBDPC_SUBSET) {
@@ -47,7 +49,10 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
                 rp->refine_overflow = 0; rp->n_reincorporated = 0; rp->n_dropped = 0;
                 rp->zero_norm_seen = 0;     // counted by the assignment kernels, which run later
                 rp->max_key_distance = 0.0f;
-                for (int k = 0; k < 5; ++k) rp->reserved[k] = 0;
+                rp->rho_rechecked = 0; rp->rho_near_ties = 0;
+                // (a clustering call on a subset follows a split, whose two counters it adds to)
+                if (mode != INIT_DBDPC_SUBSET) { rp->score_near_ties = 0; rp->nonfinite_seen = 0; }
+                rp->reserved[0] = 0;
             }
             if (mode == INIT_REINC) { rp->n_reincorporated = 0; rp->n_dropped = 0; }
         }
@@ -467,6 +472,7 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
     __shared__ int s_bin[256];
     __shared__ int s_sel[2][2];
     __shared__ int s_wtot[16];
+    __shared__ int s_odd[2];             // scores next to the threshold without being equal to it; non-finite scores
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int n = sg.n;
@@ -559,7 +565,12 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
         cnt += __popcll(__ballot(t < i1 && s_key[t] >= tau));
     }
     if (lane == 0) s_wtot[wave] = cnt;
+    if (tid == 0) { s_odd[0] = 0; s_odd[1] = 0; }
     __syncthreads();
+    // the threshold as a score again (inverse of ordered_key), for the two counters of the report
+    const float tau_f = __uint_as_float((tau & 0x80000000u) ? (tau & 0x7FFFFFFFu) : ~tau);
+    const double tau_band = 1e-6 * fabs((double)tau_f);
+    int n_near = 0, n_bad = 0;
     int kp = 0, total = 0;
     for (int w = 0; w < 16; ++w) {
         if (w < wave) kp += s_wtot[w];
@@ -570,16 +581,24 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
     for (int i = i0; i < i1; i += 64) {
         const int t = i + lane;
         const bool in = t < i1;
-        const bool keep = in && s_key[t] >= tau;
+        const uint32_t key = in ? s_key[t] : tau;
+        const bool keep = in && key >= tau;
         const uint64_t m = __ballot(keep);
         const int below = __popcll(m & ((1ull << lane) - 1ull));
         if (keep) ko[kp + below] = t;
         else if (in) po[t - (kp + below)] = t;
         kp += __popcll(m);
+        const float f = __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+        n_near += __popcll(__ballot(key != tau && fabs((double)f - (double)tau_f) <= tau_band));
+        n_bad += __popcll(__ballot(in && !isfinite(f)));
     }
+    if (lane == 0 && (n_near | n_bad)) { atomicAdd(&s_odd[0], n_near); atomicAdd(&s_odd[1], n_bad); }
+    __syncthreads();
     if (tid == 0) {
         rep[b].n_kept = total;
         rep[b].n_pruned = n - total;
+        rep[b].score_near_ties = s_odd[0];
+        rep[b].nonfinite_seen = s_odd[1];
     }
     // Scores tied at the threshold: more tokens are kept than the n - m whose bitmap rows and
     // words were cleared along with the key norms; clear what the clustering will use.
@@ -612,7 +631,7 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
     a.keys = (const char*)keys; a.dk = dk;
     a.q = (const char*)q; a.qcols = qcols;
     a.nn = w.nn; a.rinv = w.rinv; a.adj = w.adj; a.qg_part = w.qg_part;
-    a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt;
+    a.status = w.status; a.ident = w.ident; a.near_cnt = w.near_cnt; a.tie_cnt = w.tie_cnt;
     a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
     a.zeros = w.zeros; a.ksplit = w.ksplit;
     a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;

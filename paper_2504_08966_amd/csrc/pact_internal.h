@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include "pact.h"
+#include "pact_measure.h"
 
 namespace pact {
 
@@ -38,6 +39,9 @@ constexpr int GRAM_MAX_WORKGROUPS = 256; // workgroups of 8 wavefronts per sampl
 constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-evaluation, per sample
 constexpr uint32_t NEAR_MIRROR = 0x80000000u;   // flag in a listed pair's row: the pair (col, row) is meant as well
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
+constexpr int RHO_RECHECK_MAX = PACT_MAX_RHO_RECHECK;   // tokens per sample whose density is evaluated again in fp64
+constexpr int RHO_RECHECK_CHUNK = 128;                  // kept tokens per partial sum of such an evaluation
+constexpr int32_t OVERFLOW_NEAR_LIST = 1, OVERFLOW_RHO_RECHECK = 2;   // bits of pact_report.refine_overflow
 
 struct WsLayout {
     size_t qg_part, qg, logits, hnorm, sm_part;        // score
@@ -50,15 +54,21 @@ struct WsLayout {
     size_t preds, heads;                               // [B][n_max][PRED_CAP] u16, [B][n_max] 4 x u16 (count + first 3)
     size_t ksplit;                                     // [total][3][dk rounded up to 8] bf16: fp32 clustering keys as three bf16 parts
     size_t near_list, near_cnt, stat;                  // refine list, counter; [B][workgroups * 8] most negative density exponent seen
+    size_t tie_list, tie_cnt;                          // [B][RHO_RECHECK_MAX] kept positions whose density is re-evaluated; [B][4]: count, ticket
+    size_t rho_fix;                                    // [B][min(RHO_RECHECK_MAX, n_max)][ceil(n_max / RHO_RECHECK_CHUNK)][2] f64 partial sums of those
     size_t offsets, members, big;                      // merge CSR (global row index); ids of the large clusters
     size_t zeros;                                      // 256 zero bytes
     size_t total;
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+__host__ __device__ inline int64_t rho_fix_tokens(int64_t n_max) { return n_max < RHO_RECHECK_MAX ? n_max : RHO_RECHECK_MAX; }
+__host__ __device__ inline int64_t rho_fix_chunks(int64_t n_max) { return (n_max + RHO_RECHECK_CHUNK - 1) / RHO_RECHECK_CHUNK; }
 
-// dk: width of the clustering keys (0 for calls that run no Gram pass)
-inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qcols, int64_t n_q, int64_t dk) {
+// dk: width of the clustering keys (0 for calls that run no Gram pass); k_dt: their type (only
+// fp32 keys have a three-part bf16 copy)
+inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qcols, int64_t n_q, int64_t dk,
+                            int k_dt) {
     WsLayout L;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -85,11 +95,14 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.near_list = take(sizeof(uint32_t) * 2 * B * NEAR_CAP);
     L.near_cnt = take(sizeof(int32_t) * 2 * B);   // per sample: list slots taken, ordered pairs they stand for
     L.stat = take(sizeof(uint32_t) * B * GRAM_MAX_WORKGROUPS * 8);   // one word per wavefront of the density pass
+    L.tie_list = take(sizeof(int32_t) * B * RHO_RECHECK_MAX);
+    L.tie_cnt = take(sizeof(int32_t) * 4 * B);
+    L.rho_fix = take(sizeof(double) * 2 * B * rho_fix_tokens(n_max) * rho_fix_chunks(n_max));
     L.offsets = take(sizeof(int32_t) * (total + B));
     L.members = take(sizeof(int32_t) * total);
     L.big = take(sizeof(int32_t) * total);
     L.zeros = take(256);
-    L.ksplit = take(sizeof(uint16_t) * 3 * total * ((dk + 7) / 8 * 8));   // planes padded to whole 16-byte chunks
+    L.ksplit = take(k_dt == PACT_F32 ? sizeof(uint16_t) * 3 * total * ((dk + 7) / 8 * 8) : 0);   // planes padded to whole 16-byte chunks
     L.total = off;
     return L;
 }
@@ -100,6 +113,7 @@ struct Ws {
     double* nn; float* rinv; int32_t* ident;
     uint64_t* adj; float* cbest; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
+    int32_t* tie_list; int32_t* tie_cnt; double* rho_fix;
     int32_t* offsets; int32_t* members; int32_t* big; uint32_t* zeros; uint16_t* ksplit;
 };
 
@@ -116,6 +130,8 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.preds = (uint16_t*)(p + L.preds); w.heads = (uint2*)(p + L.heads);
     w.cmask = (uint64_t*)(p + L.cmask); w.near_list = (uint32_t*)(p + L.near_list);
     w.near_cnt = (int32_t*)(p + L.near_cnt); w.stat = (uint32_t*)(p + L.stat);
+    w.tie_list = (int32_t*)(p + L.tie_list); w.tie_cnt = (int32_t*)(p + L.tie_cnt);
+    w.rho_fix = (double*)(p + L.rho_fix);
     w.offsets = (int32_t*)(p + L.offsets); w.big = (int32_t*)(p + L.big);
     w.members = (int32_t*)(p + L.members); w.zeros = (uint32_t*)(p + L.zeros);
     w.ksplit = (uint16_t*)(p + L.ksplit);
@@ -175,7 +191,7 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
                          int32_t* cluster_counts, pact_report* rep, bool count_totals,
                          const int32_t* kept_idx, hipStream_t st);
 int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
-                 const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+                 const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
                  hipStream_t st);
 

@@ -292,7 +292,7 @@ int launch_handoff(const Batch& bt, const int32_t* center_idx, const int32_t* cl
 }
 
 int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_dt, int32_t h,
-                 const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
+                 const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
                  hipStream_t st) {
     const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(int);
@@ -304,7 +304,7 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
         raised = lds;
     }
     PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id,
-                      const_cast<pact_report*>(rep), cluster_counts, recount ? 1 : 0, recount ? 0 : 1,
+                      rep, cluster_counts, recount ? 1 : 0, recount ? 0 : 1,
                       w.offsets, w.members, w.big);
     if (h_dt == PACT_BF16)
         return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/pact.h declares; argument
+"""The C-ABI library loads and exports every symbol include/*.h declares; argument
 validation answers before anything touches a GPU.  CPU only (no compute calls)."""
 import ctypes as C
 import os
@@ -12,16 +12,23 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "pact.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b((?:pact|dbdpc)_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b((?:pact|dbdpc)_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
     lib = P.load_library()
     names = declared_functions()
     assert {"pact_score", "pact_prune", "dbdpc_cluster", "pact_reincorporate", "pact_merge",
-            "pact_reduce", "pact_reduce_varlen", "pact_workspace_bytes", "pact_strerror"} <= set(names)
+            "pact_reduce", "pact_reduce_varlen", "pact_workspace_bytes", "pact_strerror",
+            "pact_attention_handoff", "pact_profile_read", "pact_calibration_copy", "pact_plan_workgroups"} <= set(names)
     for name in names:
         assert getattr(lib, name) is not None, name
 
@@ -35,6 +42,33 @@ def test_workspace_size_is_monotone_and_bounded():
     assert P.pact_workspace_bytes(1 << 20, 1, 128, 2, 64) == 0
     assert P.pact_workspace_bytes(729, 65, 128, 2, 64) == 0
     assert P.pact_workspace_bytes(729, 1, 128, 65, 64) == 0
+    # fp32 clustering keys need room for their three-part bf16 copy, bf16 keys do not
+    f32 = P.pact_workspace_bytes(7290, 1, 512, 4, 128, P.PACT_F32)
+    bf16 = P.pact_workspace_bytes(7290, 1, 512, 4, 128, P.PACT_BF16)
+    assert b == f32 and f32 - bf16 >= 7290 * 3 * 512 * 2 and bf16 < 24 << 20
+    assert P.load_library().pact_workspace_bytes(729, 1, 128, 7, 2, 64) == 0        # unknown key type
+
+
+def test_report_layout_matches_the_header():
+    """The binding reads the device-side report as 16 words: their order is the struct's."""
+    text = open(os.path.join(ROOT, "include", "pact.h")).read()
+    body = text[text.index("typedef struct {\n    int32_t n_kept"):text.index("} pact_report;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(?:int32_t|float)\s+([a-z_]+)(?:\[(\d+)\])?;", body)
+    names = [f for f, k in fields if f != "reserved"]
+    assert tuple(names) == P.REPORT_FIELDS
+    assert sum(int(k) if k else 1 for f, k in fields) == 16
+
+
+def test_non_contiguous_tensors_are_refused():
+    import torch
+    from paper_2504_08966_amd import binding
+    t = torch.zeros(8, 8)
+    assert binding._p(t) is not None and binding._p(None) is None
+    with pytest.raises(P.PactError):
+        binding._p(t[:, ::2])
+    with pytest.raises(P.PactError):
+        binding._p(t.t())
 
 
 def test_strerror_covers_all_codes():
