@@ -243,6 +243,19 @@ def test_long_video_fp32_keys(seed):
     print(f"vid_long seed {seed}: rho_rechecked={g['rep']['rho_rechecked']} dc_checked_pairs={g['rep']['dc_checked_pairs']}")
 
 
+def test_long_video_fp32_keys_nothing_pruned():
+    # lambda = 0: all 16384 tokens are clustered, the 16384 x 16384 distance matrix of the workload
+    # list (the oracle holds it in fp64: about 70 s and 11 GB on the host)
+    s = gen.make_sample("vid_long", 0, lam=0.0)
+    d_c = gu.d_c_of(s)
+    g = gu.gpu_reduce(s, d_c)
+    o = oracle_reduce(s, d_c)
+    assert_same(g, o, s, "vid_long, lambda 0")
+    m = gu.manifest()[gu.sample_key(s)]
+    assert g["rep"]["n_kept"] == 16384 == m["q"] and g["rep"]["n_centers"] == m["C"] and _clean(g["rep"])
+    print(f"vid_long lambda 0: C={m['C']} rho_rechecked={g['rep']['rho_rechecked']} dc_checked_pairs={g['rep']['dc_checked_pairs']}")
+
+
 # ------------------------------------------------------------------ degenerate inputs
 
 def _mk(keys, hidden=None, queries=None, name="tiny_f32"):
