@@ -120,7 +120,9 @@ typedef struct {
     int32_t n_centers;         /* C                                         (dbdpc_cluster) */
     int32_t n_reincorporated;  /* pruned tokens recovered by Eq. 8          (pact_reincorporate) */
     int32_t n_dropped;         /* pruned tokens not recovered                (pact_reincorporate) */
-    int32_t rounds;            /* parallel centre rounds run, the last one confirming that no token is left */
+    int32_t rounds;            /* parallel centre rounds run, the last one confirming that no token is left (a
+                                * round may use decisions other wavefronts took earlier in the same round, so
+                                * the count can differ by one or two between runs; the centres cannot) */
     int32_t dc_checked_pairs;  /* ordered kept pairs re-evaluated in fp64 near d_c */
     int32_t dc_near_ties;      /* of those, pairs with |d - d_c| <= 1e-6 (each pair counted twice) */
     int32_t refine_overflow;   /* bit 0: the near-d_c list overflowed (those pairs keep their fp32 decision);
@@ -226,6 +228,26 @@ int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
                 float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
                 int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
                 pact_report* rep, void* ws, size_t ws_bytes, void* stream);
+
+/* pact_reduce for callers that cannot allocate a workspace or pass one in: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation calls.  Arguments, outputs and
+ * results are those of pact_reduce; the scratch is an array of PACT_STATIC_SCRATCH_BYTES bytes
+ * that is part of the library's device code (each GPU the library runs on holds its own copy
+ * until the process ends).  The call makes no allocation of any kind.
+ *  - A call that would need more scratch than that (pact_workspace_bytes(n, 1, n_kv*d_h, k_dt,
+ *    n_q, d_h) tells) returns PACT_ERR_WORKSPACE; every single image of up to 8748 tokens with
+ *    512-wide bf16 keys and 28 query heads fits.
+ *  - All calls on one GPU share that GPU's array: they must be ordered on one stream (or
+ *    otherwise serialised); calls that overlap on one GPU race.  The array keeps the last call's
+ *    contents, and like any workspace it is initialised by each call as far as the call reads it. */
+#define PACT_STATIC_SCRATCH_BYTES (48u << 20)
+int pact_reduce_static(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+                       const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                       const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                       const pact_params* p,
+                       float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                       int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                       pact_report* rep, void* stream);
 
 /* Alg. 3 for `batch` independent samples whose tokens are concatenated along dim 0.
  *   cu_seqlens host int32 [batch+1], cu_seqlens[0] = 0, strictly increasing; sample b owns

@@ -77,6 +77,9 @@ def load_library():
     lib.pact_reduce.restype = C.c_int
     lib.pact_reduce.argtypes = [vp, C.c_int, i32, i32, vp, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
                                 C.POINTER(_Params), vp, vp, vp, vp, vp, vp, C.c_int, vp, vp, vp, sz, vp]
+    lib.pact_reduce_static.restype = C.c_int
+    lib.pact_reduce_static.argtypes = [vp, C.c_int, i32, i32, vp, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
+                                       C.POINTER(_Params), vp, vp, vp, vp, vp, vp, C.c_int, vp, vp, vp]
     lib.pact_reduce_varlen.restype = C.c_int
     lib.pact_reduce_varlen.argtypes = [vp, C.c_int, i32, vp, vp, C.c_int, i32, i32, vp, C.c_int, i32, i32,
                                        C.POINTER(i32), i32, C.POINTER(_Params), vp, vp, vp, vp, vp, vp,
@@ -245,6 +248,24 @@ def pact_reduce(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int, params
         _p(o["center_idx"]), _p(o["cluster_id"]), _p(o["merged"]), _out_dt(o["merged"].dtype),
         _p(o["cluster_counts"]), _p(o["rep"]), _p(ws), ws.numel(), _stream()), "pact_reduce")
     return o
+
+
+def pact_reduce_static(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int, params: PactParams, out):
+    """pact_reduce on the library's own scratch array: no workspace argument, and nothing is
+    allocated here either - `out` is a dict of output tensors as pact_reduce returns it."""
+    n, h = hidden.shape
+    pc = params.c()
+    _check(load_library().pact_reduce_static(
+        _p(hidden), _dt(hidden), n, h, _p(keys_pre), _p(keys), _dt(keys), n_kv, d_h, _p(q), _dt(q),
+        q.shape[0], n_q, C.byref(pc), _p(out["scores"]), _p(out["kept_idx"]), _p(out["pruned_idx"]),
+        _p(out["center_idx"]), _p(out["cluster_id"]), _p(out["merged"]), _out_dt(out["merged"].dtype),
+        _p(out["cluster_counts"]), _p(out["rep"]), _stream()), "pact_reduce_static")
+    return out
+
+
+def new_outputs(total: int, h: int, batch: int = 1, out_dtype=torch.float32, device="cuda"):
+    """Output tensors of pact_reduce / pact_reduce_varlen, sized for the worst case."""
+    return _alloc_outputs(total, h, batch, out_dtype, device)
 
 
 def pact_reduce_varlen(hidden, keys_pre, keys, q, n_kv: int, d_h: int, n_q: int, cu_seqlens, params,

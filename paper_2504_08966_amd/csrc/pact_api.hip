@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "pact_internal.h"
@@ -85,6 +86,31 @@ static void fill_single(Batch& bt, int32_t n, const pact_params& p) {
 static pact_params default_params() {
     pact_params p; p.lambda = 0.0f; p.d_c = 0.0f; p.d_n = 2.0f; p.alpha = 1.5f; p.fallback_T = 10; p.flags = 0;
     return p;
+}
+
+// ------------------------------------------------------------------------------ own scratch
+// Workspace of pact_reduce_static: one array per GPU, part of the loaded code object (no
+// allocation call ever made for it), kept until the process ends.  `scratch` is the host-side
+// handle of the symbol, not a device address: the address on the current device comes from
+// hipGetSymbolAddress, once per device, and is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[PACT_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_addr[MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+static int own_scratch_address(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return PACT_ERR_NOGPU; }
+    if (dev < 0 || dev >= MAX_DEVICES) return PACT_ERR_NOGPU;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return PACT_ERR_HIP; }
+        if ((uintptr_t)ptr & 255u) return PACT_ERR_HIP;
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return PACT_OK;
 }
 
 struct ReduceIO {
@@ -289,13 +315,15 @@ static int validate_reduce_common(const void* hidden, pact_dtype h_dt, int32_t h
     return PACT_OK;
 }
 
-int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
-                const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
-                const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
-                const pact_params* p,
-                float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
-                int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
-                pact_report* rep, void* ws, size_t ws_bytes, void* stream) {
+// pact_reduce and pact_reduce_static: the same checks and the same launches; `ws` is the
+// caller's workspace, or NULL for the library's own scratch array.
+static int reduce_single(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+                         const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                         const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                         const pact_params* p,
+                         float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                         int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                         pact_report* rep, void* ws, size_t ws_bytes, bool own_scratch, void* stream) {
     if (!p) return PACT_ERR_NULL;
     int rc = validate_reduce_common(hidden, h_dt, h, keys_pre, keys, k_dt, n_kv, d_h, q, q_dt, n_q, scores,
                                     kept_idx, pruned_idx, center_idx, cluster_id, merged, out_dt,
@@ -306,14 +334,41 @@ int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
     if ((rc = check_params(p->lambda, p->d_c, p->d_n, p->alpha))) return rc;
     if (p->fallback_T < 0) return PACT_ERR_PARAM;
     const WsLayout L = make_layout(n, 1, n, (int64_t)n_q * d_h, n_q, (int64_t)n_kv * d_h, k_dt);
-    if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
+    if (own_scratch) {
+        if (L.total > (size_t)PACT_STATIC_SCRATCH_BYTES) return PACT_ERR_WORKSPACE;
+    } else if ((rc = check_ws(ws, ws_bytes, L.total))) return rc;
     if ((rc = check_device())) return rc;
+    if (own_scratch && (rc = own_scratch_address(&ws))) return rc;
     Batch bt;
     fill_single(bt, n, *p);
     const Ws w = resolve(ws, L);
     ReduceIO io{hidden, h_dt, h, keys_pre, keys, k_dt, n_kv, d_h, q, q_dt, q_rows == n ? 1 : 0, n_q,
                 scores, kept_idx, pruned_idx, center_idx, cluster_id, merged, out_dt, cluster_counts, rep};
     return run_reduce(bt, w, io, (hipStream_t)stream);
+}
+
+int pact_reduce(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+                const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                const pact_params* p,
+                float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                pact_report* rep, void* ws, size_t ws_bytes, void* stream) {
+    return reduce_single(hidden, h_dt, n, h, keys_pre, keys, k_dt, n_kv, d_h, q, q_dt, q_rows, n_q, p, scores,
+                         kept_idx, pruned_idx, center_idx, cluster_id, merged, out_dt, cluster_counts, rep,
+                         ws, ws_bytes, false, stream);
+}
+
+int pact_reduce_static(const void* hidden, pact_dtype h_dt, int32_t n, int32_t h,
+                       const void* keys_pre, const void* keys, pact_dtype k_dt, int32_t n_kv, int32_t d_h,
+                       const void* q, pact_dtype q_dt, int32_t q_rows, int32_t n_q,
+                       const pact_params* p,
+                       float* scores, int32_t* kept_idx, int32_t* pruned_idx, int32_t* center_idx,
+                       int32_t* cluster_id, void* merged, pact_dtype out_dt, int32_t* cluster_counts,
+                       pact_report* rep, void* stream) {
+    return reduce_single(hidden, h_dt, n, h, keys_pre, keys, k_dt, n_kv, d_h, q, q_dt, q_rows, n_q, p, scores,
+                         kept_idx, pruned_idx, center_idx, cluster_id, merged, out_dt, cluster_counts, rep,
+                         nullptr, 0, true, stream);
 }
 
 int pact_reduce_varlen(const void* hidden, pact_dtype h_dt, int32_t h,
