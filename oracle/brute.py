@@ -80,39 +80,32 @@ def centers_fixed_point_enumeration(D, order, d_c) -> list:
 
 
 def recursive_centers(D, rho, d_c, T) -> np.ndarray:
-    """Recursive centre identification (appendix D, Alg. 4), read as follows: rank_i is
-    the position of i in the density order (0 = densest); delta_i is the minimum
-    distance from i to the *remaining* vectors that precede it in that order (+inf if
-    none); every remaining i with delta_i > d_c becomes a centre; the new centres and
-    every remaining vector within d_c (<=) of one of them leave the set; when a pass
-    finds fewer than T new centres the rest is finished by Alg. 2's sequential loop
-    over the remaining vectors in density order, testing against all centres so far."""
+    """Centres by peeling (the scheme appendix D proves equal to Alg. 2's loop), stated with
+    sets rather than as the printed procedure.  Let `before(i)` be the vectors that precede i
+    in the density order and N(i) the vectors within d_c of i.  While vectors remain:
+      * a remaining vector with no remaining vector of before(i) in N(i) has nothing left that
+        could ever exclude it: all such vectors become centres together;
+      * the new centres and every remaining vector in the N(.) of one of them leave;
+      * once a peel yields fewer than T centres, what remains is taken one vector at a time in
+        density order (a centre iff no centre so far is in its N(.)).
+    T = 0 never leaves the peeling, T = infinity leaves it after the first peel."""
     D = np.asarray(D, dtype=np.float64)
     q = D.shape[0]
     order = order_by_definition(rho)
-    rank = np.empty(q, dtype=np.int64)
-    rank[order] = np.arange(q)
-    live = np.ones(q, dtype=bool)
-    centers = []
-    while live.any():
-        idx = np.flatnonzero(live)
-        new = []
-        for i in idx:
-            higher = idx[rank[idx] < rank[i]]
-            delta = D[i, higher].min() if higher.size else math.inf
-            if delta > d_c:
-                new.append(int(i))
-        centers.extend(new)
-        for i in new:
-            live[i] = False
-        for k in idx:
-            if live[k] and any(D[i, k] <= d_c for i in new):
-                live[k] = False
-        if len(new) < T:
-            rest = sorted(np.flatnonzero(live), key=lambda i: rank[i])
-            for i in rest:
-                if not centers or min(D[i, s] for s in centers) > d_c:
-                    centers.append(int(i))
+    position = {int(i): k for k, i in enumerate(order)}
+    near = [set(int(j) for j in np.flatnonzero(D[i] <= d_c)) - {i} for i in range(q)]
+    before = [set(int(j) for j in range(q) if position[j] < position[i]) for i in range(q)]
+    remaining = set(range(q))
+    centers = set()
+    while remaining:
+        peel = {i for i in remaining if not (near[i] & before[i] & remaining)}
+        centers |= peel
+        remaining -= peel
+        remaining -= set().union(*(near[i] for i in peel)) if peel else set()
+        if len(peel) < T:
+            for i in sorted(remaining, key=position.get):
+                if not (near[i] & centers):
+                    centers.add(i)
             break
     return np.array(sorted(centers), dtype=np.int64)
 

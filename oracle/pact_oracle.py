@@ -230,6 +230,14 @@ def merge(H, cluster_id, n_clusters: int):
     return merged, counts
 
 
+def centre_representatives(H, center_idx) -> np.ndarray:
+    """The "no merging" variant of the ablation study (Sec. "Ablation study": the centre of each
+    cluster stands for the cluster instead of the mean of its members): row s of the reduced
+    set is the hidden state of centre s, unchanged."""
+    H = _f64(H)
+    return H[np.asarray(center_idx, dtype=np.int64)].copy()
+
+
 def max_pairwise_distance(U) -> float:
     """The statistic Sec. "Selecting the layer L" (and the figure on the maximum distance
     between keys) looks at: the largest Eq. 5 distance between two of the vectors; 0 for a
@@ -250,7 +258,7 @@ def attention_handoff(center_idx, counts, positions=None):
 
 
 def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.float32,
-                use_norm: bool = True, use_query: bool = True):
+                use_norm: bool = True, use_query: bool = True, merge_clusters: bool = True):
     """Alg. 3: EUTI on (H, K_pre, Q), DBDPC on the flattened K_post of the important
     tokens, recovery of unimportant tokens, merge, position = centre index.
 
@@ -260,7 +268,8 @@ def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.flo
     here first.  The scores also cross it as float32, so the percentile split is taken
     on the float32-rounded scores (score_dtype), the precision that decision is made
     in on both sides.  use_norm / use_query select the two ablations of Eq. 2 (see
-    euti_scores).
+    euti_scores); merge_clusters=False is the "no merging" variant (centre_representatives):
+    clusters, recovery and counts as usual, the reduced rows are the centres' own.
     """
     lam, d_c, d_n, alpha = (float(np.float32(v)) for v in (lam, d_c, d_n, alpha))
     H = _f64(H)
@@ -283,6 +292,8 @@ def pact_reduce(H, K_pre, Q, K_post, lam, d_c, d_n, alpha, *, score_dtype=np.flo
     cluster_id[pruned] = rl
 
     merged, counts = merge(H, cluster_id, center_idx.size)
+    if not merge_clusters:
+        merged = centre_representatives(H, center_idx)
     return dict(
         scores=scores, scores_dec=s_dec, tau=tau, kept_idx=kept, pruned_idx=pruned,
         rho=cl["rho"], order=cl["order"], D_kept=cl["D"], D_pruned_centers=D_pc,

@@ -33,17 +33,6 @@
 
 namespace pact {
 
-// Optional in-kernel phase clock (build with -DPACT_GRAM_STAMPS): thread 0 of every workgroup
-// of sample 0 records the 100 MHz wall clock at five points of its last tile (and the shader
-// clock counter around the slice loop, slots 5 and 6).
-#ifdef PACT_GRAM_STAMPS
-__device__ unsigned long long g_gram_stamps[2][512][8];
-#define PACT_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.y == 0) { g_gram_stamps[MODE][blockIdx.x][k] = wall_clock64(); \
-        if ((k) == 1 || (k) == 2) g_gram_stamps[MODE][blockIdx.x][4 + (k)] = clock64(); } } while (0)
-#else
-#define PACT_STAMP(k) do { } while (0)
-#endif
-
 enum { MODE_DENSITY = 0, MODE_CAND = 1 };
 
 struct GramArgs {
@@ -203,7 +192,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             ga.stat[((size_t)b * ga.stat_wgs + wg) * 8 + (threadIdx.x >> 6)] = 0u;
         return;
     }
-    PACT_STAMP(0);
     const int tilesR = (nA + TILE_R - 1) / TILE_R;
     const int tilesC = (nB + TILE_C - 1) / TILE_C;
 
@@ -375,8 +363,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 }
             }
         };
-
-        PACT_STAMP(1);
         f32x16_t acc[MI][2];
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -435,7 +421,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
                 }
             }
         }
-        PACT_STAMP(2);
         // LDS the epilogue may use for its buffers: the ring stage that the last slice did not
         // occupy; where the two halves of the ring alternate independently the last slice may
         // occupy halves of both, so there every wavefront finishes its reads first.
@@ -695,7 +680,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             }
         }
         }
-        PACT_STAMP(3);
         if (MODE == MODE_DENSITY && nearN > 0) flush_near();
 
         if (MODE == MODE_DENSITY) {
@@ -731,7 +715,6 @@ __global__ __launch_bounds__(512, 2) void gram_kernel(Batch bt, GramArgs ga) {
             if (gRow < nA && colBase + pair * 128 < nB)
                 ga.rho_part[((size_t)b * bt.W + colBase / GRAM_RHO_ROWS + pair) * bt.n_max + gRow] = v;
         }
-        PACT_STAMP(4);
         if (tl + t_step < l_hi) {
             // the ring and sRinv are rewritten by the next tile: every wavefront must be done with
             // them (and the slice loop's vmcnt arithmetic assumes nothing older is outstanding)
@@ -933,10 +916,5 @@ int plan_gram_workgroups(const int32_t* tiles, int32_t batch, uint16_t* wg_map, 
     return PACT_OK;
 }
 
-#ifdef PACT_GRAM_STAMPS
-extern "C" int pact_debug_stamps(unsigned long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_gram_stamps), sizeof(g_gram_stamps));
-}
-#endif
 
 }  // namespace pact

@@ -120,12 +120,22 @@ def test_argument_validation_is_host_side():
     assert lib.pact_merge(fake, 1, 16, 60, fake, None, fake, 0, fake, 0, fake, fake, ws_bytes, None) == ALIGN
     # pact_reduce / pact_reduce_varlen
     prm = P.PactParams(0.45, 0.02).c()
+    bad_prm = P.PactParams(0.45, 0.02, d_n=-1.0).c()
     rd = lambda p, **k: lib.pact_reduce(fake, 1, k.get("n", 16), 64, fake, k.get("keys", fake), 1, 2, 8, fake,
                                         1, k.get("q_rows", 16), 2, p, fake, fake, fake, fake, fake,
                                         k.get("merged", fake), 0, fake, fake, fake, k.get("ws_bytes", ws_bytes), None)
     assert rd(None) == NULL and rd(C.byref(prm), keys=None) == NULL and rd(C.byref(prm), merged=None) == NULL
     assert rd(C.byref(prm), n=0) == SHAPE and rd(C.byref(prm), q_rows=3) == SHAPE
     assert rd(C.byref(prm), ws_bytes=64) == WS
+    # the entry point that brings its own scratch: the same checks, and a size limit instead of a workspace check
+    st = lambda p, **k: lib.pact_reduce_static(fake, 1, k.get("n", 16), k.get("h", 64), fake, k.get("keys", fake),
+                                               k.get("k_dt", 1), k.get("n_kv", 2), k.get("d_h", 8), fake, 1,
+                                               k.get("n", 16), k.get("n_q", 2), p, fake, fake, fake, fake, fake, fake, 0,
+                                               fake, fake, None)
+    assert st(None) == NULL and st(C.byref(prm), keys=None) == NULL and st(C.byref(bad_prm)) == PARAM
+    assert st(C.byref(prm), n=0) == SHAPE
+    assert st(C.byref(prm), n=16384, h=3584, k_dt=0, n_kv=4, d_h=128, n_q=4) == WS  # 136 MiB of scratch: refused
+    assert P.pact_workspace_bytes(8748, 1, 512, 28, 128, P.PACT_BF16) <= 48 << 20
     bad = P.PactParams(0.45, 0.02, d_n=-1.0).c()
     assert rd(C.byref(bad)) == PARAM
     cu_bad = (C.c_int32 * 3)(0, 8, 8)          # empty second sample

@@ -180,7 +180,12 @@ def test_no_merge_flag_returns_centre_rows():
     s = gen.make_sample("tiny_f32", 8)
     d_c = gu.d_c_of(s)
     g = gu.gpu_reduce(s, d_c, flags=P.PACT_FLAG_NO_MERGE)
-    assert np.array_equal(g["merged"], s.hidden[g["center_idx"]])
+    o = oracle_reduce(s, d_c, merge_clusters=False)
+    assert_same(g, o, s, "no merging")
+    assert np.array_equal(g["merged"], o["merged"])              # the centres' rows, bit for bit
+    s2 = gen.make_sample("tiny_bf16", 8)
+    g2 = gu.gpu_reduce(s2, gu.d_c_of(s2), flags=P.PACT_FLAG_NO_MERGE, out_dtype=torch.bfloat16)
+    assert np.array_equal(g2["merged"], oracle_reduce(s2, gu.d_c_of(s2), merge_clusters=False)["merged"])
 
 
 def test_two_runs_are_bitwise_identical():

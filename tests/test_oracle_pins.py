@@ -363,6 +363,28 @@ def test_merge_identities():
     assert np.array_equal(merged[8], H[7].astype(np.float64))
 
 
+def test_no_merging_variant_keeps_the_centre_rows():
+    # the ablation that lets the centre stand for its cluster: rows of H at the centres, bit for bit,
+    # in the order of the centres; everything but the rows is the full method's
+    r = rng(33)
+    H = r.normal(size=(20, 5)).astype(np.float32)
+    centres = np.array([2, 7, 11, 19])
+    rows = po.centre_representatives(H, centres)
+    assert rows.shape == (4, 5) and all(np.array_equal(rows[k], H[c].astype(np.float64)) for k, c in enumerate(centres))
+    rows[0, 0] = 99.0
+    assert H[2, 0] != 99.0                                     # a copy, not a view
+    s = gen.make_sample("tiny_f32", 4)
+    d_c = 0.02
+    a = po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5)
+    b = po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5, merge_clusters=False)
+    for k in ("kept_idx", "center_idx", "cluster_id", "counts"):
+        assert np.array_equal(a[k], b[k])
+    assert np.array_equal(b["merged"], s.hidden[b["center_idx"]].astype(np.float64))
+    single = a["counts"] == 1                                  # a cluster of one: mean and centre row coincide
+    assert single.any() and np.array_equal(a["merged"][single], b["merged"][single])
+    assert not np.array_equal(a["merged"][~single], b["merged"][~single])
+
+
 @pytest.mark.parametrize("name,seed", [("tiny_f32", 5), ("tiny_bf16", 6)])
 def test_pact_pipeline_conservation_and_limits(name, seed):
     s = gen.make_sample(name, seed)
