@@ -422,13 +422,14 @@ __device__ __forceinline__ int preds_of_row(int p, int q, const double* r, const
 }
 
 // grid (ceil(n_max/4), B), block 256: one wavefront per kept token.  Tokens with a neighbour
-// inside the band are appended to the sample's list (tie_cnt[4b] counts them, also past the
-// list's end: the re-evaluation is then skipped and reported).
+// inside the band are appended to the sample's list, as position | token << 16 (tie_cnt[4b]
+// counts them, also past the list's end: the re-evaluation is then skipped and reported).
 __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_report* __restrict__ rep,
                                                           const uint64_t* __restrict__ adj,
                                                           const double* __restrict__ rho,
                                                           uint16_t* __restrict__ preds,
                                                           uint2* __restrict__ heads,
+                                                          const int32_t* __restrict__ idx,
                                                           int32_t* __restrict__ tie_list,
                                                           int32_t* __restrict__ tie_cnt) {
     const int b = blockIdx.y;
@@ -442,9 +443,48 @@ __global__ __launch_bounds__(256) void build_preds_kernel(Batch bt, const pact_r
                                        (uint16_t*)(heads + (size_t)b * bt.n_max + p), s_nb[threadIdx.x >> 6], lane,
                                        recheck_band2(bt.s[b].d_n));
     if (odd && lane == 0) {
+        // position and token in one word (both below 2^15), so that the re-evaluation finds the
+        // token's key without another look-up
+        static_assert(PACT_MAX_TOKENS <= 32768, "two 15-bit numbers per list entry");
         const int slot = atomicAdd(&tie_cnt[4 * b], 1);
-        if (slot < RHO_RECHECK_MAX) tie_list[(size_t)b * RHO_RECHECK_MAX + slot] = p;
+        if (slot < RHO_RECHECK_MAX) tie_list[(size_t)b * RHO_RECHECK_MAX + slot] = p | (idx[bt.s[b].base + p] << 16);
     }
+}
+
+// Set-up step of the kernel that runs the centre rounds, for a sample with listed tokens: their
+// fp64 densities from the partial sums (one wavefront per token), written over the fp32-term
+// ones; then their predecessor lists again from the new values.  All wavefronts of the workgroup
+// call it; `nb` is a per-wavefront buffer of PREDS_SPREAD entries.
+__device__ __forceinline__ void finish_rechecked_densities(const Batch& bt, int b, int q, int T, int wave, int nwaves, int lane,
+                                                           const int32_t* list, const double* part_b, double* rho_b,
+                                                           double* rho_opt_b, const uint64_t* adj, uint16_t* preds,
+                                                           uint2* heads, volatile uint16_t* nb, pact_report* rep) {
+    const int nch = (q + RHO_RECHECK_CHUNK - 1) / RHO_RECHECK_CHUNK;
+    for (int t = wave; t < T; t += nwaves) {
+        double ah = 0.0, al = 0.0;
+        for (int c = lane; c < nch; c += 64) {
+            const double2 v = *(const double2*)(part_b + ((size_t)t * nch + c) * 2);
+            ah += v.x;
+            al += v.y;
+        }
+        const double acc = wave_sum_f64(ah) + wave_sum_f64(al);
+        if (lane == 0) {
+            const int p = min(list[t] & 0xFFFF, q - 1);
+            rho_b[p] = acc;
+            if (rho_opt_b) rho_opt_b[p] = acc;
+        }
+    }
+    __syncthreads();                                   // (the values are read back by this workgroup only)
+    int fine = 0;
+    for (int t = wave; t < T; t += nwaves) {
+        const int p = min(list[t] & 0xFFFF, q - 1);
+        fine += preds_of_row<false>(p, q, rho_b, adj + ((size_t)b * bt.n_max + p) * bt.W,
+                                    preds + ((size_t)b * bt.n_max + p) * PRED_CAP,
+                                    (uint16_t*)(heads + (size_t)b * bt.n_max + p), nb, lane, 0.0);
+    }
+    if (lane == 0 && fine) atomicAdd(&rep[b].rho_near_ties, fine);
+    if (wave == 0 && lane == 0) rep[b].rho_rechecked = T;
+    __syncthreads();
 }
 
 // Status checks of the list positions 1..15 of a predecessor record held in two 16-byte
@@ -482,14 +522,17 @@ __device__ __forceinline__ bool check_pending15(const uint4& v0, const uint4& v1
 constexpr int RESOLVE_CACHED = 4;
 __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_report* rep,
                                                               const uint64_t* __restrict__ adj,
-                                                              const double* __restrict__ rho,
-                                                              const uint16_t* __restrict__ preds,
-                                                              const uint2* __restrict__ heads,
+                                                              double* rho, double* rho_opt,
+                                                              uint16_t* preds, uint2* heads,
                                                               const int32_t* __restrict__ idx,
+                                                              const int32_t* __restrict__ tie_list,
+                                                              const int32_t* __restrict__ tie_cnt,
+                                                              const double* __restrict__ rho_fix,
                                                               uint32_t* status, int32_t* cnum,
                                                               uint64_t* cmask, int32_t* center_idx) {
     extern __shared__ unsigned char s_raw[];
     __shared__ int s_flag[3], s_nlong, s_nover;
+    __shared__ uint16_t s_nb[16][PREDS_SPREAD];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int tid = threadIdx.x;
@@ -503,7 +546,21 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         const int p = tid + 1024 * k;
         h[k] = (p < bt.n_max) ? heads[(size_t)b * bt.n_max + p] : make_uint2(0, 0);
     }
+    const int T = tie_cnt[4 * b];
     const int q = clamp_count(rep[b].n_kept, sg.n);
+    if (T > 0 && T <= RHO_RECHECK_MAX) {
+        // tokens whose density was evaluated again in fp64: finish those sums and rebuild the
+        // lists they decide, then fetch the heads again (some of them are new)
+        finish_rechecked_densities(bt, b, q, T, wave, 16, lane, tie_list + (size_t)b * RHO_RECHECK_MAX,
+                                   rho_fix + (size_t)b * 2 * rho_fix_tokens(bt.n_max) * rho_fix_chunks(bt.n_max),
+                                   rho + (size_t)b * bt.n_max, rho_opt ? rho_opt + sg.base : nullptr, adj, preds, heads,
+                                   s_nb[wave], rep);
+#pragma unroll
+        for (int k = 0; k < RESOLVE_CACHED; ++k) {
+            const int p = tid + 1024 * k;
+            h[k] = (p < bt.n_max) ? heads[(size_t)b * bt.n_max + p] : make_uint2(0, 0);
+        }
+    }
     const int qpad = (bt.n_max + 63) / 64 * 64;
     lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64]
     lds_u16* s_list = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
@@ -907,40 +964,58 @@ __device__ __forceinline__ void group_dot64_with_norm(const char* mine, const ch
     nn_other = acc2;
 }
 
+// The same for rows whose 16-byte chunks the lanes already hold (chunks part, part + 16, .. of rows
+// of at most 64 chunks): same order of operations as group_dot64_with_norm.
+template <int DT>
+__device__ __forceinline__ void chunk_dots64(const uint4 (&va)[4], const uint4 (&vb)[4], int nchunk, int part,
+                                             double& dot, double& nn_other) {
+    constexpr int EPL = Elem<DT>::EPL;
+    double acc = 0.0, acc2 = 0.0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (part + 16 * u < nchunk) {
+            double a[8], x[8];
+            Elem<DT>::widen(va[u], a);
+            Elem<DT>::widen(vb[u], x);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) { acc = fma(a[i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
+        }
+    }
+#pragma unroll
+    for (int sft = 1; sft <= 8; sft <<= 1) { acc += __shfl_xor(acc, sft, 64); acc2 += __shfl_xor(acc2, sft, 64); }
+    dot = acc;
+    nn_other = acc2;
+}
+
 // Densities of the listed tokens again, entirely in fp64 (Eq. 5 and Eq. 6 as they are written:
 // dot product, two norms - recomputed here by the routine that computes the dot product, so
 // that a copy of the token is at distance exactly 0 -, one division, one exponential per pair,
-// the term of the token itself exactly 1), then the predecessor lists of those tokens again
-// from the new values.
+// the term of the token itself exactly 1).  This kernel leaves partial sums; the kernel that
+// runs the centre rounds adds them up and rebuilds the predecessor lists of those tokens
+// (finish_rechecked_densities below) before it looks at any list.
 // Work items are (listed token, chunk of RHO_RECHECK_CHUNK kept tokens): one workgroup per item
-// and turn, 16 lanes per pair; a chunk's terms are summed in a fixed order, a token's chunks
-// likewise.  The sum itself is exact, hence the same in any order and for any two tokens with
-// the same terms (two tokens at equal distances from everything else tie exactly, as they do
-// for a correctly rounded sum, and the index decides): every term t in (0, 1] is split into
-// hi = t rounded to a multiple of 2^-30 and lo = t - hi; sums of at most 32768 such hi, and of
-// such lo as long as t >= 2^-17 (d_n >= 0.17), fit the 53 bits of an fp64 whatever their order,
-// and the density is hi_total + lo_total, rounded once.  The workgroup that finishes last (one
-// counter per sample) adds the chunks up and rebuilds the lists; nobody waits for anybody.
+// and turn, 16 lanes per pair.  The sums are exact, hence the same in any order and for any two
+// tokens with the same terms (two tokens at equal distances from everything else tie exactly, as
+// they do for a correctly rounded sum, and the index decides): every term t in (0, 1] is split
+// into hi = t rounded to a multiple of 2^-30 and lo = t - hi; sums of at most 32768 such hi, and
+// of such lo as long as t >= 2^-17 (d_n >= 0.17), fit the 53 bits of an fp64 whatever their
+// order, and the density is hi_total + lo_total, rounded once.
 // grid (blocks per sample, B), block 256.
 template <int DT>
 __global__ __launch_bounds__(256) void rho_recheck_kernel(Batch bt, const char* keys, int dk, const int32_t* idx,
-                                                           const uint64_t* adj, pact_report* rep,
-                                                           double* rho, double* rho_opt, double* part,
-                                                           const int32_t* tie_list, int32_t* tie_cnt,
-                                                           uint16_t* preds, uint2* heads) {
+                                                           pact_report* rep, double* part,
+                                                           const int32_t* tie_list, const int32_t* tie_cnt) {
     __shared__ double s_hi[RHO_RECHECK_CHUNK], s_lo[RHO_RECHECK_CHUNK];
-    __shared__ uint16_t s_nb[4][PREDS_SPREAD];
-    __shared__ int s_last;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int T = tie_cnt[4 * b];                      // (the same for every workgroup of the sample)
+    const int q = clamp_count(rep[b].n_kept, sg.n);
     if (T <= 0) return;
     if (T > RHO_RECHECK_MAX) {
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&rep[b].refine_overflow, OVERFLOW_RHO_RECHECK);
         return;
     }
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q = clamp_count(rep[b].n_kept, sg.n);
+    const int tid = threadIdx.x, lane = tid & 63;
     const int nch = (q + RHO_RECHECK_CHUNK - 1) / RHO_RECHECK_CHUNK;
     const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
     const int nchunk = (int)(row_bytes / 16);
@@ -948,68 +1023,66 @@ __global__ __launch_bounds__(256) void rho_recheck_kernel(Batch bt, const char* 
     const int32_t* ix = idx + sg.base;
     const int32_t* list = tie_list + (size_t)b * RHO_RECHECK_MAX;
     double* part_b = part + (size_t)b * 2 * rho_fix_tokens(bt.n_max) * rho_fix_chunks(bt.n_max);   // [T][nch][2], T <= q <= n_max
-    double* rho_b = rho + (size_t)b * bt.n_max;
     const double d_n = (double)sg.d_n;
     const int g = tid >> 4, part16 = tid & 15;
+    constexpr int PER = RHO_RECHECK_CHUNK / 16;          // pairs per group of 16 lanes and item
+    static_assert(PER == 4, "a group's four rows are requested together");
     for (int item = blockIdx.x; item < T * nch; item += gridDim.x) {
         const int t = item / nch, c = item - t * nch;
-        const int p = min(max(list[t], 0), q - 1);
-        const int tok = ix[p];
+        // this group's kept tokens: lane s of the group fetches the s-th one's token (one trip for all)
+        const int pk_mine = c * RHO_RECHECK_CHUNK + (part16 & (PER - 1)) * 16 + g;
+        const int tk_mine = ix[min(pk_mine, q - 1)];
+        const int ent = list[t];
+        const int p = min(ent & 0xFFFF, q - 1), tok = min(max(ent >> 16, 0), sg.n - 1);
         const char* mine = kb + (size_t)tok * row_bytes;
-        double nnp, dot, nnk;
-        group_dot64_with_norm<DT>(mine, mine, nchunk, part16, dot, nnp);
+        if (nchunk <= 64) {
+            // rows of at most 1 KB: a lane holds its (at most four) 16-byte chunks of the token's row and
+            // those of the group's four other rows, all requested together
+            uint4 vm[4], vk[PER][4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) vm[u] = *(const uint4*)(mine + (size_t)min(part16 + 16 * u, nchunk - 1) * 16);
+#pragma unroll
+            for (int s = 0; s < PER; ++s) {
+                const int tk = __shfl(tk_mine, (lane & ~15) + s, 64);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    vk[s][u] = *(const uint4*)(kb + (size_t)tk * row_bytes + (size_t)min(part16 + 16 * u, nchunk - 1) * 16);
+            }
+            double nnp, dd;
+            chunk_dots64<DT>(vm, vm, nchunk, part16, dd, nnp);
+#pragma unroll
+            for (int s = 0; s < PER; ++s) {
+                const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
+                double dot, nnk;
+                chunk_dots64<DT>(vm, vk[s], nchunk, part16, dot, nnk);
+                const double d = cos_dist64(dot, nnp, nnk);
+                const double term = pk >= q ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
+                const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
+                if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
+            }
+        } else {
+            double nnp, dot, nnk;
+            group_dot64_with_norm<DT>(mine, mine, nchunk, part16, dot, nnp);
 #pragma unroll 1
-        for (int s = 0; s < RHO_RECHECK_CHUNK / 16; ++s) {
-            const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
-            const bool valid = pk < q;
-            const int tk = ix[valid ? pk : p];
-            group_dot64_with_norm<DT>(mine, kb + (size_t)tk * row_bytes, nchunk, part16, dot, nnk);
-            const double d = cos_dist64(dot, nnp, nnk);
-            const double term = !valid ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
-            const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
-            if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
+            for (int s = 0; s < PER; ++s) {
+                const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
+                const int tk = __shfl(tk_mine, (lane & ~15) + s, 64);
+                group_dot64_with_norm<DT>(mine, kb + (size_t)tk * row_bytes, nchunk, part16, dot, nnk);
+                const double d = cos_dist64(dot, nnp, nnk);
+                const double term = pk >= q ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
+                const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
+                if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
+            }
         }
         __syncthreads();
-        if (wave == 0) {
-            static_assert(RHO_RECHECK_CHUNK == 128, "two terms per lane");
-            const double vh = wave_sum_f64(s_hi[lane] + s_hi[lane + 64]);
-            const double vl = wave_sum_f64(s_lo[lane] + s_lo[lane + 64]);
+        if (tid < 64) {
+            static_assert(RHO_RECHECK_CHUNK == 64, "one term per lane");
+            const double vh = wave_sum_f64(s_hi[lane]);
+            const double vl = wave_sum_f64(s_lo[lane]);
             if (lane == 0) *(double2*)(part_b + ((size_t)t * nch + c) * 2) = make_double2(vh, vl);
         }
         __syncthreads();
     }
-    // the last workgroup of the sample to get here finishes the job
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) s_last = atomicAdd(&tie_cnt[4 * b + 1], 1) == (int)gridDim.x - 1;
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    for (int t = wave; t < T; t += 4) {
-        double ah = 0.0, al = 0.0;
-        for (int c = lane; c < nch; c += 64) {
-            const double2 v = *(const double2*)(part_b + ((size_t)t * nch + c) * 2);
-            ah += v.x;
-            al += v.y;
-        }
-        const double acc = wave_sum_f64(ah) + wave_sum_f64(al);
-        if (lane == 0) {
-            const int p = min(max(list[t], 0), q - 1);
-            rho_b[p] = acc;
-            if (rho_opt) rho_opt[sg.base + p] = acc;
-        }
-    }
-    __threadfence();
-    __syncthreads();
-    int fine = 0;
-    for (int t = wave; t < T; t += 4) {
-        const int p = min(max(list[t], 0), q - 1);
-        fine += preds_of_row<false>(p, q, rho_b, adj + ((size_t)b * bt.n_max + p) * bt.W,
-                                    preds + ((size_t)b * bt.n_max + p) * PRED_CAP,
-                                    (uint16_t*)(heads + (size_t)b * bt.n_max + p), s_nb[wave], lane, 0.0);
-    }
-    if (lane == 0 && fine) atomicAdd(&rep[b].rho_near_ties, fine);
-    if (tid == 0) rep[b].rho_rechecked = T;
 }
 
 // Eq. 8/9: every pruned token joins the nearest centre iff its fp64 distance is below
@@ -1220,18 +1293,15 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
                     w.near_list, w.near_cnt, w.stat, stat_words, w.adj, rep, w.rho_part, w.rho, rho_opt);
     dim3 gtok((bt.n_max + 3) / 4, bt.B);
     PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
-                w.heads, w.tie_list, w.tie_cnt);
+                w.heads, idx, w.tie_list, w.tie_cnt);
     // neighbours whose densities the fp32 terms cannot order: fp64 (a few tokens of an image)
-    const int rb = 512 / bt.B < 4 ? 4 : (512 / bt.B > 256 ? 256 : 512 / bt.B);
+    const int rb = 1024 / bt.B < 4 ? 4 : (1024 / bt.B > 512 ? 512 : 1024 / bt.B);
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
-                    w.adj, rep, w.rho, rho_opt, w.rho_fix, w.tie_list, w.tie_cnt, w.preds, w.heads);
+                    rep, w.rho_fix, w.tie_list, w.tie_cnt);
     else
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_F32>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
-                    w.adj, rep, w.rho, rho_opt, w.rho_fix, w.tie_list, w.tie_cnt, w.preds, w.heads);
-    if (rank_opt)
-        PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
-                    w.rho, rank_opt);
+                    rep, w.rho_fix, w.tie_list, w.tie_cnt);
     const size_t qpad = (size_t)((bt.n_max + 63) / 64 * 64);
     const size_t lds = qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4;
     static size_t raised = 0;
@@ -1242,7 +1312,11 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         raised = lds;
     }
     PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
-                      w.adj, w.rho, w.preds, w.heads, idx, w.status, w.cnum, w.cmask, center_idx);
+                      w.adj, w.rho, rho_opt, w.preds, w.heads, idx, w.tie_list, w.tie_cnt, w.rho_fix, w.status,
+                      w.cnum, w.cmask, center_idx);
+    if (rank_opt)          // (after the fp64 densities are in place)
+        PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
+                    w.rho, rank_opt);
     if (!assign_now) return PACT_OK;          // the caller runs it with the recovery (launch_reincorporate)
     NearArgs a;
     std::memset(&a, 0, sizeof(a));

@@ -40,7 +40,7 @@ constexpr int NEAR_CAP = 1 << 16;     // near-threshold pairs kept for fp64 re-e
 constexpr uint32_t NEAR_MIRROR = 0x80000000u;   // flag in a listed pair's row: the pair (col, row) is meant as well
 constexpr uint32_t ST_UNKNOWN = 0, ST_CENTER = 1, ST_NOT = 2;
 constexpr int RHO_RECHECK_MAX = PACT_MAX_RHO_RECHECK;   // tokens per sample whose density is evaluated again in fp64
-constexpr int RHO_RECHECK_CHUNK = 128;                  // kept tokens per partial sum of such an evaluation
+constexpr int RHO_RECHECK_CHUNK = 64;                   // kept tokens per partial sum of such an evaluation
 constexpr int32_t OVERFLOW_NEAR_LIST = 1, OVERFLOW_RHO_RECHECK = 2;   // bits of pact_report.refine_overflow
 
 struct WsLayout {
