@@ -7,16 +7,20 @@ synthetic LLaVA-OneVision-7B-shaped anyres image: N = 7290 tokens, hidden 3584, 
 outputs and workspace are resident in HBM before the timed region; the timed region is K
 back-to-back calls bracketed by device synchronisation.
 
-Prints ONE JSON line: whole-job images/s, ms per step, the roofline
-record of the dominant kernel (per-kernel durations measured with HIP events recorded by the
-library on the launch stream, in a separate pass right after the timed one) and the CPU
-oracle timed on this machine's host cores on the same input.
+Prints ONE JSON line: whole-job images/s, ms per step, the roofline record of the dominant
+kernel (per-kernel durations measured with HIP events recorded by the library on the launch
+stream, in a separate pass right after the timed one), the bandwidth-bound stages with cold
+caches first, the other workload shapes (a 729-token fp32 image, the same image with the
+model's 28 query heads, 8 videos, 16 ragged images, a 16384-token video with fp32 keys, with
+and without pruning), each with its density pass against the matrix-core peak and its merge
+against the HBM peak, and the CPU oracle timed on this machine's host cores on the same image.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -36,35 +40,62 @@ def algorithmic_work(kernel: str, n, h, dk, q, C, n_reinc, key_bytes, hid_bytes,
         return "mfma", 2.0 * (n - q) * C * dk, "flop"
     if kernel == "qglobal_hnorm":         # read H once (norms) and the query partials, write norms and the global query
         return "hbm", n * h * hid_bytes + 512 * n_q * d_h * 8 + n * 8 + n_q * d_h * 8, "B"
-    if kernel == "score_logits":          # read K_pre once, write logits
-        return "hbm", n * dk * key_bytes + n * n_q * 8, "B"
-    if kernel == "qglobal_partial":
-        return "hbm", n * n_q * d_h * key_bytes, "B"
     if kernel == "merge_mean":            # read member rows once, write C merged rows
         return "hbm", (q + n_reinc) * h * hid_bytes + C * h * out_bytes, "B"
-    if kernel == "key_prep":              # read the keys, clear the bitmap of the kept tokens
-        return "hbm", n * dk * key_bytes + q * ((q + 63) // 64) * 8, "B"
+    if kernel == "prep":                  # keys and queries read, the kept x kept bitmap cleared
+        return "hbm", n * dk * key_bytes + n * n_q * d_h * key_bytes + q * ((q + 63) // 64) * 8, "B"
     return None, 0.0, ""
 
 
+def _profile_table(name):
+    """Rows `| kernel | a | b | ...` of a committed rocprofv3 summary under profiles/ -> {kernel: [cells]}."""
+    path = os.path.join(ROOT, "profiles", name)
+    rows = {}
+    if os.path.exists(path):
+        for ln in open(path):
+            cells = [c.strip() for c in ln.strip().strip("|").split("|")]
+            if len(cells) >= 3 and re.fullmatch(r"[a-z_]+", cells[0] or ""):
+                rows[cells[0]] = cells[1:]
+    return rows
+
+
 def measured_traffic(kernel: str):
-    """HBM bytes per launch of `kernel` (read + write) from the committed rocprofv3 --pmc summary:
-    its table rows are `| kernel | fetch bytes | write bytes | ... |`; None when there is no row."""
-    path = os.path.join(ROOT, "profiles", "pact_reduce_img7b_hbm_traffic.md")
-    if not os.path.exists(path):
+    """HBM bytes per launch of `kernel` (read + write) from the committed rocprofv3 --pmc summary."""
+    cells = _profile_table("pact_reduce_img7b_hbm_traffic.md").get(kernel)
+    try:
+        return float(cells[0]) + float(cells[1])
+    except (TypeError, ValueError, IndexError):
         return None
-    for ln in open(path):
-        cells = [c.strip() for c in ln.strip().strip("|").split("|")]
-        if len(cells) >= 3 and cells[0] == kernel:
-            try:
-                return float(cells[1]) + float(cells[2])
-            except ValueError:
-                return None
-    return None
+
+
+def rocprof_us(kernel: str):
+    """Average duration of `kernel` in the committed rocprofv3 kernel trace of this command (us)."""
+    cells = _profile_table("pact_reduce_img7b_kernel_stats.md").get(kernel)
+    try:
+        return float(cells[1])
+    except (TypeError, ValueError, IndexError):
+        return None
+
+
+def kernel_times(P, torch, fn, steps):
+    """us per call of every kernel (the library's event brackets), and launches per call."""
+    P.pact_profile_enable(True)
+    P.pact_profile_reset()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    recs = P.pact_profile_read(steps * 64)
+    P.pact_profile_enable(False)
+    tot, cnt = {}, {}
+    for k, ms in recs:
+        tot[k] = tot.get(k, 0.0) + ms
+        cnt[k] = cnt.get(k, 0) + 1
+    return {k: v / steps * 1e3 for k, v in tot.items()}, {k: c // steps for k, c in cnt.items()}
 
 
 def other_configs(P, gen, torch, np, only=None, steps_override=None):
-    """us per call of the other workload shapes (warm, back to back), with their counts.
+    """us per call of the other workload shapes (warm, back to back), with their counts, the
+    algorithmic matrix-core fraction of their density pass and HBM fraction of their merge.
     only: run just that shape (for a profiler run of one shape), steps_override calls of it."""
     with open(os.path.join(ROOT, "pact_synth", "manifest.json")) as f:
         man = json.load(f)
@@ -75,7 +106,8 @@ def other_configs(P, gen, torch, np, only=None, steps_override=None):
 
     def entry(sm):
         grids = sm.n // (sm.config.gh * sm.config.gw)
-        return man[f"{sm.config.name}:s{sm.seed}:g{grids}:l{sm.lam:.2f}"]
+        heads = "" if sm.queries.shape[1] == sm.config.n_kv else f":q{sm.queries.shape[1]}"
+        return man[f"{sm.config.name}:s{sm.seed}:g{grids}:l{sm.lam:.2f}{heads}"]
 
     def timeit(fn, steps):
         for _ in range(5):
@@ -87,42 +119,69 @@ def other_configs(P, gen, torch, np, only=None, steps_override=None):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps * 1e6
 
-    def kernel_table(fn, steps=10):
-        """us per call of every kernel (the library's event brackets), largest first."""
-        P.pact_profile_enable(True)
-        P.pact_profile_reset()
-        for _ in range(steps):
-            fn()
-        torch.cuda.synchronize()
-        recs = P.pact_profile_read(steps * 64)
-        P.pact_profile_enable(False)
-        tot = {}
-        for k, ms in recs:
-            tot[k] = tot.get(k, 0.0) + ms
-        return {k: round(v / steps * 1e3, 1) for k, v in sorted(tot.items(), key=lambda kv: -kv[1])}
+    def fractions(kus, reps, ns, h, dk):
+        """density pass: unique pairs of all samples against the bf16 matrix-core peak (fp32 keys run on the
+        bf16 instruction as three parts, six passes: their algorithmic flops are still q^2 dk); merge: member
+        rows read + merged rows written against the HBM peak."""
+        out = {}
+        if "gram_density" in kus:
+            fl = sum(float(r["n_kept"]) ** 2 * dk for r in reps)
+            out["density_pass"] = {"us": round(kus["gram_density"], 1), "algorithmic_GFLOP": round(fl / 1e9, 2),
+                                   "frac_of_bf16_mfma_peak": round(fl / (kus["gram_density"] * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4)}
+        if "merge_mean" in kus:
+            by = sum((r["n_kept"] + r["n_reincorporated"]) * h * 2 + r["n_centers"] * h * 4 for r in reps)
+            out["merge"] = {"us": round(kus["merge_mean"], 1), "algorithmic_MB": round(by / 1e6, 1),
+                            "frac_of_hbm_peak": round(by / (kus["merge_mean"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
+        return out
 
     out = {}
-    for name, steps in (("img_0p5b", 200), ("vid_long", 20)):
+    singles = (("img_0p5b", dict(), 200), ("img_7b_q28", dict(n_q=28), 100), ("vid_long", dict(), 20),
+               ("vid_long_lambda0", dict(lam=0.0), 10))
+    for name, kw, steps in singles:
         if only is not None and name != only:
             continue
         steps = steps_override or steps
-        cfg = gen.CONFIGS[name]
-        sm = gen.make_sample(cfg, 0)
+        base = {"img_7b_q28": "img_7b", "vid_long_lambda0": "vid_long"}.get(name, name)
+        cfg = gen.CONFIGS[base]
+        sm = gen.make_sample(cfg, 0, **kw)
         m = entry(sm)
+        n_q = sm.queries.shape[1]
         hid = dev(sm.hidden, cfg.hidden_dtype)
         ks = dev(sm.keys.reshape(sm.n, -1), cfg.key_dtype)
         qs = dev(sm.queries.reshape(sm.n, -1), cfg.key_dtype)
         prm = P.PactParams(sm.lam, m["d_c"], 2.0, 1.5)
-        ws = P.alloc_workspace(sm.n, 1, cfg.dk, cfg.n_kv, cfg.d_h)
-        o = P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws)
-        us = timeit(lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws, out=o), steps)
+        ws = P.alloc_workspace(sm.n, 1, cfg.dk, n_q, cfg.d_h, key_dtype=ks.dtype)
+        o = P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, n_q, prm, ws=ws)
+        call = lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, n_q, prm, ws=ws, out=o)
+        us = timeit(call, steps)
         r = P.read_report(o["rep"])
         assert r["n_kept"] == m["q"] and r["n_centers"] == m["C"], (name, r, m)
-        out[name] = {"n": sm.n, "batch": 1, "us_per_call": round(us, 1), "samples_per_s": round(1e6 / us, 1),
-                     "q": r["n_kept"], "C": r["n_centers"],
-                     "kernels_us": kernel_table(lambda: P.pact_reduce(hid, ks, ks, qs, cfg.n_kv, cfg.d_h, cfg.n_kv,
-                                                                      prm, ws=ws, out=o))}
+        kus, _ = kernel_times(P, torch, call, min(steps, 10))
+        out[name] = {"n": sm.n, "batch": 1, "key_dtype": cfg.key_dtype, "query_heads": n_q, "lambda": sm.lam,
+                     "us_per_call": round(us, 1), "samples_per_s": round(1e6 / us, 1), "q": r["n_kept"],
+                     "C": r["n_centers"], "rho_rechecked": r["rho_rechecked"], **fractions(kus, [r], [sm.n], cfg.hidden, cfg.dk),
+                     "kernels_us": {k: round(v, 1) for k, v in sorted(kus.items(), key=lambda kv: -kv[1])}}
         del hid, ks, qs, ws, o
+    if only in (None, "img_7b_hidden_dbdpc"):
+        # DBDPC alone on the hidden states of the benchmark image (the ablation that clusters hidden states
+        # instead of keys): 7290 vectors of width 3584, nothing pruned
+        sm = gen.make_sample("img_7b", 0)
+        m = man["img_7b:s0:g10:hidden"]
+        hid = dev(sm.hidden, "bf16")
+        ws = P.alloc_workspace(sm.n, 1, sm.config.hidden, 1, 1, key_dtype=hid.dtype)
+        o = P.dbdpc_cluster(hid, m["d_c"], 2.0, ws=ws)
+        call = lambda: P.dbdpc_cluster(hid, m["d_c"], 2.0, ws=ws)
+        us = timeit(call, steps_override or 50)
+        r = P.read_report(o["rep"])
+        assert r["n_centers"] == m["C"], (r, m)
+        kus, _ = kernel_times(P, torch, call, 10)
+        fl = float(sm.n) ** 2 * sm.config.hidden
+        out["img_7b_hidden_dbdpc"] = {
+            "n": sm.n, "width": sm.config.hidden, "us_per_call": round(us, 1), "C": r["n_centers"],
+            "density_pass": {"us": round(kus["gram_density"], 1), "algorithmic_GFLOP": round(fl / 1e9, 1),
+                             "frac_of_bf16_mfma_peak": round(fl / (kus["gram_density"] * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS["bf16"], 4)},
+            "kernels_us": {k: round(v, 1) for k, v in sorted(kus.items(), key=lambda kv: -kv[1])}}
+        del hid, ws, o
     for name, make, steps in (("vid_7b_batch8", lambda: gen.make_batch("vid_7b", 0), 30),
                               ("varlen16", lambda: gen.make_varlen_batch(0), 30)):
         if only is not None and name != only:
@@ -139,19 +198,53 @@ def other_configs(P, gen, torch, np, only=None, steps_override=None):
         prms = [P.PactParams(sm.lam, entry(sm)["d_c"], 2.0, 1.5) for sm in samples]
         exp = [(entry(sm)["q"], entry(sm)["C"]) for sm in samples]
         n_max = max(sm.n for sm in samples)
-        ws = P.alloc_workspace(n_max, len(samples), cfg0.dk, cfg0.n_kv, cfg0.d_h)
+        ws = P.alloc_workspace(n_max, len(samples), cfg0.dk, cfg0.n_kv, cfg0.d_h, key_dtype=ks.dtype)
         o = P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h, cfg0.n_kv, cu, prms, ws=ws)
-        us = timeit(lambda: P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h, cfg0.n_kv, cu, prms,
-                                                 ws=ws, out=o), steps)
+        call = lambda: P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h, cfg0.n_kv, cu, prms, ws=ws, out=o)
+        us = timeit(call, steps)
         reps = P.read_report(o["rep"])
         assert [(r["n_kept"], r["n_centers"]) for r in reps] == exp, (name, reps, exp)
+        kus, _ = kernel_times(P, torch, call, min(steps, 10))
         out[name] = {"n_total": cu[-1], "batch": len(samples), "us_per_call": round(us, 1),
                      "us_per_sample": round(us / len(samples), 1),
                      "samples_per_s": round(len(samples) * 1e6 / us, 1),
-                     "kernels_us": kernel_table(lambda: P.pact_reduce_varlen(hid, ks, ks, qs, cfg0.n_kv, cfg0.d_h,
-                                                                             cfg0.n_kv, cu, prms, ws=ws, out=o))}
+                     "rho_rechecked": sum(r["rho_rechecked"] for r in reps),
+                     **fractions(kus, reps, [sm.n for sm in samples], cfg0.hidden, cfg0.dk),
+                     "kernels_us": {k: round(v, 1) for k, v in sorted(kus.items(), key=lambda kv: -kv[1])}}
         del hid, ks, qs, ws, o
     return out
+
+
+def cpu_baseline(s, d_c):
+    """The oracle as it stands on this machine's host cores, on the benchmark image: once with every
+    numerical library held to one thread, once with the threads they take by themselves."""
+    from oracle import pact_oracle as po
+    try:
+        from threadpoolctl import threadpool_info, threadpool_limits
+    except Exception:
+        threadpool_info, threadpool_limits = None, None
+
+    def run(budget_s, max_reps):
+        reps, t_cpu = 0, 0.0
+        while reps < 2 or (t_cpu < budget_s and reps < max_reps):
+            t1 = time.perf_counter()
+            po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5)
+            t_cpu += time.perf_counter() - t1
+            reps += 1
+        return reps, t_cpu
+
+    pool = max([i.get("num_threads", 1) for i in threadpool_info()] + [1]) if threadpool_info else 1
+    reps_all, t_all = run(8.0, 30)
+    one = None
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            reps_1, t_1 = run(10.0, 4)
+        one = {"value": round(reps_1 / t_1, 4), "unit": "images/s", "cores": 1, "ms_per_step": round(t_1 / reps_1 * 1e3, 1),
+               "sample": f"{reps_1} runs, every numerical library held to one thread"}
+    return {"value": round(reps_all / t_all, 4), "unit": "images/s", "cores": pool, "kind": "oracle",
+            "sample": f"{reps_all} runs of the fp64 numpy oracle's pact_reduce on the benchmark image (matmuls on the "
+                      f"{pool} BLAS threads numpy takes by itself, the rest on one thread)",
+            "ms_per_step": round(t_all / reps_all * 1e3, 1), "host_cpu_count": os.cpu_count(), "one_thread": one}
 
 
 def main():
@@ -163,13 +256,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-table", action="store_true", help="print per-kernel averages to stderr")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache passes (profiling runs)")
-    ap.add_argument("--all-configs", action="store_true",
-                    help="also time the other workload shapes (single image, video batch, ragged batch, long "
-                         "video) and add them to the JSON line under other_configs")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the other workload shapes (single image, 28 query heads, video batch, ragged batch, "
+                         "long video); by default they are timed after the benchmark image and reported under other_configs")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also launch the library's plain copy kernel once over this many MiB "
                          "(a dispatch of known HBM traffic for rocprofv3 --pmc runs)")
-    ap.add_argument("--only-config", choices=["img_0p5b", "vid_long", "vid_7b_batch8", "varlen16"], default=None,
+    ap.add_argument("--only-config", choices=["img_0p5b", "img_7b_q28", "vid_long", "vid_long_lambda0", "img_7b_hidden_dbdpc",
+                                              "vid_7b_batch8", "varlen16"], default=None,
                     help="run --steps calls of that workload shape alone and print its record (a profiler run of "
                          "one shape; the benchmark line is not printed)")
     args = ap.parse_args()
@@ -205,7 +299,7 @@ def main():
 
     hidden, keys, q = dev(s.hidden), dev(s.keys.reshape(n, -1)), dev(s.queries.reshape(n, -1))
     prm = P.PactParams(s.lam, d_c, 2.0, 1.5)
-    ws = P.alloc_workspace(n, 1, dk, cfg.n_kv, cfg.d_h)
+    ws = P.alloc_workspace(n, 1, dk, cfg.n_kv, cfg.d_h, key_dtype=keys.dtype)
     out = P.pact_reduce(hidden, keys, keys, q, cfg.n_kv, cfg.d_h, cfg.n_kv, prm, ws=ws)
 
     def step():
@@ -232,25 +326,14 @@ def main():
     assert rep["n_kept"] == man["q"] and rep["n_centers"] == man["C"], (rep, man)
 
     # per-kernel durations: library-side HIP events on the launch stream, separate pass
-    P.pact_profile_enable(True)
-    P.pact_profile_reset()
     prof_steps = min(args.steps, 50)
-    for _ in range(prof_steps):
-        step()
-    torch.cuda.synchronize()
-    recs = P.pact_profile_read(prof_steps * 64)
-    P.pact_profile_enable(False)
-    tot, cnt = {}, {}
-    for name, ms in recs:
-        tot[name] = tot.get(name, 0.0) + ms
-        cnt[name] = cnt.get(name, 0) + 1
-    per_step = {k: v / prof_steps for k, v in tot.items()}          # ms per step, all launches of k
-    per_launch = {k: tot[k] / cnt[k] for k in tot}
+    per_step_us, launches = kernel_times(P, torch, step, prof_steps)
+    per_launch_us = {k: per_step_us[k] / max(launches[k], 1) for k in per_step_us}
     if args.kernel_table:
-        for k in sorted(per_step, key=per_step.get, reverse=True):
-            print(f"  {k:18s} {per_step[k] * 1e3:9.2f} us/step  {cnt[k] // prof_steps} launch(es)  "
-                  f"{per_launch[k] * 1e3:9.2f} us/launch", file=sys.stderr)
-        print(f"  sum of kernels      {sum(per_step.values()) * 1e3:9.2f} us/step; wall {ms_per_step * 1e3:.2f} us/step",
+        for k in sorted(per_step_us, key=per_step_us.get, reverse=True):
+            print(f"  {k:18s} {per_step_us[k]:9.2f} us/step  {launches[k]} launch(es)  {per_launch_us[k]:9.2f} us/launch",
+                  file=sys.stderr)
+        print(f"  sum of kernels      {sum(per_step_us.values()):9.2f} us/step; wall {ms_per_step * 1e3:.2f} us/step",
               file=sys.stderr)
 
     # distribution over steps (events on the launch stream around each step), warm and cold:
@@ -271,20 +354,12 @@ def main():
 
     def cold_pass(scrub):
         us = step_times(dist_steps, scrub)
-        P.pact_profile_enable(True)
-        P.pact_profile_reset()
-        cold_prof_steps = 30
-        for _ in range(cold_prof_steps):
+
+        def scrubbed_step():
             scrub()
             step()
-        torch.cuda.synchronize()
-        crecs = P.pact_profile_read(cold_prof_steps * 64)
-        P.pact_profile_enable(False)
-        ctot, ccnt = {}, {}
-        for name, ms in crecs:
-            ctot[name] = ctot.get(name, 0.0) + ms
-            ccnt[name] = ccnt.get(name, 0) + 1
-        return us, {k: ctot[k] / ccnt[k] for k in ctot}
+        tab, cnt = kernel_times(P, torch, scrubbed_step, 30)
+        return us, {k: tab[k] / max(cnt[k], 1) for k in tab}
 
     dist_steps = min(max(args.steps, 100), 300)
     warm_us = step_times(dist_steps, None)
@@ -302,60 +377,46 @@ def main():
 
     q_kept, C, n_re = rep["n_kept"], rep["n_centers"], rep["n_reincorporated"]
     roof = None
-    for k in sorted(per_step, key=per_step.get, reverse=True):
+    for k in sorted(per_step_us, key=per_step_us.get, reverse=True):
         bound, work, unit = algorithmic_work(k, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
         if bound is None:
             continue
-        sec = per_launch[k] * 1e-3
+        sec = per_launch_us[k] * 1e-6
         if bound == "mfma":
             ach, peak, u = work / sec / 1e12, PEAK_MFMA_TFLOPS["bf16"], "TFLOP/s"
         else:
             ach, peak, u = work / sec / 1e9, PEAK_HBM_GBS, "GB/s"
-        traffic = measured_traffic(k)
         roof = {"kernel": k, "bound": bound, "achieved": round(ach, 3), "peak": peak, "unit": u,
-                "frac": round(ach / peak, 4), "traffic": traffic, "us_per_launch": round(sec * 1e6, 2),
+                "frac": round(ach / peak, 4), "traffic": measured_traffic(k), "us_per_launch": round(sec * 1e6, 2),
                 "work_per_launch": work, "work_unit": unit,
-                "share_of_step": round(per_step[k] / sum(per_step.values()), 3)}
+                "share_of_step": round(per_step_us[k] / sum(per_step_us.values()), 3)}
+        # the same kernel's average in the committed rocprofv3 kernel trace (begin/end timestamps; the event
+        # brackets above include the dispatch overhead inside the bracket, about 2.5 us)
+        rp = rocprof_us(k)
+        if rp:
+            roof["us_per_launch_rocprof"] = rp
+            roof["frac_rocprof"] = round(work / (rp * 1e-6) / (1e12 if bound == "mfma" else 1e9) / peak, 4)
         if k == "gram_density":
             # the kernel computes the full (symmetric) matrix: executed flops are twice the algorithmic ones
             roof["executed_flop_per_launch"] = 2.0 * work
             roof["frac_executed"] = round(2.0 * ach / peak, 4)
         break
 
-    # the bandwidth-bound stages, warm (inputs still in the caches from the previous step) and cold
+    # the bandwidth-bound stages: cold first (nothing of the inputs in any cache), then warm (inputs still in the
+    # caches from the previous step)
     hbm_stages = {}
     for k in ("qglobal_hnorm", "merge_mean", "prep"):
-        kk = "key_prep" if k == "prep" else k
-        bound, work, unit = algorithmic_work(kk, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
-        if k == "prep":
-            work = n * dk * 2 * 2 + q_kept * ((q_kept + 63) // 64) * 8     # keys + queries read, kept x kept bitmap cleared
-        if k not in per_launch:
+        bound, work, unit = algorithmic_work(k, n, h, dk, q_kept, C, n_re, 2, 2, 4, cfg.n_kv, cfg.d_h)
+        if k not in per_launch_us:
             continue
         ent = {"bytes_algorithmic": work, "traffic_measured": measured_traffic(k)}
-        for tag, tbl in (("warm", per_launch), ("cold", cold_per_launch), ("cold_read_scrub", coldr_per_launch)):
+        for tag, tbl in (("cold", cold_per_launch), ("cold_read_scrub", coldr_per_launch), ("warm", per_launch_us)):
             if k in tbl:
-                gbs = work / (tbl[k] * 1e-3) / 1e9
-                ent[tag] = {"us": round(tbl[k] * 1e3, 2), "GB/s": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
+                gbs = work / (tbl[k] * 1e-6) / 1e9
+                ent[tag] = {"us": round(tbl[k], 2), "GB/s": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
         hbm_stages[k] = ent
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import pact_oracle as po
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-        except Exception:
-            cores = 1
-        reps, t_cpu = 0, 0.0
-        while reps < 3 or (t_cpu < 12.0 and reps < 40):        # about 12 s of CPU work
-            t1 = time.perf_counter()
-            po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, 2.0, 1.5)
-            t_cpu += time.perf_counter() - t1
-            reps += 1
-        cpu = {"value": round(reps / t_cpu, 4), "unit": "images/s", "cores": cores, "kind": "oracle",
-               "sample": f"{reps} runs of the fp64 numpy oracle's pact_reduce on the same image "
-                         f"(matmuls on {cores} BLAS threads, the rest on one thread)",
-               "ms_per_step": round(t_cpu / reps * 1e3, 1)}
+    cpu = None if args.no_cpu_baseline else cpu_baseline(s, d_c)
 
     line = {
         "metric": "images/sec per pact_reduce at N=7290, Dk=512", "value": round(args.steps / dt, 2),
@@ -365,18 +426,22 @@ def main():
         "data": "synthetic",
         "config": {"workload": "LLaVA-OV-7B-shaped anyres image, N=7290 (10x729), H=3584, Dk=512 (4x128) bf16, "
                                "lambda=0.45, d_n=2, alpha=1.5, d_c=%.6f (71%% reduction), batch 1" % d_c,
-                   "seed": args.seed, "q": q_kept, "C": C, "n_reincorporated": n_re,
-                   "rounds": rep["rounds"], "dc_checked_pairs": rep["dc_checked_pairs"]},
+                   "seed": args.seed, "q": q_kept, "C": C, "n_reincorporated": n_re, "launches_per_call": sum(launches.values()),
+                   "rounds": rep["rounds"], "dc_checked_pairs": rep["dc_checked_pairs"], "dc_near_ties": rep["dc_near_ties"],
+                   "rho_rechecked": rep["rho_rechecked"], "rho_near_ties": rep["rho_near_ties"],
+                   "score_near_ties": rep["score_near_ties"], "nonfinite_seen": rep["nonfinite_seen"],
+                   "refine_overflow": rep["refine_overflow"]},
         "roofline": roof,
         "cpu_baseline": cpu,
-        "us_per_step_warm": pct(warm_us), "us_per_step_cold": pct(cold_us) if cold_us is not None else None,
+        "us_per_step_cold": pct(cold_us) if cold_us is not None else None,
         "us_per_step_cold_read_scrub": pct(coldr_us) if coldr_us is not None else None,
+        "us_per_step_warm": pct(warm_us),
         "hbm_stages": hbm_stages,
-        "kernels_us_per_step": {k: round(v * 1e3, 2) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
-        "kernels_us_per_step_cold": {k: round(v * 1e3, 2) for k, v in sorted(cold_per_launch.items(), key=lambda kv: -kv[1])},
-        "kernels_us_per_step_cold_read_scrub": {k: round(v * 1e3, 2) for k, v in sorted(coldr_per_launch.items(), key=lambda kv: -kv[1])},
+        "kernels_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
+        "kernels_us_per_step_cold": {k: round(v, 2) for k, v in sorted(cold_per_launch.items(), key=lambda kv: -kv[1])},
+        "kernels_us_per_step_cold_read_scrub": {k: round(v, 2) for k, v in sorted(coldr_per_launch.items(), key=lambda kv: -kv[1])},
     }
-    if args.all_configs:
+    if not args.no_other_configs:
         line["other_configs"] = other_configs(P, gen, torch, np)
     print(json.dumps(line))
 

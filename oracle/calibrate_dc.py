@@ -34,7 +34,8 @@ MANIFEST = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__
 
 def sample_key(s: gen.Sample) -> str:
     grids = s.n // (s.config.gh * s.config.gw)
-    return f"{s.config.name}:s{s.seed}:g{grids}:l{s.lam:.2f}"
+    heads = "" if s.queries.shape[1] == s.config.n_kv else f":q{s.queries.shape[1]}"      # query heads, if not one per key head
+    return f"{s.config.name}:s{s.seed}:g{grids}:l{s.lam:.2f}{heads}"
 
 
 def calibrate(s: gen.Sample, target: float) -> dict:
@@ -91,6 +92,36 @@ def calibrate(s: gen.Sample, target: float) -> dict:
     }
 
 
+def calibrate_vectors(U, target: float) -> dict:
+    """DBDPC alone on the rows of U (nothing pruned, no recovery): d_c for a reduction 1 - C/n of
+    `target`, moved to the middle of the widest nearby gap of pair distances like calibrate()."""
+    U = np.asarray(U, dtype=np.float64)
+    n = U.shape[0]
+    D = po.cosine_distance_matrix(U)
+    order = po.density_order(po.density(D, D_N))
+    want_c = max(1, int(round((1.0 - target) * n)))
+    lo, hi = 0.0, 2.0
+    for _ in range(40):
+        mid = 0.5 * (lo + hi)
+        if po.select_centers(D, order, mid).size > want_c:
+            lo = mid
+        else:
+            hi = mid
+        if hi - lo < 1e-7:
+            break
+    d0 = hi
+    allp = np.sort(D[np.triu_indices(n, 1)])
+    w = 0.002 * max(d0, 1e-3)
+    a = max(int(np.searchsorted(allp, d0 - w, "left")), 0)
+    b = min(max(int(np.searchsorted(allp, d0 + w, "right")), a + 2), allp.size)
+    dd = allp[a:b]
+    k = int(np.argmax(np.diff(dd)))
+    d_c = float(np.float32(0.5 * (dd[k] + dd[k + 1])))
+    centers = po.select_centers(D, order, d_c)
+    return {"d_c": d_c, "d_c_hex": float(d_c).hex(), "d_n": D_N, "n": n, "q": n, "C": int(centers.size),
+            "reduction": 1.0 - centers.size / n, "min_gap_to_dc": float(np.abs(allp - d_c).min())}
+
+
 def groups():
     g = {
         "tiny_f32": lambda: [gen.make_sample("tiny_f32", s) for s in range(10)],
@@ -100,6 +131,8 @@ def groups():
         "vid_7b": lambda: [s for b in range(3) for s in gen.make_batch("vid_7b", b)],
         "varlen": lambda: [s for b in range(3) for s in gen.make_varlen_batch(b)],
         "vid_long": lambda: [gen.make_sample("vid_long", s) for s in range(3)],
+        # the 7B-shaped image with the model's 28 query heads on its 4 key heads (scores, hence the kept set, differ)
+        "img_7b_q28": lambda: [gen.make_sample("img_7b", s, n_q=28) for s in range(2)],
         # the long video with nothing pruned: all 16384 tokens are clustered
         "vid_long_all": lambda: [gen.make_sample("vid_long", 0, lam=0.0)],
     }
@@ -109,11 +142,27 @@ def groups():
 def main(argv):
     only_missing = "--missing" in argv
     argv = [a for a in argv if a != "--missing"]
-    want = argv or list(groups().keys())
+    want = argv or list(groups().keys()) + ["img_7b_hidden"]
     manifest = {}
     if os.path.exists(MANIFEST):
         with open(MANIFEST) as f:
             manifest = json.load(f)
+    if "img_7b_hidden" in want:
+        # clustering on the hidden states instead of the keys (the ablation of Sec. "Ablation study"): the
+        # 3584-wide hidden states of the benchmark image, 60% reduction as in the paper's DBDPC-only tables
+        want = [w for w in want if w != "img_7b_hidden"]
+        key = "img_7b:s0:g10:hidden"
+        if not (only_missing and key in manifest):
+            t = time.time()
+            entry = calibrate_vectors(gen.make_sample("img_7b", 0).hidden, 0.60)
+            if os.path.exists(MANIFEST):
+                with open(MANIFEST) as f:
+                    manifest = json.load(f)
+            manifest[key] = entry
+            print(f"{key}: d_c={entry['d_c']:.6f} C={entry['C']} reduction={entry['reduction']:.4f} "
+                  f"gap={entry['min_gap_to_dc']:.2e} ({time.time() - t:.1f}s)", flush=True)
+            with open(MANIFEST, "w") as f:
+                json.dump(manifest, f, indent=1, sort_keys=True)
     for name in want:
         for s in groups()[name]():
             if only_missing and sample_key(s) in manifest:

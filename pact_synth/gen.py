@@ -95,7 +95,7 @@ class Sample:
     seed: int
     hidden: np.ndarray      # [n, hidden]  float32 container
     keys: np.ndarray        # [n, n_kv, d_h]; used for EUTI and DBDPC alike
-    queries: np.ndarray     # [n, n_q, d_h], n_q == n_kv
+    queries: np.ndarray     # [n, n_q, d_h], n_q == n_kv unless asked otherwise
     lam: float
     extra: dict = field(default_factory=dict)
 
@@ -174,8 +174,10 @@ def _directions(rng, cfg: Config, n_blobs: int, grids: int):
 
 
 def make_sample(cfg: Config | str, seed: int, *, grids: int | None = None,
-                lam: float | None = None) -> Sample:
-    """One image / video of configuration `cfg` from `seed`."""
+                lam: float | None = None, n_q: int | None = None) -> Sample:
+    """One image / video of configuration `cfg` from `seed`.  n_q: number of query heads (a
+    multiple of the key heads, as in grouped-query models; default: as many as key heads).
+    Hidden states and keys do not depend on it."""
     if isinstance(cfg, str):
         cfg = CONFIGS[cfg]
     grids = cfg.grids if grids is None else grids
@@ -192,8 +194,10 @@ def make_sample(cfg: Config | str, seed: int, *, grids: int | None = None,
     hnorm = np.exp(rng.normal(0.0, 0.5, n))
     hidden = _unit(hdir) * hnorm[:, None]
 
-    m = _unit(rng.standard_normal((cfg.n_kv, cfg.d_h)))
-    queries = np.sqrt(cfg.d_h) * m[None, :, :] + rng.standard_normal((n, cfg.n_kv, cfg.d_h))
+    n_q = cfg.n_kv if n_q is None else n_q
+    assert n_q % cfg.n_kv == 0
+    m = _unit(rng.standard_normal((n_q, cfg.d_h)))
+    queries = np.sqrt(cfg.d_h) * m[None, :, :] + rng.standard_normal((n, n_q, cfg.d_h))
 
     return Sample(cfg, seed, _cast(hidden, cfg.hidden_dtype), _cast(keys, cfg.key_dtype),
                   _cast(queries, cfg.key_dtype), cfg.lam if lam is None else lam)

@@ -930,55 +930,23 @@ __device__ __forceinline__ double group_dot64(const char* mine, const char* othe
     return acc;
 }
 
-// group_dot64 for the row pair (mine, other) and, in the same pass and the same order of
-// operations, for (other, other): rows that are bit-identical then give bit-identical dot products
-// and norms, i.e. a cosine of exactly 1.
+// Dot product in fp64 of two rows whose 16-byte chunks the 16 lanes of a group already hold (chunks
+// part, part + 16, .. of rows of at most 64 chunks; the first row widened to fp64 beforehand) and, in the
+// same pass and the same order of
+// operations, of the second row with itself: rows that are bit-identical then give bit-identical
+// dot products and norms, i.e. a cosine of exactly 1.  Every lane of the group gets both sums.
 template <int DT>
-__device__ __forceinline__ void group_dot64_with_norm(const char* mine, const char* other, int nchunk, int part,
-                                                      double& dot, double& nn_other) {
-    constexpr int EPL = Elem<DT>::EPL;
-    double acc = 0.0, acc2 = 0.0;
-#pragma unroll 1
-    for (int k0 = part; k0 < nchunk; k0 += 64) {
-        uint4 va[4], vb[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const size_t o = (size_t)(k0 + 16 * u < nchunk ? k0 + 16 * u : k0) * 16;
-            va[u] = *(const uint4*)(mine + o);
-            vb[u] = *(const uint4*)(other + o);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (k0 + 16 * u < nchunk) {
-                double a[8], x[8];
-                Elem<DT>::widen(va[u], a);
-                Elem<DT>::widen(vb[u], x);
-#pragma unroll
-                for (int i = 0; i < EPL; ++i) { acc = fma(a[i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
-            }
-        }
-    }
-#pragma unroll
-    for (int sft = 1; sft <= 8; sft <<= 1) { acc += __shfl_xor(acc, sft, 64); acc2 += __shfl_xor(acc2, sft, 64); }
-    dot = acc;
-    nn_other = acc2;
-}
-
-// The same for rows whose 16-byte chunks the lanes already hold (chunks part, part + 16, .. of rows
-// of at most 64 chunks): same order of operations as group_dot64_with_norm.
-template <int DT>
-__device__ __forceinline__ void chunk_dots64(const uint4 (&va)[4], const uint4 (&vb)[4], int nchunk, int part,
+__device__ __forceinline__ void chunk_dots64(const double (&a)[4][8], const uint4 (&vb)[4], int nchunk, int part,
                                              double& dot, double& nn_other) {
     constexpr int EPL = Elem<DT>::EPL;
     double acc = 0.0, acc2 = 0.0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         if (part + 16 * u < nchunk) {
-            double a[8], x[8];
-            Elem<DT>::widen(va[u], a);
+            double x[8];
             Elem<DT>::widen(vb[u], x);
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) { acc = fma(a[i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
+            for (int i = 0; i < EPL; ++i) { acc = fma(a[u][i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
         }
     }
 #pragma unroll
@@ -1048,27 +1016,67 @@ __global__ __launch_bounds__(256) void rho_recheck_kernel(Batch bt, const char* 
                 for (int u = 0; u < 4; ++u)
                     vk[s][u] = *(const uint4*)(kb + (size_t)tk * row_bytes + (size_t)min(part16 + 16 * u, nchunk - 1) * 16);
             }
+            double am[4][8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<DT>::widen(vm[u], am[u]);
             double nnp, dd;
-            chunk_dots64<DT>(vm, vm, nchunk, part16, dd, nnp);
+            chunk_dots64<DT>(am, vm, nchunk, part16, dd, nnp);
 #pragma unroll
             for (int s = 0; s < PER; ++s) {
                 const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
                 double dot, nnk;
-                chunk_dots64<DT>(vm, vk[s], nchunk, part16, dot, nnk);
+                chunk_dots64<DT>(am, vk[s], nchunk, part16, dot, nnk);
                 const double d = cos_dist64(dot, nnp, nnk);
                 const double term = pk >= q ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
                 const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
                 if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
             }
         } else {
-            double nnp, dot, nnk;
-            group_dot64_with_norm<DT>(mine, mine, nchunk, part16, dot, nnp);
+            // longer rows: the group's four pairs advance together, four chunks of the token's row
+            // and of each of the four other rows per trip (same order of operations per pair as above)
+            constexpr int EPL = Elem<DT>::EPL;
+            const char* rowk[PER];
+#pragma unroll
+            for (int s = 0; s < PER; ++s) rowk[s] = kb + (size_t)__shfl(tk_mine, (lane & ~15) + s, 64) * row_bytes;
+            double nnp = 0.0, dot[PER], nnk[PER];
+#pragma unroll
+            for (int s = 0; s < PER; ++s) dot[s] = nnk[s] = 0.0;
 #pragma unroll 1
+            for (int k0 = part16; k0 < nchunk; k0 += 64) {
+                uint4 vm[4], vk[PER][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const size_t o = (size_t)min(k0 + 16 * u, nchunk - 1) * 16;
+                    vm[u] = *(const uint4*)(mine + o);
+#pragma unroll
+                    for (int s = 0; s < PER; ++s) vk[s][u] = *(const uint4*)(rowk[s] + o);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (k0 + 16 * u < nchunk) {
+                        double a[8], x[8];
+                        Elem<DT>::widen(vm[u], a);
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) nnp = fma(a[i], a[i], nnp);
+#pragma unroll
+                        for (int s = 0; s < PER; ++s) {
+                            Elem<DT>::widen(vk[s][u], x);
+#pragma unroll
+                            for (int i = 0; i < EPL; ++i) { dot[s] = fma(a[i], x[i], dot[s]); nnk[s] = fma(x[i], x[i], nnk[s]); }
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int sft = 1; sft <= 8; sft <<= 1) {
+                nnp += __shfl_xor(nnp, sft, 64);
+#pragma unroll
+                for (int s = 0; s < PER; ++s) { dot[s] += __shfl_xor(dot[s], sft, 64); nnk[s] += __shfl_xor(nnk[s], sft, 64); }
+            }
+#pragma unroll
             for (int s = 0; s < PER; ++s) {
                 const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
-                const int tk = __shfl(tk_mine, (lane & ~15) + s, 64);
-                group_dot64_with_norm<DT>(mine, kb + (size_t)tk * row_bytes, nchunk, part16, dot, nnk);
-                const double d = cos_dist64(dot, nnp, nnk);
+                const double d = cos_dist64(dot[s], nnp, nnk[s]);
                 const double term = pk >= q ? 0.0 : (pk == p ? 1.0 : exp(-d / d_n));
                 const double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
                 if (part16 == 0) { s_hi[s * 16 + g] = hi; s_lo[s * 16 + g] = term - hi; }
@@ -1295,7 +1303,8 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
                 w.heads, idx, w.tie_list, w.tie_cnt);
     // neighbours whose densities the fp32 terms cannot order: fp64 (a few tokens of an image)
-    const int rb = 1024 / bt.B < 4 ? 4 : (1024 / bt.B > 512 ? 512 : 1024 / bt.B);
+    // (a workgroup per work item for up to 64 listed tokens of a 4000-token sample; the others leave at once)
+    const int rb = 8192 / bt.B > 4096 ? 4096 : 8192 / bt.B;
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
                     rep, w.rho_fix, w.tie_list, w.tie_cnt);

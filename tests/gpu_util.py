@@ -25,7 +25,8 @@ def manifest():
 
 def sample_key(s: gen.Sample) -> str:
     grids = s.n // (s.config.gh * s.config.gw)
-    return f"{s.config.name}:s{s.seed}:g{grids}:l{s.lam:.2f}"
+    heads = "" if s.queries.shape[1] == s.config.n_kv else f":q{s.queries.shape[1]}"      # query heads, if not one per key head
+    return f"{s.config.name}:s{s.seed}:g{grids}:l{s.lam:.2f}{heads}"
 
 
 def d_c_of(s: gen.Sample) -> float:

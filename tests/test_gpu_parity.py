@@ -165,6 +165,20 @@ def test_reduce_end_to_end_headline_shape(seed):
     assert r["refine_overflow"] == 0 and r["rho_near_ties"] == 0 and r["nonfinite_seen"] == 0
 
 
+@pytest.mark.parametrize("seed", range(2))
+def test_reduce_headline_shape_with_28_query_heads(seed):
+    """The 7B model's own head counts: 28 query heads on 4 key heads, Q [7290, 3584] (Eq. 1 over 52 MB)."""
+    s = gen.make_sample("img_7b", seed, n_q=28)
+    cfg, d_c = s.config, gu.d_c_of(s)
+    d = gu.sample_to_dev(s)
+    o = P.pact_reduce(d["hidden"], d["keys"], d["keys"], d["q"], cfg.n_kv, cfg.d_h, 28, P.PactParams(s.lam, d_c, 2.0, 1.5))
+    torch.cuda.synchronize()
+    g = gu.trim(o, s.n)
+    assert_same(g, oracle_reduce(s, d_c), s, f"img_7b seed {seed}, 28 query heads")
+    m = gu.manifest()[gu.sample_key(s)]
+    assert g["rep"]["n_kept"] == m["q"] and g["rep"]["n_centers"] == m["C"] and _clean(g["rep"])
+
+
 def test_bf16_output_is_the_rounded_mean():
     s = gen.make_sample("tiny_bf16", 7)
     d_c = gu.d_c_of(s)
@@ -529,6 +543,24 @@ def test_clustering_on_hidden_states(name, seed, dtype):
     assert np.array_equal(out["center_idx"][:C].cpu().numpy(), ref["centers"])
     assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["labels"])
     assert 1 < C < s.n
+
+
+def test_clustering_on_hidden_states_at_full_width():
+    # the ablation at the benchmark image's own size: DBDPC on the 3584-wide bf16 hidden states of 7290 tokens
+    # (a 7 times longer contraction than the keys'; the oracle needs about half a minute for its 7290^2 matrix)
+    s = gen.make_sample("img_7b", 0)
+    m = gu.manifest()["img_7b:s0:g10:hidden"]
+    H = s.hidden.astype(np.float64)
+    ref = po.dbdpc(H, m["d_c"], 2.0)
+    out = P.dbdpc_cluster(gu.dev(s.hidden, "bf16"), m["d_c"], 2.0, want_rho=True)
+    torch.cuda.synchronize()
+    rep = P.read_report(out["rep"])
+    C = rep["n_centers"]
+    assert C == m["C"] == ref["centers"].size and _clean(rep)
+    assert np.array_equal(out["center_idx"][:C].cpu().numpy(), ref["centers"])
+    assert np.array_equal(out["cluster_id"].cpu().numpy(), ref["labels"])
+    np.testing.assert_allclose(out["rho"].cpu().numpy(), ref["rho"], rtol=1e-7, atol=0)
+    print(f"hidden-state clustering: C={C} dc_checked_pairs={rep['dc_checked_pairs']} rho_rechecked={rep['rho_rechecked']}")
 
 
 def test_calibration_copy_copies():
