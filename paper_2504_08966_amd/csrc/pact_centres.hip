@@ -807,11 +807,23 @@ struct NearArgs {
     const uint64_t* adj;
     float margin;
     int32_t* cluster_id; int32_t* cluster_counts;
+    int32_t* slots; int32_t* big;           // (optional) first members per cluster and the list of large clusters
     // assignment of kept tokens (Alg. 2 last loop); assign_blocks == 0: not in this launch
     const int32_t* idx; const uint64_t* cmask; const uint32_t* status; const int32_t* cnum; int assign_blocks;
     // recovery of pruned tokens (Eq. 8/9): the blocks before the assignment ones
     const int32_t* pruned_idx; const int32_t* center_idx; const float* cbest;
 };
+
+// Token `tok` joins cluster c (both local to the sample): the cluster's size goes up and, where
+// the caller keeps them, the token takes the next of the cluster's member slots; the member that
+// makes a cluster a large one puts it on the list of those.  counts/slots/big: the sample's.
+__device__ __forceinline__ void join_cluster(const NearArgs& a, pact_report* rp, int base, int c, int tok) {
+    const int s = atomicAdd(&a.cluster_counts[base + c], 1);
+    if (a.slots) {
+        if (s < MERGE_SLOTS) a.slots[(size_t)(base + c) * MERGE_SLOTS + s] = tok;
+        if (s == MERGE_BIG - 1) a.big[base + atomicAdd(&rp->reserved[0], 1)] = c;
+    }
+}
 
 // Alg. 2 last loop: every kept token joins the nearest centre.  Candidates are the centres
 // its bitmap row reaches (the nearest centre is within d_c, hence one of them; it need not
@@ -890,7 +902,7 @@ __device__ __forceinline__ void assign_body(const Batch& bt, const NearArgs& a, 
     }
     if (lane == 0) {
         cluster_id[sg.base + tok] = cid;
-        if (cid >= 0 && cluster_counts) atomicAdd(&cluster_counts[sg.base + cid], 1);
+        if (cid >= 0 && cluster_counts) join_cluster(a, rep + b, sg.base, cid, tok);
         note_odd_norm(rep + b, nnb[tok]);
     }
 }
@@ -1221,9 +1233,9 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
         }
         if (part == 0) {
             cluster_id[tok] = res;
-            // (recovered / dropped totals are derived from the cluster sizes by the CSR kernel: a
+            // (recovered / dropped totals are derived from the cluster sizes by the merge: a
             //  counter that every wavefront hits would serialise at one L2 address)
-            if (res >= 0 && cluster_counts) atomicAdd(&cluster_counts[res], 1);
+            if (res >= 0 && cluster_counts) join_cluster(a, rep + b, sg.base, res, tok);
             note_odd_norm(rep + b, nnb[tok]);
         }
     }
@@ -1357,6 +1369,7 @@ int launch_reincorporate(const Batch& bt, const Ws& w, const void* keys, pact_dt
     if (kept_idx) {
         a.idx = kept_idx; a.cmask = w.cmask; a.status = w.status; a.cnum = w.cnum;
         a.assign_blocks = (bt.n_max + 3) / 4;
+        a.slots = w.slots; a.big = w.big;     // (a full reduction: the merge follows)
     }
     if (kept_idx && bt.total >= 20000) {
         // Large batches are bound by how many wavefronts of these searches the chip holds: the two

@@ -7,10 +7,8 @@
 
 namespace pact {
 
-// Clusters of at least this many rows are merged first (a cluster of 30 rows takes several times
-// as long as one of 2, and started in the last turn it alone would be the end of the kernel);
-// the others follow in cluster order, i.e. in token order, which their reads profit from.
-constexpr int MERGE_BIG = 12;
+// The large clusters (MERGE_BIG rows or more) are merged first; the others follow in cluster order,
+// i.e. in token order, which their reads profit from.
 
 // Member lists (CSR) of all clusters of a sample, by one workgroup: cluster sizes (taken from
 // cluster_counts, or recounted from cluster_id for a stand-alone merge), their exclusive scan,
@@ -155,18 +153,23 @@ template <> struct StoreOut<PACT_BF16> {
 };
 
 // One workgroup per cluster (persistent over clusters).  grid (min(n_max, 4096), B), block 512.
+// The members of a cluster come from the CSR lists (slots == nullptr), or from the cluster's
+// member slots, or - a cluster with more members than slots - from a pass over cluster_id.
+// With slots the last workgroup also derives the recovered / dropped totals from the sizes.
 template <int HDT, int ODT>
 __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __restrict__ hidden, int h,
                                                      const int32_t* __restrict__ cluster_id,
                                                      const int32_t* __restrict__ center_idx,
-                                                     const pact_report* __restrict__ rep,
+                                                     pact_report* rep,
                                                      const int32_t* __restrict__ cluster_counts,
                                                      const int32_t* __restrict__ offsets,
                                                      const int32_t* __restrict__ members,
+                                                     const int32_t* __restrict__ slots,
                                                      const int32_t* __restrict__ big,
                                                      char* __restrict__ merged, int stream) {
     __shared__ int s_raw[MERGE_LDS_MEMBERS];
     __shared__ int s_sorted[MERGE_LDS_MEMBERS];
+    __shared__ int s_n;
     constexpr int EPL = Elem<HDT>::EPL;
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
@@ -180,6 +183,8 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
     // work items 0 .. nbig-1: the large clusters; then all clusters in order, the large ones skipped
     for (int k = blockIdx.x; k < nbig + C; k += gridDim.x) {
         const int c = (k < nbig) ? big[sg.base + k] : k - nbig;
+        // (the slots go out with the size: garbage beyond it, never used)
+        const int slot_pre = (slots && tid < MERGE_SLOTS) ? slots[(size_t)(sg.base + c) * MERGE_SLOTS + tid] : 0;
         int m = cluster_counts[sg.base + c];
         if (k >= nbig && m >= MERGE_BIG) continue;                 // (uniform over the workgroup)
         bool in_lds = true;
@@ -187,8 +192,24 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
         if (no_merge) {
             if (tid == 0) s_sorted[0] = center_idx[sg.base + c];
         } else if (m <= MERGE_LDS_MEMBERS) {
-            const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
-            for (int k = tid; k < m; k += 512) s_raw[k] = mem[k];
+            if (!slots) {
+                const int32_t* mem = members + sg.base + offsets[sg.base + b + c];
+                for (int k = tid; k < m; k += 512) s_raw[k] = mem[k];
+            } else if (m <= MERGE_SLOTS) {
+                if (tid < m) s_raw[tid] = slot_pre;
+            } else {
+                if (tid == 0) s_n = 0;
+                __syncthreads();
+                // (16 ids per thread and trip to memory)
+                for (int i0 = tid; i0 < sg.n; i0 += 16 * 512) {
+                    int ids[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) ids[u] = (i0 + 512 * u < sg.n) ? cluster_id[sg.base + i0 + 512 * u] : -1;
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (ids[u] == c) s_raw[min(atomicAdd(&s_n, 1), MERGE_LDS_MEMBERS - 1)] = i0 + 512 * u;
+                }
+            }
             __syncthreads();
             for (int k = tid; k < m; k += 512) {
                 const int v = s_raw[k];
@@ -245,12 +266,29 @@ __global__ __launch_bounds__(512) void merge_kernel(Batch bt, const char* __rest
                                              (size_t)e, outv, stream != 0);
         }
     }
+    if (slots && blockIdx.x == gridDim.x - 1) {
+        // every member of a cluster is a kept or a recovered token
+        int loc = 0;
+        for (int c = tid; c < C; c += 512) loc += cluster_counts[sg.base + c];
+        loc = (int)wave_sum_f64((double)loc);
+        __syncthreads();
+        if (tid == 0) s_n = 0;
+        __syncthreads();
+        if ((tid & 63) == 0 && loc) atomicAdd(&s_n, loc);
+        __syncthreads();
+        if (tid == 0) {
+            const int q = clamp_count(rep[b].n_kept, sg.n);
+            rep[b].n_reincorporated = s_n - q;
+            rep[b].n_dropped = sg.n - s_n;
+        }
+    }
 }
 
 template <int HDT>
 static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int32_t h,
-                          const int32_t* cluster_id, const int32_t* center_idx, const pact_report* rep,
-                          void* merged, pact_dtype out_dt, const int32_t* cluster_counts, hipStream_t st) {
+                          const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
+                          void* merged, pact_dtype out_dt, const int32_t* cluster_counts, const int32_t* slots,
+                          hipStream_t st) {
     dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
     // (the member rows are read for the last time and the merged rows are not read again by this
     //  library: both with the streaming hint when the hidden states alone exceed what the
@@ -258,10 +296,10 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
     const int stream = hidden_streams(bt.total, h, Elem<HDT>::BYTES) ? 1 : 0;
     if (out_dt == PACT_BF16)
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_BF16>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged, stream);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, slots, w.big, (char*)merged, stream);
     else
         PACT_LAUNCH("merge_mean", (merge_kernel<HDT, PACT_F32>), grid, dim3(512), st, bt, (const char*)hidden,
-                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, w.big, (char*)merged, stream);
+                    h, cluster_id, center_idx, rep, cluster_counts, w.offsets, w.members, slots, w.big, (char*)merged, stream);
     return PACT_OK;
 }
 
@@ -295,22 +333,26 @@ int launch_merge(const Batch& bt, const Ws& w, const void* hidden, pact_dtype h_
                  const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                  void* merged, pact_dtype out_dt, int32_t* cluster_counts, bool recount,
                  hipStream_t st) {
-    const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(int);
-    static size_t raised = 0;
-    if (lds > 48 * 1024 && lds > raised) {
-        if (hipFuncSetAttribute((const void*)scan_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return PACT_ERR_HIP;
-        raised = lds;
+    // recount: a stand-alone merge, which has cluster_id alone to go by: member lists by a pass of
+    // their own.  Otherwise the clustering stages have noted sizes, first members and large clusters.
+    if (recount) {
+        const size_t lds = (size_t)((bt.n_max + 63) / 64 * 64) * sizeof(int);
+        static size_t raised = 0;
+        if (lds > 48 * 1024 && lds > raised) {
+            if (hipFuncSetAttribute((const void*)scan_fill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds) != hipSuccess)
+                return PACT_ERR_HIP;
+            raised = lds;
+        }
+        PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id,
+                          rep, cluster_counts, 1, 0, w.offsets, w.members, w.big);
     }
-    PACT_LAUNCH_SHMEM("scan_fill", scan_fill_kernel, dim3(bt.B), dim3(1024), lds, st, bt, cluster_id,
-                      rep, cluster_counts, recount ? 1 : 0, recount ? 0 : 1,
-                      w.offsets, w.members, w.big);
+    const int32_t* slots = recount ? nullptr : w.slots;
     if (h_dt == PACT_BF16)
         return launch_merge_k<PACT_BF16>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
-                                         cluster_counts, st);
+                                         cluster_counts, slots, st);
     return launch_merge_k<PACT_F32>(bt, w, hidden, h, cluster_id, center_idx, rep, merged, out_dt,
-                                    cluster_counts, st);
+                                    cluster_counts, slots, st);
 }
 
 }  // namespace pact
