@@ -11,8 +11,10 @@ namespace pact {
 //   blocks [nQ, nQ + nKeyBlocks)      : one wavefront per token: squared key norm (fp64),
 //                                       reciprocal norm (fp32), cleared bitmap row, and the
 //                                       per-token initial state (status, cluster id, counts);
-//   blocks [0, nQ = QG_CHUNKS or 0)   : Eq. 1 pass 1, column sums of one row chunk of Q.
-// grid (nKeyBlocks + (do_q ? QG_CHUNKS : 0), B), block 256.
+//   blocks [0, nQ)                    : Eq. 1 pass 1, column sums of one row chunk of Q; rows wider than
+//                                       1024 columns are shared out in groups of 1024 columns
+//                                       (nQ = QG_CHUNKS x groups, or 0 without a query pass).
+// grid (nKeyBlocks + nQ, B), block 256.
 struct PrepArgs {
     const char* keys; int32_t dk;
     const char* q; int32_t qcols;            // q == nullptr: no query pass
@@ -21,7 +23,7 @@ struct PrepArgs {
     pact_report* rep; int32_t* cluster_id; int32_t* cluster_counts;
     const int32_t* n_idx_dev; uint32_t* zeros;
     uint16_t* ksplit;                        // fp32 keys only: [total][3][dk rounded up to 8] bf16 parts for the Gram passes
-    int32_t mode; int32_t n_key_blocks;
+    int32_t mode; int32_t n_key_blocks; int32_t n_q_blocks;
 };
 
 template <int KDT, int QDT>
@@ -29,7 +31,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int lane = threadIdx.x & 63;
-    const int n_q_blocks = a.q ? QG_CHUNKS : 0;      // the query chunks come first: they are the longer job
+    const int n_q_blocks = a.n_q_blocks;             // the query chunks come first: they are the longer job
     if ((int)blockIdx.x >= n_q_blocks) {
         const int kblk = blockIdx.x - n_q_blocks;
         if (kblk == 0 && b == 0 && threadIdx.x < 64) a.zeros[threadIdx.x] = 0u;
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         return;
     }
     // ---- Eq. 1, pass 1
-    const int chunk = blockIdx.x;
+    const int chunk = blockIdx.x % QG_CHUNKS, cgroup = blockIdx.x / QG_CHUNKS;
     const int rows_per = (sg.n + QG_CHUNKS - 1) / QG_CHUNKS;
     const int r0 = chunk * rows_per;
     const int r1 = min(sg.n, r0 + rows_per);
@@ -143,7 +145,8 @@ __global__ __launch_bounds__(256) void prep_kernel(Batch bt, PrepArgs a) {
         }
     };
     if (RG == 1) {
-        for (int c = threadIdx.x * 4; c < a.qcols; c += 256 * 4) {
+        const int c = cgroup * 1024 + threadIdx.x * 4;
+        if (c < a.qcols) {
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             sum_rows(c, acc);
 #pragma unroll
@@ -260,11 +263,23 @@ __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols
     hnorm_row<HDT>(hidden, h, (size_t)sg.base + i, threadIdx.x & 63, hnorm, stream != 0);
 }
 
+constexpr int LOGITS_MAX_REP = 8;        // query heads per key head that the grouped fast path handles
+constexpr int LOGITS_QG_LDS = 4096;      // columns of the global query that its LDS copy holds
+// key row of at most 1 KB, a power-of-two number of whole 16-byte chunks per head
+__host__ __device__ inline bool logits_shaped(int n_kv, int d_h, int elem_bytes) {
+    const int lph = d_h * elem_bytes / 16;
+    return (size_t)n_kv * d_h * elem_bytes <= 1024 && lph * 16 == d_h * elem_bytes && lph >= 1 && (lph & (lph - 1)) == 0;
+}
+__host__ __device__ inline bool logits_grouped(int n_kv, int n_q, int d_h, int elem_bytes) {
+    const int rep = n_q / n_kv;
+    return rep > 1 && rep <= LOGITS_MAX_REP && logits_shaped(n_kv, d_h, elem_bytes) && n_q * d_h <= LOGITS_QG_LDS;
+}
+
 // ------------------------------------------------------------------------------------------
 // Eq. 2, pass 1: one wavefront per token computes the n_q logits k_i^(g(j)) . Qg^(j); the
 // workgroup (SCORE_TOK_PER_WG tokens) then leaves one online-softmax partial (max, sum of exp)
 // per head.  grid (ceil(n_max/16), B), block 1024.
-template <int KDT, int HDT>
+template <int KDT, int HDT, bool GROUPED>
 __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char* __restrict__ keys, int n_kv, int d_h,
                                                             int n_q, const double* __restrict__ qg,
                                                             double* __restrict__ logits,
@@ -272,6 +287,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
                                                             const char* __restrict__ hidden, int h,
                                                             double* __restrict__ hnorm, int hshare, int stream) {
     __shared__ double s_l[SCORE_TOK_PER_WG][PACT_MAX_QHEADS];
+    __shared__ double s_qg[GROUPED ? LOGITS_QG_LDS : 1];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
     const int lane = threadIdx.x & 63;
@@ -289,14 +305,58 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
     const double* qgb = qg + (size_t)b * qcols;
     const size_t krow = (size_t)n_kv * d_h * Elem<KDT>::BYTES;
 
-    // Fast path (the usual shapes: key row of at most 1 KB, one query head per key head, a
-    // power-of-two number of 16-byte chunks per head): the whole key row is one load per lane
-    // and a head's logit is a reduction over the few lanes that hold it.
+    // Fast paths (the usual shapes: key row of at most 1 KB, a power-of-two number of 16-byte
+    // chunks per head): the whole key row is one load per lane and a head's logit is a reduction
+    // over the few lanes that hold it.  `fast`: one query head per key head.  GROUPED (its own
+    // build; the host checks logits_grouped()): up to LOGITS_MAX_REP query heads per key head
+    // (grouped-query attention); a lane then forms the partial logits of all query heads of its
+    // key head, against a copy of the global query in LDS.
     const int lph = (int)((size_t)d_h * Elem<KDT>::BYTES / 16);      // lanes (chunks) per head
-    const bool fast = rep == 1 && krow <= 1024 && (size_t)lph * 16 == (size_t)d_h * Elem<KDT>::BYTES &&
-                      lph >= 1 && (lph & (lph - 1)) == 0;
+    const bool fast = rep == 1 && logits_shaped(n_kv, d_h, Elem<KDT>::BYTES);
     const int i = t0 + wave;
-    if (i < sg.n) {
+    if constexpr (GROUPED) {
+        // The copy is laid out so that the lanes of a wavefront read neighbouring words: element k
+        // of chunk cc of query head kvh * rep + r sits at ((r * EPL + k) * n_kv + kvh) * lph + cc,
+        // i.e. at (r * EPL + k) * (lanes that hold the key row) + (the lane that needs it).
+        constexpr int EPL = Elem<KDT>::EPL;
+        const int klanes = n_kv * lph;
+        for (int c = threadIdx.x; c < qcols; c += 1024) {
+            const int j = c / d_h, e = c - j * d_h;
+            s_qg[(((j % rep) * EPL + (e % EPL)) * n_kv + j / rep) * lph + e / EPL] = qgb[c];
+        }
+        __syncthreads();
+        if (i < sg.n) {
+            const size_t g = (size_t)sg.base + i;
+            const bool klane = lane < klanes;
+            const int kvh = lane / lph;
+            double acc[LOGITS_MAX_REP];
+#pragma unroll
+            for (int r = 0; r < LOGITS_MAX_REP; ++r) acc[r] = 0.0;
+            if (klane) {
+                const uint4 kv = *(const uint4*)(keys + g * krow + (size_t)lane * 16);
+                double x[8];
+                Elem<KDT>::widen(kv, x);
+#pragma unroll
+                for (int r = 0; r < LOGITS_MAX_REP; ++r)
+                    if (r < rep) {
+#pragma unroll
+                        for (int k = 0; k < EPL; ++k) acc[r] = fma(x[k], s_qg[(r * EPL + k) * klanes + lane], acc[r]);
+                    }
+            }
+#pragma unroll
+            for (int r = 0; r < LOGITS_MAX_REP; ++r)
+                if (r < rep)
+                    for (int sft = 1; sft < lph; sft <<= 1) acc[r] += __shfl_xor(acc[r], sft, 64);
+            if (klane && (lane & (lph - 1)) == 0) {
+#pragma unroll
+                for (int r = 0; r < LOGITS_MAX_REP; ++r)
+                    if (r < rep) {
+                        logits[g * n_q + kvh * rep + r] = acc[r];
+                        s_l[wave][kvh * rep + r] = acc[r];
+                    }
+            }
+        }
+    } else if (i < sg.n) {
         const size_t g = (size_t)sg.base + i;
         const char* kp = keys + g * krow;
         if (fast) {
@@ -406,46 +466,83 @@ __device__ __forceinline__ void combine_softmax_partials(const double* part, int
 }
 
 // ------------------------------------------------------------------------------------------
-// Eq. 2, pass 2: combine the partials into (max, normaliser) per head, then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
-// grid (ceil(n_max/256), B), block 256.
-__global__ __launch_bounds__(256) void score_final_kernel(Batch bt, int n_q,
-                                                          const double* __restrict__ logits,
-                                                          const double* __restrict__ hnorm,
-                                                          const double* __restrict__ sm_part,
-                                                          float* __restrict__ scores) {
+// Eq. 2, pass 2 for many query heads, first half: (max, normaliser) of every head, once per sample
+// (left to every workgroup of the kernel below, the n_q * n / 16 exponentials of the combine are
+// most of that kernel's time from a dozen heads on).  mz: [B][n_q][2].  grid (n_q, B), block 64.
+__global__ __launch_bounds__(64) void softmax_combine_kernel(Batch bt, int n_q, const double* __restrict__ sm_part,
+                                                             double* __restrict__ mz) {
+    const int b = blockIdx.y, j = blockIdx.x;
+    const Seg sg = bt.s[b];
+    if (sg.n <= 0) return;
+    const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+    const int nwg = (sg.n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
+    double m, z;
+    combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, threadIdx.x, m, z);
+    if (threadIdx.x == 0) { mz[((size_t)b * n_q + j) * 2] = m; mz[((size_t)b * n_q + j) * 2 + 1] = z; }
+}
+
+// Eq. 2, pass 2: (max, normaliser) per head - combined here from the partials, or read from mz -
+// then s_i = |h_i| * (1/n_q) sum_j exp(l_ij - M_j) / Z_j.
+// A workgroup finishes TOK tokens with TOK * PARTS threads: thread (token, part) takes the heads
+// part, part + PARTS, ... of its token (and its wavefront the heads wave, wave + TOK * PARTS / 64,
+// ... of the combine); the parts of a token meet in LDS and are added in the order of their numbers.
+// grid (ceil(n_max/TOK), B), block TOK * PARTS.
+template <int TOK, int PARTS>
+__global__ __launch_bounds__(TOK * PARTS) void score_final_kernel(Batch bt, int n_q,
+                                                                  const double* __restrict__ logits,
+                                                                  const double* __restrict__ hnorm,
+                                                                  const double* __restrict__ sm_part,
+                                                                  const double* __restrict__ mz,
+                                                                  float* __restrict__ scores) {
     __shared__ double s_M[PACT_MAX_QHEADS], s_Z[PACT_MAX_QHEADS];
+    __shared__ double s_acc[PARTS > 1 ? PARTS - 1 : 1][TOK];
     const int b = blockIdx.y;
     const Seg sg = bt.s[b];
-    if (blockIdx.x * 256 >= sg.n) return;
+    if (blockIdx.x * TOK >= sg.n) return;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
+    const int tok = threadIdx.x % TOK, part = threadIdx.x / TOK;
     const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     const int nwg = (sg.n + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
     // this thread's token: its norm and first logits are requested before the partials are
     // combined (they do not depend on them)
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int i = blockIdx.x * TOK + tok;
     const size_t g = (size_t)sg.base + min(i, sg.n - 1);
     const double hn = hnorm[g];
     double lg[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) lg[j] = (j < n_q) ? logits[g * n_q + j] : 0.0;
-    for (int j = wave; j < n_q; j += 4) {
-        double m, z;
-        combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
-        if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
+    for (int u = 0; u < 4; ++u) lg[u] = (part + u * PARTS < n_q) ? logits[g * n_q + part + u * PARTS] : 0.0;
+    if (mz) {
+        if ((int)threadIdx.x < n_q) {
+            s_M[threadIdx.x] = mz[((size_t)b * n_q + threadIdx.x) * 2];
+            s_Z[threadIdx.x] = mz[((size_t)b * n_q + threadIdx.x) * 2 + 1];
+        }
+    } else {
+        for (int j = wave; j < n_q; j += TOK * PARTS / 64) {
+            double m, z;
+            combine_softmax_partials(sm_part + ((size_t)b * smwg * n_q + j) * 2, nwg, n_q * 2, lane, m, z);
+            if (lane == 0) { s_M[j] = m; s_Z[j] = z; }
+        }
     }
     __syncthreads();
-    if (i >= sg.n) return;
     // the two ablations of Eq. 2: without the norm; norm only (softmax term -> 1/n)
-    double p = 1.0 / (double)sg.n;
-    if (!(sg.flags & PACT_FLAG_SCORE_NORM_ONLY)) {
-        double acc = 0.0;
+    const bool norm_only = (sg.flags & PACT_FLAG_SCORE_NORM_ONLY) != 0;
+    double acc = 0.0;
+    if (!norm_only && i < sg.n) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (j < n_q) acc += exp(lg[j] - s_M[j]) / s_Z[j];
-        for (int j = 4; j < n_q; ++j) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
-        p = acc / (double)n_q;
+        for (int u = 0; u < 4; ++u)
+            if (part + u * PARTS < n_q) acc += exp(lg[u] - s_M[part + u * PARTS]) / s_Z[part + u * PARTS];
+        for (int j = part + 4 * PARTS; j < n_q; j += PARTS) acc += exp(logits[g * n_q + j] - s_M[j]) / s_Z[j];
     }
+    if (PARTS > 1) {
+        if (part > 0) s_acc[part - 1][tok] = acc;
+        __syncthreads();
+        if (part > 0) return;
+#pragma unroll
+        for (int k = 0; k + 1 < PARTS; ++k) acc += s_acc[k][tok];
+    }
+    if (i >= sg.n) return;
+    const double p = norm_only ? 1.0 / (double)sg.n : acc / (double)n_q;
     scores[g] = (float)((sg.flags & PACT_FLAG_SCORE_NO_NORM) ? p : hn * p);
 }
 
@@ -635,7 +732,8 @@ int launch_prep(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_dt,
     a.rep = rep; a.cluster_id = cluster_id; a.cluster_counts = cluster_counts; a.n_idx_dev = n_idx_dev;
     a.zeros = w.zeros; a.ksplit = w.ksplit;
     a.mode = mode; a.n_key_blocks = keys ? (bt.n_max + 3) / 4 : 0;
-    dim3 grid(a.n_key_blocks + (q ? QG_CHUNKS : 0), bt.B);
+    a.n_q_blocks = q ? QG_CHUNKS * ((qcols + 1023) / 1024) : 0;
+    dim3 grid(a.n_key_blocks + a.n_q_blocks, bt.B);
     return (k_dt == PACT_BF16) ? launch_prep_q<PACT_BF16>(bt, a, q_dt, grid, st)
                                : launch_prep_q<PACT_F32>(bt, a, q_dt, grid, st);
 }
@@ -672,14 +770,14 @@ static int launch_logits_hnorm(const Batch& bt, const Ws& w, const ScoreIn& in, 
     // tokens past the split: n - split(n) <= n - floor(n * share / 256), which grows with n
     const int rest = bt.n_max - ((bt.n_max * share) >> 8);
     dim3 grid(n_logit_blocks + (rest + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
-    if (in.k_dt == PACT_BF16)
-        PACT_LAUNCH("score_logits", (score_logits_kernel<PACT_BF16, HDT>), grid, dim3(1024), st, bt,
-                    (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part, n_logit_blocks,
-                    (const char*)in.hidden, in.h, w.hnorm, share, stream);
-    else
-        PACT_LAUNCH("score_logits", (score_logits_kernel<PACT_F32, HDT>), grid, dim3(1024), st, bt,
-                    (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part, n_logit_blocks,
-                    (const char*)in.hidden, in.h, w.hnorm, share, stream);
+    const bool grouped = logits_grouped(in.n_kv, in.n_q, in.d_h, in.k_dt == PACT_BF16 ? 2 : 4);
+#define PACT_LOGITS(KDT, G)                                                                                          \
+    PACT_LAUNCH("score_logits", (score_logits_kernel<KDT, HDT, G>), grid, dim3(1024), st, bt,                        \
+                (const char*)in.keys_pre, in.n_kv, in.d_h, in.n_q, w.qg, w.logits, w.sm_part, n_logit_blocks,        \
+                (const char*)in.hidden, in.h, w.hnorm, share, stream)
+    if (in.k_dt == PACT_BF16) { if (grouped) PACT_LOGITS(PACT_BF16, true); else PACT_LOGITS(PACT_BF16, false); }
+    else { if (grouped) PACT_LOGITS(PACT_F32, true); else PACT_LOGITS(PACT_F32, false); }
+#undef PACT_LOGITS
     return PACT_OK;
 }
 
@@ -694,8 +792,18 @@ int launch_score(const Batch& bt, const Ws& w, const ScoreIn& in, hipStream_t st
 }
 
 int launch_score_only(const Batch& bt, const Ws& w, int n_q, float* scores, hipStream_t st) {
-    PACT_LAUNCH("score_final", score_final_kernel, dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt,
-                n_q, w.logits, w.hnorm, w.sm_part, scores);
+    // Many query heads: the combine once per sample in a launch of its own (its result in the
+    // array of the query's chunk sums, which the global query has replaced by now), and sixteen
+    // threads per token.
+    if (n_q > 8) {
+        double* mz = w.qg_part;
+        PACT_LAUNCH("softmax_combine", softmax_combine_kernel, dim3(n_q, bt.B), dim3(64), st, bt, n_q, w.sm_part, mz);
+        PACT_LAUNCH("score_final", (score_final_kernel<64, 16>), dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt,
+                    n_q, w.logits, w.hnorm, w.sm_part, (const double*)mz, scores);
+    } else {
+        PACT_LAUNCH("score_final", (score_final_kernel<256, 1>), dim3((bt.n_max + 255) / 256, bt.B), dim3(256), st, bt,
+                    n_q, w.logits, w.hnorm, w.sm_part, (const double*)nullptr, scores);
+    }
     return PACT_OK;
 }
 
