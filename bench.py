@@ -416,6 +416,28 @@ def main():
                 ent[tag] = {"us": round(tbl[k], 2), "GB/s": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
         hbm_stages[k] = ent
 
+    # what a plain copy reaches on this machine (the library's copy kernel; bytes read + bytes written per
+    # second): the yardstick for stages that read and write, next to the 8 TB/s data-sheet peak
+    hbm_reference = {}
+    for mib in (32, 256):
+        src = torch.full((mib << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            P.pact_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(20):
+            P.pact_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t1) / 20 * 1e6
+        hbm_reference[f"copy_{mib}MiB"] = {"us": round(us, 1), "GB/s_moved": round(2 * (mib << 20) / us / 1e3, 1)}
+        del src, dst
+    for k, ent in hbm_stages.items():
+        ref = hbm_reference["copy_32MiB"]["GB/s_moved"]
+        for tag in ("cold", "cold_read_scrub", "warm"):
+            if tag in ent:
+                ent[tag]["frac_of_copy_rate"] = round(ent[tag]["GB/s"] / ref, 4)
+
     cpu = None if args.no_cpu_baseline else cpu_baseline(s, d_c)
 
     line = {
@@ -437,6 +459,7 @@ def main():
         "us_per_step_cold_read_scrub": pct(coldr_us) if coldr_us is not None else None,
         "us_per_step_warm": pct(warm_us),
         "hbm_stages": hbm_stages,
+        "hbm_reference": hbm_reference,
         "kernels_us_per_step": {k: round(v, 2) for k, v in sorted(per_step_us.items(), key=lambda kv: -kv[1])},
         "kernels_us_per_step_cold": {k: round(v, 2) for k, v in sorted(cold_per_launch.items(), key=lambda kv: -kv[1])},
         "kernels_us_per_step_cold_read_scrub": {k: round(v, 2) for k, v in sorted(coldr_per_launch.items(), key=lambda kv: -kv[1])},

@@ -289,7 +289,14 @@ static int launch_merge_k(const Batch& bt, const Ws& w, const void* hidden, int3
                           const int32_t* cluster_id, const int32_t* center_idx, pact_report* rep,
                           void* merged, pact_dtype out_dt, const int32_t* cluster_counts, const int32_t* slots,
                           hipStream_t st) {
-    dim3 grid(bt.n_max < 4096 ? bt.n_max : 4096, bt.B);
+    // One workgroup per cluster where the grid allows it (a tenth of the workgroups looping over
+    // ten clusters each took a third longer: a cluster is a chain of two trips to memory).  The
+    // number of clusters is known on the device only; in a batch a third of the longest sample's
+    // tokens (the workloads here end with 0.25 .. 0.3 n clusters) saves the dispatch of thousands
+    // of workgroups that find nothing to do (8 videos: 113 -> 109 us).
+    int gx = bt.n_max < 4096 ? bt.n_max : 4096;
+    if (bt.B > 1 && gx > bt.n_max / 3 + 64) gx = bt.n_max / 3 + 64;
+    dim3 grid(gx, bt.B);
     // (the member rows are read for the last time and the merged rows are not read again by this
     //  library: both with the streaming hint when the hidden states alone exceed what the
     //  last-level cache keeps)
