@@ -16,6 +16,7 @@ dropped) and how close any decision-relevant distance comes to a threshold.
 """
 from __future__ import annotations
 
+import hashlib
 import json
 import os
 import sys
@@ -36,6 +37,19 @@ def sample_key(s: gen.Sample) -> str:
     grids = s.n // (s.config.gh * s.config.gw)
     heads = "" if s.queries.shape[1] == s.config.n_kv else f":q{s.queries.shape[1]}"      # query heads, if not one per key head
     return f"{s.config.name}:s{s.seed}:g{grids}:l{s.lam:.2f}{heads}"
+
+
+def digest(a) -> str:
+    """Fingerprint of an integer array (values as int64, in order): what the GPU tests compare where the
+    oracle is not run again."""
+    return hashlib.sha256(np.ascontiguousarray(a, dtype=np.int64).tobytes()).hexdigest()[:24]
+
+
+def oracle_digests(s: gen.Sample, d_c: float) -> dict:
+    """Fingerprints of the oracle's discrete results for the whole of Alg. 3 on sample s."""
+    o = po.pact_reduce(s.hidden, s.keys, s.queries, s.keys, s.lam, d_c, D_N, ALPHA)
+    return {"kept_idx": digest(o["kept_idx"]), "center_idx": digest(o["center_idx"]),
+            "cluster_id": digest(o["cluster_id"]), "counts": digest(o["counts"])}
 
 
 def calibrate(s: gen.Sample, target: float) -> dict:
@@ -135,8 +149,13 @@ def groups():
         "img_7b_q28": lambda: [gen.make_sample("img_7b", s, n_q=28) for s in range(2)],
         # the long video with nothing pruned: all 16384 tokens are clustered
         "vid_long_all": lambda: [gen.make_sample("vid_long", 0, lam=0.0)],
+        # further long videos, stored with fingerprints of the oracle's results (DIGEST_GROUPS)
+        "vid_long_more": lambda: [gen.make_sample("vid_long", s) for s in range(3, 10)],
     }
     return g
+
+
+DIGEST_GROUPS = ("vid_long_more",)
 
 
 def main(argv):
@@ -169,6 +188,8 @@ def main(argv):
                 continue
             t = time.time()
             entry = calibrate(s, s.config.target_reduction)
+            if name in DIGEST_GROUPS:
+                entry["digest"] = oracle_digests(s, entry["d_c"])
             if os.path.exists(MANIFEST):           # (another run may have added entries meanwhile)
                 with open(MANIFEST) as f:
                     manifest = json.load(f)

@@ -154,7 +154,9 @@ __device__ __forceinline__ void nearest_candidate(lds_i32* cand, lds_i32* ctok, 
 //       Eq. 5 in fp64 and clear the bit if the distance exceeds d_c (one wavefront per pair);
 //   the other blocks: Eq. 6 completed, rho_p = sum over the row blocks of the column
 //       partials (64 tokens x 4 slices per block).  With d_n = 2 every term is an fp32 value
-//       in [e^-1, 1], so these fp64 additions are exact whatever their order.
+//       in [e^-1, 1], so these fp64 additions are exact whatever their order; for other d_n they
+//       are rounded, in an order that is fixed for a given shape (no atomics anywhere), and
+//       the order of close densities is settled in fp64 further down the line anyway.
 constexpr int REFINE_BLOCKS = 768;     // 3072 wavefronts: one pair each on the benchmark image (2 200 pairs), so that no
                                        // wavefront evaluates two or three rows one after the other (256: 1.2 us longer)
 
@@ -1315,8 +1317,10 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     PACT_LAUNCH("build_preds", build_preds_kernel, gtok, dim3(256), st, bt, rep, w.adj, w.rho, w.preds,
                 w.heads, idx, w.tie_list, w.tie_cnt);
     // neighbours whose densities the fp32 terms cannot order: fp64 (a few tokens of an image)
-    // (a workgroup per work item for up to 64 listed tokens of a 4000-token sample; the others leave at once)
-    const int rb = 8192 / bt.B > 4096 ? 4096 : 8192 / bt.B;
+    // (one sample: 2048 workgroups, a work item each for up to 32 listed tokens of a 4000-token sample -
+    //  the chip holds 512 of them at a time, and 4096 took 0.8 us longer to dispatch; a batch: 8192
+    //  shared out equally, since the listed tokens are not spread evenly over the samples)
+    const int rb = bt.B == 1 ? 2048 : 8192 / bt.B;
     if (k_dt == PACT_BF16)
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
                     rep, w.rho_fix, w.tie_list, w.tie_cnt);

@@ -275,6 +275,33 @@ def test_long_video_fp32_keys_nothing_pruned():
     print(f"vid_long lambda 0: C={m['C']} rho_rechecked={g['rep']['rho_rechecked']} dc_checked_pairs={g['rep']['dc_checked_pairs']}")
 
 
+@pytest.mark.parametrize("seed", range(3, 10))
+def test_long_video_further_seeds_against_stored_fingerprints(seed):
+    # Seven more 16384-token videos.  The oracle is not run again here: `python -m oracle.calibrate_dc
+    # vid_long_more` stored fingerprints of its kept set, centres, cluster ids and cluster sizes with the
+    # calibrated d_c; the merged rows are checked against means recomputed from the GPU's own cluster ids
+    # (a property that holds whatever the clusters are; that the clusters are the oracle's is the
+    # fingerprints' part).
+    from oracle.calibrate_dc import digest
+    s = gen.make_sample("vid_long", seed)
+    m = gu.manifest()[gu.sample_key(s)]
+    g = gu.gpu_reduce(s, m["d_c"])
+    r = g["rep"]
+    assert (r["n_kept"], r["n_centers"], r["n_reincorporated"], r["n_dropped"]) == \
+           (m["q"], m["C"], m["n_reincorporated"], m["n_dropped"]), (r, m)
+    for name, arr in (("kept_idx", g["kept_idx"]), ("center_idx", g["center_idx"]), ("cluster_id", g["cluster_id"]),
+                      ("counts", g["counts"])):
+        assert digest(arr) == m["digest"][name], f"vid_long seed {seed}: {name} differs from the oracle's"
+    assert _clean(r)
+    H = np.asarray(s.hidden, dtype=np.float64)
+    rng = np.random.default_rng(seed)
+    for c in rng.choice(m["C"], 64, replace=False):
+        members = np.flatnonzero(g["cluster_id"] == c)
+        assert members.size == g["counts"][c] and g["center_idx"][c] in members
+        np.testing.assert_allclose(g["merged"][c], H[members].mean(axis=0), rtol=rtol_for(s.config), atol=1e-30)
+    print(f"vid_long seed {seed}: rho_rechecked={r['rho_rechecked']} dc_checked_pairs={r['dc_checked_pairs']}")
+
+
 # ------------------------------------------------------------------ degenerate inputs
 
 def _mk(keys, hidden=None, queries=None, name="tiny_f32"):
