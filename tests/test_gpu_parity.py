@@ -302,6 +302,32 @@ def test_long_video_further_seeds_against_stored_fingerprints(seed):
     print(f"vid_long seed {seed}: rho_rechecked={r['rho_rechecked']} dc_checked_pairs={r['dc_checked_pairs']}")
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_structured_inputs_at_cutoffs_and_normalisers_outside_the_calibrated_set(block):
+    # images, videos and small grids of the generator (near-duplicate neighbours, blobs) at seeds that are
+    # not in the manifest, with a cutoff that is NOT moved into a gap of the pair distances (pairs within
+    # 1e-6 of it do occur: the fp64 re-check has to agree with the oracle on them) and density
+    # normalisers from 0.25 to 8; ten cases per block
+    rng = np.random.default_rng(9000 + block)
+    base_dc = {"img_7b": 0.0203, "img_0p5b": 0.05, "tiny_bf16": 0.0185, "vid_7b": 0.004}
+    seen = {"dc_near_ties": 0, "rho_rechecked": 0}
+    for case in range(10):
+        name = str(rng.choice(["img_7b", "img_7b", "img_0p5b", "vid_7b", "tiny_bf16"]))
+        seed = int(rng.integers(100, 100000))
+        grids = int(rng.choice([2, 4, 5, 10])) if name == "img_7b" else None
+        s = gen.make_sample(name, seed, grids=grids, lam=float(rng.choice([0.0, 0.3, 0.45, 0.6])))
+        d_n = float(rng.choice([0.25, 0.5, 1.0, 2.0, 2.0, 4.0, 8.0]))
+        alpha = float(rng.choice([1.0, 1.5, 2.0]))
+        d_c = float(np.float32(base_dc[name] * rng.uniform(0.6, 1.5)))
+        what = f"{name} seed {seed} n={s.n} lambda={s.lam} d_n={d_n} alpha={alpha} d_c={d_c:.5f}"
+        g = gu.gpu_reduce(s, d_c, d_n=d_n, alpha=alpha)
+        assert_same(g, oracle_reduce(s, d_c, d_n=d_n, alpha=alpha), s, what)
+        assert g["rep"]["refine_overflow"] == 0 and g["rep"]["nonfinite_seen"] == 0, what
+        for k in seen:
+            seen[k] += g["rep"][k]
+    print(f"block {block}: {seen}")
+
+
 # ------------------------------------------------------------------ degenerate inputs
 
 def _mk(keys, hidden=None, queries=None, name="tiny_f32"):
