@@ -512,16 +512,29 @@ __device__ __forceinline__ bool check_pending15(const uint4& v0, const uint4& v1
 // centres are numbered in ascending token order and published.
 //  * The first round needs no look-ups: nothing is decided yet, so exactly the tokens without a
 //    preceding neighbour become centres.  It is folded into the set-up.
-//  * Each thread owns the tokens tid, tid + 1024, ... and keeps the 8-byte heads of the first
-//    four in registers; tokens with more than HEAD_PREDS preceding neighbours are collected in
-//    a list, and thread i also keeps the first 32 bytes of the i-th listed token's record.
-//    Per token a bit mask remembers which predecessors are still undecided, so a round only
-//    looks at those.
+//  * Tokens with one to HEAD_PREDS preceding neighbours (most of the others) go on a work list of
+//    8-byte entries (position and the predecessors that are still undecided).  A round reads the
+//    list, looks the predecessors' statuses up, decides what it can and appends the entries that
+//    stay undecided - without the predecessors found not to be centres - to the list of the next
+//    round (a ballot and one LDS atomic per wavefront): a round costs what is still undecided, not
+//    n, and the wavefronts beyond the list's end have nothing to do.  Two lists alternate; they
+//    live in LDS (WL_LDS, samples of up to RESOLVE_LDS_TOKENS tokens) or in the workspace.
+//  * Tokens with more preceding neighbours are collected in a list of their own; thread i keeps
+//    the first 32 bytes of the i-th listed token's record and a bit mask of the predecessors
+//    that are still undecided.
 //  * Tokens whose list overflowed the record are evaluated from their bitmap row by a whole
 //    wavefront.
 // grid (B), block 1024, dynamic LDS: (n_max + 64) bytes (status) + n_max * 2 bytes (token
-// lists: long lists from the front, overflowed from the back) + W * 4 bytes (centres per word).
+// lists: long lists from the front, overflowed from the back) + W * 4 bytes (centres per word)
+// [+ 2 * 8 * n_max bytes of work lists].
 constexpr int RESOLVE_CACHED = 4;
+typedef uint32_t wl_entry __attribute__((ext_vector_type(2)));      // position | predecessor << 16, two more predecessors (0xFFFF: none)
+typedef __attribute__((address_space(3))) wl_entry lds_wl_entry;
+template <bool WL_LDS> struct WorkList;
+template <> struct WorkList<true> { typedef lds_wl_entry* ptr; };
+template <> struct WorkList<false> { typedef wl_entry* ptr; };
+
+template <bool WL_LDS>
 __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_report* rep,
                                                               const uint64_t* __restrict__ adj,
                                                               double* rho, double* rho_opt,
@@ -531,9 +544,9 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
                                                               const int32_t* __restrict__ tie_cnt,
                                                               const double* __restrict__ rho_fix,
                                                               uint32_t* status, int32_t* cnum,
-                                                              uint64_t* cmask, int32_t* center_idx) {
+                                                              uint64_t* cmask, int32_t* center_idx, uint2* worklist) {
     extern __shared__ unsigned char s_raw[];
-    __shared__ int s_flag[3], s_nlong, s_nover;
+    __shared__ int s_flag[3], s_cnt[3], s_nlong, s_nover;
     __shared__ uint16_t s_nb[16][PREDS_SPREAD];
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
@@ -567,13 +580,28 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
     lds_vu8* s_st = (lds_vu8*)s_raw;                             // [qpad + 64]
     lds_u16* s_list = (lds_u16*)(s_raw + qpad + 64);             // [n_max]
     lds_i32* s_wcnt = (lds_i32*)(s_raw + qpad + 64 + (size_t)qpad * 2);   // [W + 1]
+    // the two work lists, n_max entries each
+    typedef typename WorkList<WL_LDS>::ptr wl_ptr;
+    wl_ptr wl[2];
+    if constexpr (WL_LDS) {
+        const size_t off = ((size_t)qpad + 64 + (size_t)qpad * 2 + ((size_t)bt.W + 1) * 4 + 7) & ~(size_t)7;
+        wl[0] = (wl_ptr)(s_raw + off);
+        wl[1] = wl[0] + bt.n_max;
+    } else {
+        wl[0] = (wl_ptr)worklist + (size_t)b * 2 * bt.n_max;
+        wl[1] = wl[0] + bt.n_max;
+    }
     const double* r = rho + (size_t)b * bt.n_max;
     const uint4* rec = (const uint4*)(preds + (size_t)b * bt.n_max * PRED_CAP);   // 8 pieces per token
     const uint2* hd = heads + (size_t)b * bt.n_max;
     const int Wq = (q + 63) >> 6;
     const int last = bt.n_max - 1;                               // overflow list grows down from here
 
-    if (tid == 0) { s_nlong = 0; s_nover = 0; s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0; }
+    if (tid == 0) {
+        s_nlong = 0; s_nover = 0;
+        s_flag[0] = 0; s_flag[1] = 0; s_flag[2] = 0;
+        s_cnt[0] = 0; s_cnt[1] = 0; s_cnt[2] = 0;
+    }
     __syncthreads();
     // the token indices this thread will publish at the end (words wave, wave + 16, ...): fetched
     // now, so that the last phase does not start with a trip to memory
@@ -584,16 +612,23 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         const int p = ((wave + 16 * k) << 6) + lane;
         pub_ix[k] = (p < q) ? ix[p] : 0;
     }
-#pragma unroll
-    for (int k = 0; k < RESOLVE_CACHED; ++k)
-        if (tid + 1024 * k >= q) h[k] = make_uint2(0, 0);
-    // set-up = round 1, and the two token lists (appended a wavefront at a time)
-    auto setup = [&](int p, uint32_t hx) __attribute__((always_inline)) {
-        const int c = hx & 0xFFFF;
+    // set-up = round 1, and the three token lists (appended a wavefront at a time)
+    auto setup = [&](int p, uint2 hv) __attribute__((always_inline)) {
+        const int c = hv.x & 0xFFFF;
         const bool in = p < q;
         if (in) s_st[p] = (c == 0) ? ST_CENTER : ST_UNKNOWN;
-        const bool lng = in && c > HEAD_PREDS && c <= KP, ovr = in && c > KP;
-        const uint64_t ml = __ballot(lng), mo = __ballot(ovr);
+        const bool sht = in && c >= 1 && c <= HEAD_PREDS, lng = in && c > HEAD_PREDS && c <= KP, ovr = in && c > KP;
+        const uint64_t ms = __ballot(sht), ml = __ballot(lng), mo = __ballot(ovr);
+        if (ms) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&s_cnt[1], __popcll(ms));
+            base = __shfl(base, 0, 64);
+            if (sht) {
+                // (slots of the head past its count hold nothing)
+                const uint32_t j1 = c >= 2 ? (hv.y & 0xFFFFu) : 0xFFFFu, j2 = c >= 3 ? (hv.y >> 16) : 0xFFFFu;
+                wl[1][base + lanes_below(ms, lane)] = wl_entry{(uint32_t)p | (hv.x & 0xFFFF0000u), j1 | (j2 << 16)};
+            }
+        }
         if (ml) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_nlong, __popcll(ml));
@@ -608,20 +643,13 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         }
     };
 #pragma unroll
-    for (int k = 0; k < RESOLVE_CACHED; ++k) setup(tid + 1024 * k, h[k].x);
+    for (int k = 0; k < RESOLVE_CACHED; ++k) setup(tid + 1024 * k, h[k]);
     for (int p0 = 1024 * RESOLVE_CACHED; p0 < q; p0 += 1024) {      // (wave-uniform trip count)
         const int p = p0 + tid;
-        setup(p, p < q ? hd[p].x : 0u);
+        setup(p, p < q ? hd[p] : make_uint2(0, 0));
     }
     __syncthreads();
     const int nlong = s_nlong, nover = s_nover;
-    // pending masks: one bit per predecessor position
-    uint32_t pmh[RESOLVE_CACHED];
-#pragma unroll
-    for (int k = 0; k < RESOLVE_CACHED; ++k) {
-        const int c = h[k].x & 0xFFFF;
-        pmh[k] = (c <= HEAD_PREDS) ? ((1u << c) - 1u) : 0u;
-    }
     int lp = -1, lc = 0;                                         // this thread's listed token
     uint4 l0 = make_uint4(0, 0, 0, 0), l1 = l0;
     uint32_t pml = 0;
@@ -633,47 +661,63 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         pml = (lc >= 15) ? 0x7FFFu : ((1u << lc) - 1u);
     }
     int rounds = 1;
-    // One barrier per round: round r raises s_flag[r % 3] if it leaves a token undecided, and
-    // clears the flag of round r + 1 (last read before the previous barrier) on the way.
+    // One barrier per round: round r reads the work list r & 1 (s_cnt[r % 3] entries) and appends to the
+    // other one (s_cnt[(r + 1) % 3]); it raises s_flag[r % 3] if it leaves a token of the other kinds
+    // undecided, and clears the flag and the count of round r + 2 (last read before the previous
+    // barrier) on the way.
     while (true) {
-        if (tid == 0) s_flag[(rounds + 1) % 3] = 0;
+        if (tid == 0) { s_flag[(rounds + 1) % 3] = 0; s_cnt[(rounds + 2) % 3] = 0; }
         bool still = false;
         auto decide = [&](int p, bool blocked, bool pending) __attribute__((always_inline)) {
             if (blocked) s_st[p] = ST_NOT;
             else if (!pending) s_st[p] = ST_CENTER;
             else still = true;
         };
-        // short lists, from the heads in registers
-#pragma unroll
-        for (int k = 0; k < RESOLVE_CACHED; ++k) {
-            const int p = tid + 1024 * k;
-            if (pmh[k] != 0 && s_st[p] == ST_UNKNOWN) {
-                const int j[HEAD_PREDS] = {(int)(h[k].x >> 16), (int)(h[k].y & 0xFFFF), (int)(h[k].y >> 16)};
+        // short lists: the work list
+        {
+            const int nA = s_cnt[rounds % 3];
+            const wl_ptr A = wl[rounds & 1], Bn = wl[(rounds + 1) & 1];
+            // (plain reads: the three look-ups of an entry go out together; a status that another
+            //  wavefront changes meanwhile is seen in the next round at the latest)
+            typedef __attribute__((address_space(3))) unsigned char lds_u8r;
+            const lds_u8r* s_rd = (const lds_u8r*)s_st;
+            for (int i0 = wave * 64; i0 < nA; i0 += 1024) {              // (wave-uniform trip count)
+                const int i = i0 + lane;
+                const bool have = i < nA;
+                wl_entry e = {0xFFFF0000u, 0xFFFFFFFFu};
+                if (have) e = A[i];
+                const uint32_t p = e.x & 0xFFFFu;
+                uint32_t j[HEAD_PREDS] = {e.x >> 16, e.y & 0xFFFFu, e.y >> 16};
                 bool blocked = false;
+                uint32_t keep[HEAD_PREDS];
+                int nk = 0;
 #pragma unroll
-                for (int s = 0; s < HEAD_PREDS; ++s) {
-                    if (pmh[k] & (1u << s)) {
-                        const unsigned char sj = s_st[j[s]];
-                        blocked |= (sj == ST_CENTER);
-                        if (sj == ST_NOT) pmh[k] &= ~(1u << s);
+                for (int t = 0; t < HEAD_PREDS; ++t) keep[t] = 0xFFFFu;
+#pragma unroll
+                for (int t = 0; t < HEAD_PREDS; ++t) {
+                    const bool real = j[t] != 0xFFFFu;
+                    const unsigned char sj = s_rd[real ? j[t] : 0u];
+                    blocked |= real && sj == ST_CENTER;
+                    if (real && sj == ST_UNKNOWN) {                    // stays on the entry, moved to the front
+                        if (nk == 0) keep[0] = j[t];
+                        else if (nk == 1) keep[1] = j[t];
+                        else keep[2] = j[t];
+                        ++nk;
                     }
                 }
-                decide(p, blocked, pmh[k] != 0);
+                if (have) {
+                    if (blocked) s_st[p] = ST_NOT;
+                    else if (nk == 0) s_st[p] = ST_CENTER;
+                }
+                const bool stay = have && !blocked && nk != 0;
+                const uint64_t m = __ballot(stay);
+                if (m) {
+                    int base = 0;
+                    if (lane == 0) base = atomicAdd(&s_cnt[(rounds + 1) % 3], __popcll(m));
+                    base = __shfl(base, 0, 64);
+                    if (stay) Bn[base + lanes_below(m, lane)] = wl_entry{p | (keep[0] << 16), keep[1] | (keep[2] << 16)};
+                }
             }
-        }
-        for (int p = tid + 1024 * RESOLVE_CACHED; p < q; p += 1024) {     // beyond the cached tokens: heads from memory
-            if (s_st[p] != ST_UNKNOWN) continue;
-            const uint2 hv = hd[p];
-            const int c = hv.x & 0xFFFF;
-            if (c > HEAD_PREDS) continue;
-            const int j[HEAD_PREDS] = {(int)(hv.x >> 16), (int)(hv.y & 0xFFFF), (int)(hv.y >> 16)};
-            bool blocked = false, pending = false;
-            for (int s = 0; s < c; ++s) {
-                const unsigned char sj = s_st[j[s]];
-                blocked |= (sj == ST_CENTER);
-                pending |= (sj == ST_UNKNOWN);
-            }
-            decide(p, blocked, pending);
         }
         // long lists: the first 15 positions from registers, the rest of the record from memory
         if (lp >= 0 && s_st[lp] == ST_UNKNOWN) {
@@ -741,7 +785,7 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         }
         if (still) s_flag[rounds % 3] = 1;
         __syncthreads();
-        const int more = s_flag[rounds % 3];
+        const int more = s_flag[rounds % 3] | s_cnt[(rounds + 1) % 3];
         ++rounds;
         if (!more) break;
     }
@@ -1328,17 +1372,24 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_F32>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
                     rep, w.rho_fix, w.tie_list, w.tie_cnt);
     const size_t qpad = (size_t)((bt.n_max + 63) / 64 * 64);
-    const size_t lds = qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4;
-    static size_t raised = 0;
-    if (lds > 48 * 1024 && lds > raised) {
-        if (hipFuncSetAttribute((const void*)centre_resolve_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    const bool wl_lds = bt.n_max <= RESOLVE_LDS_TOKENS;       // the work lists fit beside the statuses
+    const size_t lds_base = (qpad + 64 + qpad * 2 + ((size_t)bt.W + 1) * 4 + 7) & ~(size_t)7;
+    const size_t lds = lds_base + (wl_lds ? (size_t)bt.n_max * 16 : 0);
+    static size_t raised[2] = {0, 0};
+    const void* fn = wl_lds ? (const void*)centre_resolve_kernel<true> : (const void*)centre_resolve_kernel<false>;
+    if (lds > 48 * 1024 && lds > raised[wl_lds ? 1 : 0]) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PACT_ERR_HIP;
-        raised = lds;
+        raised[wl_lds ? 1 : 0] = lds;
     }
-    PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel, dim3(bt.B), dim3(1024), lds, st, bt, rep,
-                      w.adj, w.rho, rho_opt, w.preds, w.heads, idx, w.tie_list, w.tie_cnt, w.rho_fix, w.status,
-                      w.cnum, w.cmask, center_idx);
+    if (wl_lds)
+        PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel<true>, dim3(bt.B), dim3(1024), lds, st, bt, rep,
+                          w.adj, w.rho, rho_opt, w.preds, w.heads, idx, w.tie_list, w.tie_cnt, w.rho_fix, w.status,
+                          w.cnum, w.cmask, center_idx, w.worklist);
+    else
+        PACT_LAUNCH_SHMEM("centre_resolve", centre_resolve_kernel<false>, dim3(bt.B), dim3(1024), lds, st, bt, rep,
+                          w.adj, w.rho, rho_opt, w.preds, w.heads, idx, w.tie_list, w.tie_cnt, w.rho_fix, w.status,
+                          w.cnum, w.cmask, center_idx, w.worklist);
     if (rank_opt)          // (after the fp64 densities are in place)
         PACT_LAUNCH("density_rank", rank_kernel, dim3((bt.n_max + 63) / 64, bt.B), dim3(1024), st, bt, rep,
                     w.rho, rank_opt);

@@ -46,6 +46,7 @@ constexpr int RHO_RECHECK_CHUNK = 64;                   // kept tokens per parti
 // The first MERGE_SLOTS members of a cluster are noted as they join it (one 128-byte line per
 // cluster), so that the merge of a full reduction needs no pass that builds member lists.
 constexpr int MERGE_BIG = 12, MERGE_SLOTS = 32;
+constexpr int RESOLVE_LDS_TOKENS = 8192;   // samples up to this size keep the work lists of the centre rounds in LDS
 constexpr int32_t OVERFLOW_NEAR_LIST = 1, OVERFLOW_RHO_RECHECK = 2;   // bits of pact_report.refine_overflow
 
 struct WsLayout {
@@ -63,6 +64,7 @@ struct WsLayout {
     size_t rho_fix;                                    // [B][min(RHO_RECHECK_MAX, n_max)][ceil(n_max / RHO_RECHECK_CHUNK)][2] f64 partial sums of those
     size_t offsets, members, big;                      // merge CSR (global row index); ids of the large clusters
     size_t slots;                                      // [total][MERGE_SLOTS] i32: first members of each cluster, in the order they joined
+    size_t worklist;                                   // [B][2][n_max] 8-byte entries: the centre rounds' work lists of samples too large for the LDS
     size_t zeros;                                      // 256 zero bytes
     size_t total;
 };
@@ -108,6 +110,7 @@ inline WsLayout make_layout(int64_t n_max, int64_t B, int64_t total, int64_t qco
     L.members = take(sizeof(int32_t) * total);
     L.big = take(sizeof(int32_t) * total);
     L.slots = take(sizeof(int32_t) * total * MERGE_SLOTS);
+    L.worklist = take(n_max > RESOLVE_LDS_TOKENS ? 16 * B * n_max : 0);
     L.zeros = take(256);
     L.ksplit = take(k_dt == PACT_F32 ? sizeof(uint16_t) * 3 * total * ((dk + 7) / 8 * 8) : 0);   // planes padded to whole 16-byte chunks
     L.total = off;
@@ -121,7 +124,7 @@ struct Ws {
     uint64_t* adj; float* cbest; double* rho_part; double* rho; int32_t* rank; uint32_t* status;
     int32_t* cnum; uint64_t* cmask; uint16_t* preds; uint2* heads; uint32_t* near_list; int32_t* near_cnt; uint32_t* stat;
     int32_t* tie_list; int32_t* tie_cnt; double* rho_fix;
-    int32_t* offsets; int32_t* members; int32_t* big; int32_t* slots; uint32_t* zeros; uint16_t* ksplit;
+    int32_t* offsets; int32_t* members; int32_t* big; int32_t* slots; uint2* worklist; uint32_t* zeros; uint16_t* ksplit;
 };
 
 inline Ws resolve(void* base, const WsLayout& L) {
@@ -140,7 +143,7 @@ inline Ws resolve(void* base, const WsLayout& L) {
     w.tie_list = (int32_t*)(p + L.tie_list); w.tie_cnt = (int32_t*)(p + L.tie_cnt);
     w.rho_fix = (double*)(p + L.rho_fix);
     w.offsets = (int32_t*)(p + L.offsets); w.big = (int32_t*)(p + L.big);
-    w.members = (int32_t*)(p + L.members); w.slots = (int32_t*)(p + L.slots); w.zeros = (uint32_t*)(p + L.zeros);
+    w.members = (int32_t*)(p + L.members); w.slots = (int32_t*)(p + L.slots); w.worklist = (uint2*)(p + L.worklist); w.zeros = (uint32_t*)(p + L.zeros);
     w.ksplit = (uint16_t*)(p + L.ksplit);
     return w;
 }
