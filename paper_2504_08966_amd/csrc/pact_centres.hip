@@ -508,6 +508,116 @@ __device__ __forceinline__ bool check_pending15(const uint4& v0, const uint4& v1
     return blocked;
 }
 
+// The same re-evaluation on the fp64 matrix instruction, for key rows of whole 64-byte quarters
+// (the usual widths).  A work item is (16 listed tokens, 64 kept tokens); each of the workgroup's four
+// wavefronts forms the 16 x 16 dot products of the listed tokens with 16 of the kept ones by
+// v_mfma_f64_16x16x4_f64: lane l supplies element k of row l % 16 of either operand, k running over
+// the quarter l / 16 of the key width (the order of the summands of a dot product is then the same
+// for every pair, which is all that the exactness argument above needs: equal rows give equal dot
+// products), and receives the products of listed tokens 4 v + l / 16, v = 0..3, with kept token
+// l % 16.  Norms are the per-token fp64 norms of the first kernel; everything after the dot product
+// is as above, and the partial sums have the same layout.
+// grid (blocks per sample, B), block 256.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+template <int DT>
+__global__ __launch_bounds__(256) void rho_recheck_mfma_kernel(Batch bt, const char* keys, int dk, const int32_t* idx,
+                                                                const double* __restrict__ nn, pact_report* rep, double* part,
+                                                                const int32_t* tie_list, const int32_t* tie_cnt) {
+    __shared__ double s_hi[4][16], s_lo[4][16];
+    const int b = blockIdx.y;
+    const Seg sg = bt.s[b];
+    const int T = tie_cnt[4 * b];                      // (the same for every workgroup of the sample)
+    const int q = clamp_count(rep[b].n_kept, sg.n);
+    if (T <= 0) return;
+    if (T > RHO_RECHECK_MAX) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(&rep[b].refine_overflow, OVERFLOW_RHO_RECHECK);
+        return;
+    }
+    constexpr int EPL = Elem<DT>::EPL;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nch = (q + RHO_RECHECK_CHUNK - 1) / RHO_RECHECK_CHUNK;
+    const int nrt = (T + 15) >> 4;
+    const size_t row_bytes = (size_t)dk * Elem<DT>::BYTES;
+    const int qchunks = (int)(row_bytes / 64);          // 16-byte chunks per quarter of a row
+    const char* kb = keys + (size_t)sg.base * row_bytes;
+    const double* nnb = nn + sg.base;
+    const int32_t* ix = idx + sg.base;
+    const int32_t* list = tie_list + (size_t)b * RHO_RECHECK_MAX;
+    double* part_b = part + (size_t)b * 2 * rho_fix_tokens(bt.n_max) * rho_fix_chunks(bt.n_max);   // [T][nch][2]
+    const double d_n = (double)sg.d_n;
+    const int i16 = lane & 15, kq = lane >> 4;
+    for (int item = blockIdx.x; item < nrt * nch; item += gridDim.x) {
+        const int rt = item / nch, c = item - rt * nch;
+        // this lane's row of either operand: listed token 16 rt + i16, kept token 64 c + 16 wave + i16
+        const int t_mine = rt * 16 + i16;
+        const int ent = list[min(t_mine, T - 1)];
+        const int p_mine = min(ent & 0xFFFF, q - 1), tokA = min(max(ent >> 16, 0), sg.n - 1);
+        const int pk_mine = c * RHO_RECHECK_CHUNK + wave * 16 + i16;
+        const int tokB = ix[min(pk_mine, q - 1)];
+        const double nnA = nnb[tokA], nnB = nnb[tokB];
+        const char* ra = kb + (size_t)tokA * row_bytes + (size_t)kq * (row_bytes / 4);
+        const char* rb = kb + (size_t)tokB * row_bytes + (size_t)kq * (row_bytes / 4);
+        // eight chunks of either row per trip to memory, the next trip's requested before this one's are multiplied;
+        // four accumulators, so that an instruction does not wait for the one before it
+        constexpr int NBT = 8;
+        f64x4_t acc[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+        uint4 va0[NBT], vb0[NBT], va1[NBT], vb1[NBT];
+        auto fetch = [&](uint4 (&va)[NBT], uint4 (&vb)[NBT], int u0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < NBT; ++u) {
+                const size_t o = (size_t)min(u0 + u, qchunks - 1) * 16;
+                va[u] = *(const uint4*)(ra + o);
+                vb[u] = *(const uint4*)(rb + o);
+            }
+        };
+        auto multiply = [&](const uint4 (&va)[NBT], const uint4 (&vb)[NBT], int u0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < NBT; ++u) {
+                if (u0 + u < qchunks) {                     // (uniform)
+                    double a[8], x[8];
+                    Elem<DT>::widen(va[u], a);
+                    Elem<DT>::widen(vb[u], x);
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[e & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[e], x[e], acc[e & 3], 0, 0, 0);
+                }
+            }
+        };
+        fetch(va0, vb0, 0);
+#pragma unroll 1
+        for (int u0 = 0; u0 < qchunks; u0 += 2 * NBT) {
+            if (u0 + NBT < qchunks) fetch(va1, vb1, u0 + NBT);
+            multiply(va0, vb0, u0);
+            if (u0 + 2 * NBT < qchunks) fetch(va0, vb0, u0 + 2 * NBT);
+            if (u0 + NBT < qchunks) multiply(va1, vb1, u0 + NBT);
+        }
+        // products of listed token 4 v + kq (of this tile) with kept token i16: terms, split, sums over the 16 kept tokens
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int src = 4 * v + kq;                     // the lane that holds that listed token's entry
+            const int p_t = __shfl(p_mine, src, 64);
+            const double nn_t = __shfl(nnA, src, 64);
+            const double dot = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
+            const double d = cos_dist64(dot, nn_t, nnB);
+            const double term = pk_mine >= q ? 0.0 : (pk_mine == p_t ? 1.0 : exp(-d / d_n));
+            double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
+            double lo = term - hi;
+#pragma unroll
+            for (int sft = 1; sft <= 8; sft <<= 1) { hi += __shfl_xor(hi, sft, 64); lo += __shfl_xor(lo, sft, 64); }
+            if (i16 == 0) { s_hi[wave][src] = hi; s_lo[wave][src] = lo; }
+        }
+        __syncthreads();
+        if (tid < 16) {
+            const int t = rt * 16 + tid;
+            const double vh = (s_hi[0][tid] + s_hi[1][tid]) + (s_hi[2][tid] + s_hi[3][tid]);
+            const double vl = (s_lo[0][tid] + s_lo[1][tid]) + (s_lo[2][tid] + s_lo[3][tid]);
+            if (t < T) *(double2*)(part_b + ((size_t)t * nch + c) * 2) = make_double2(vh, vl);
+        }
+        __syncthreads();
+    }
+}
+
 // All rounds of the centre selection in one workgroup per sample, statuses in LDS; then the
 // centres are numbered in ascending token order and published.
 //  * The first round needs no look-ups: nothing is decided yet, so exactly the tokens without a
@@ -1365,7 +1475,23 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     //  the chip holds 512 of them at a time, and 4096 took 0.8 us longer to dispatch; a batch: 8192
     //  shared out equally, since the listed tokens are not spread evenly over the samples)
     const int rb = bt.B == 1 ? 2048 : 8192 / bt.B;
-    if (k_dt == PACT_BF16)
+    // Rows of whole 64-byte quarters can go through the fp64 matrix instruction.  A 16 x 16 tile of dot
+    // products is then one wavefront's chain of dk / 4 instructions (4 us at a key width of 512), against
+    // a couple of trips to memory per 64 pairs for the vector version: with the handful of listed tokens
+    // of one image the vector version is the shorter one (12.3 against 14.9 us at 4010 kept tokens), with
+    // many kept tokens or wide rows the matrix version (16384 kept tokens: 195 -> 58 us; 8 videos:
+    // 48 -> 29 us; 3584-wide rows: 82 -> 52 us).
+    const size_t recheck_row_bytes = (size_t)dk * (k_dt == PACT_BF16 ? 2 : 4);
+    long kept_est = 0;
+    for (int b = 0; b < bt.B; ++b) kept_est += bt.s[b].n - prune_rank(bt.s[b].lambda, bt.s[b].n);
+    const bool quarters = recheck_row_bytes % 64 == 0 && (kept_est >= 6000 || recheck_row_bytes >= 4096);
+    if (quarters && k_dt == PACT_BF16)
+        PACT_LAUNCH("rho_recheck", rho_recheck_mfma_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
+                    w.nn, rep, w.rho_fix, w.tie_list, w.tie_cnt);
+    else if (quarters)
+        PACT_LAUNCH("rho_recheck", rho_recheck_mfma_kernel<PACT_F32>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
+                    w.nn, rep, w.rho_fix, w.tie_list, w.tie_cnt);
+    else if (k_dt == PACT_BF16)
         PACT_LAUNCH("rho_recheck", rho_recheck_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
                     rep, w.rho_fix, w.tie_list, w.tie_cnt);
     else

@@ -1095,6 +1095,19 @@ def test_duplicated_tokens_are_rechecked_and_ordered_by_index():
     g = gu.gpu_reduce(s, 1e-4, lam=0.0)
     assert g["rep"]["refine_overflow"] == 2 and g["rep"]["rho_rechecked"] == 0
     assert_same(g, oracle_reduce(s, 1e-4, lam=0.0), s, "1400 copies of two keys")
+    # a sample large enough for the re-evaluation on the fp64 matrix instruction (6000 kept tokens and more),
+    # in fp32 and bf16: 5700 keys once and 100 keys three times
+    for dtype, dh in (("bf16", 32), ("f32", 16)):
+        big = _random_sample(72, 5800, 2, 2, dh, 64, 0.0, dtype)
+        k = np.concatenate([big.keys, big.keys[:100], big.keys[:100]])
+        h = np.concatenate([big.hidden, big.hidden[:100] * 2.0, big.hidden[:100] * 0.5])
+        s = _mk(k, hidden=h, queries=np.concatenate([big.queries, big.queries[:200]]), name="tiny_bf16" if dtype == "bf16" else "tiny_f32")
+        d_c = _gap_dc(big.keys.reshape(5800, -1)[:1500], frac=0.004)
+        g = gu.gpu_reduce(s, d_c, lam=0.0)
+        assert_same(g, oracle_reduce(s, d_c, lam=0.0), s, f"6000 tokens, 100 keys three times, {dtype}")
+        assert 300 <= g["rep"]["rho_rechecked"] <= 1024 and g["rep"]["refine_overflow"] == 0, g["rep"]
+        copies = np.flatnonzero(np.isin(g["center_idx"], np.arange(5800, 6000)))
+        assert copies.size == 0                                  # of three copies the first one leads
 
 
 def test_report_counts_scores_next_to_the_threshold_and_non_finite_values():
