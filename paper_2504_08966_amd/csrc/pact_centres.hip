@@ -1477,14 +1477,18 @@ int launch_centres(const Batch& bt, const Ws& w, const void* keys, pact_dtype k_
     const int rb = bt.B == 1 ? 2048 : 8192 / bt.B;
     // Rows of whole 64-byte quarters can go through the fp64 matrix instruction.  A 16 x 16 tile of dot
     // products is then one wavefront's chain of dk / 4 instructions (4 us at a key width of 512), against
-    // a couple of trips to memory per 64 pairs for the vector version: with the handful of listed tokens
-    // of one image the vector version is the shorter one (12.3 against 14.9 us at 4010 kept tokens), with
-    // many kept tokens or wide rows the matrix version (16384 kept tokens: 195 -> 58 us; 8 videos:
-    // 48 -> 29 us; 3584-wide rows: 82 -> 52 us).
+    // a couple of trips to memory per 64 pairs for the vector version.  With the handful of listed tokens
+    // of one image, or of a batch of small images, the vector version is the shorter one (4010 kept
+    // tokens: 12.3 against 14.9 us; 16 ragged images: 13.4 against 22.5 us); with many kept tokens or wide
+    // rows the matrix version (16384 kept tokens, 70 listed: 195 -> 58 us; 8 videos of 3450 kept tokens:
+    // 48 -> 29 us; 3584-wide rows: 82 -> 52 us).  How many tokens are listed is known on the device only
+    // (one kernel holding both versions behind a device-side choice ran each of them a quarter to a half
+    // slower), so the host goes by the kept tokens it expects.
     const size_t recheck_row_bytes = (size_t)dk * (k_dt == PACT_BF16 ? 2 : 4);
     long kept_est = 0;
     for (int b = 0; b < bt.B; ++b) kept_est += bt.s[b].n - prune_rank(bt.s[b].lambda, bt.s[b].n);
-    const bool quarters = recheck_row_bytes % 64 == 0 && (kept_est >= 6000 || recheck_row_bytes >= 4096);
+    const bool quarters = recheck_row_bytes % 64 == 0 &&
+                          (kept_est >= (bt.B == 1 ? 6000 : 20000) || recheck_row_bytes >= 4096);
     if (quarters && k_dt == PACT_BF16)
         PACT_LAUNCH("rho_recheck", rho_recheck_mfma_kernel<PACT_BF16>, dim3(rb, bt.B), dim3(256), st, bt, k, dk, idx,
                     w.nn, rep, w.rho_fix, w.tie_list, w.tie_cnt);
