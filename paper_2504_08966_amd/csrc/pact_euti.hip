@@ -570,6 +570,8 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
     __shared__ int s_sel[2][2];
     __shared__ int s_wtot[16];
     __shared__ int s_odd[2];             // scores next to the threshold without being equal to it; non-finite scores
+    __shared__ uint32_t s_mm[2][16], s_cand[64];
+    __shared__ int s_ncand;
     const int b = blockIdx.x;
     const Seg sg = bt.s[b];
     const int n = sg.n;
@@ -597,10 +599,95 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
 
     const int m_rank = prune_rank(sg.lambda, n);
     int k = m_rank;
+    uint32_t prefix = 0, mask = 0;
+    // Selection in one histogram where that works: the keys of a sample share their leading bits
+    // (scores of one image lie within a few binades), so the 4096 bins are laid over the range the
+    // keys actually span, [smallest, largest]; the bin that holds rank k then has a handful of keys,
+    // and one wavefront finds the wanted one among them by counting.  More than 64 keys in that bin
+    // (ties, non-finite values that stretch the range): the radix select below does the whole job.
+    bool selected = false;
+    {
+        uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+        for (int r = 0; r < KREG; ++r)
+            if (tid + 1024 * r < n) { kmin = min(kmin, kreg[r]); kmax = max(kmax, kreg[r]); }
+        for (int i = tid + 1024 * KREG; i < n; i += 1024) { const uint32_t u = s_key[i]; kmin = min(kmin, u); kmax = max(kmax, u); }
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, sft, 64));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, sft, 64));
+        }
+        if (lane == 0) { s_mm[0][wave] = kmin; s_mm[1][wave] = kmax; }
+        for (int i = tid; i < 256 * 16; i += 1024) s_hist[i] = 0;
+        if (tid == 0) s_ncand = 0;
+        __syncthreads();
+        kmin = s_mm[0][lane & 15];
+        kmax = s_mm[1][lane & 15];
+#pragma unroll
+        for (int sft = 8; sft >= 1; sft >>= 1) {
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, sft, 64));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, sft, 64));
+        }
+        const uint32_t range = kmax - kmin;
+        const int nbits = range ? 32 - __builtin_clz(range) : 0;
+        const int bshift = nbits > 12 ? nbits - 12 : 0;                  // (key - kmin) >> bshift < 4096
+#pragma unroll
+        for (int r = 0; r < KREG; ++r)
+            if (tid + 1024 * r < n) atomicAdd(&s_hist[(kreg[r] - kmin) >> bshift], 1);
+        for (int i = tid + 1024 * KREG; i < n; i += 1024) atomicAdd(&s_hist[(s_key[i] - kmin) >> bshift], 1);
+        __syncthreads();
+        // exclusive scan over the bins, four per thread
+        const int c0 = s_hist[4 * tid], c1 = s_hist[4 * tid + 1], c2 = s_hist[4 * tid + 2], c3 = s_hist[4 * tid + 3];
+        const int loc = c0 + c1 + c2 + c3;
+        int inc = loc;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int v = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += v;
+        }
+        if (lane == 63) s_wtot[wave] = inc;
+        __syncthreads();
+        int e = inc - loc;
+        for (int w = 0; w < wave; ++w) e += s_wtot[w];
+        {
+            const int c[4] = {c0, c1, c2, c3};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (k >= e && k < e + c[t]) { s_sel[0][0] = 4 * tid + t; s_sel[0][1] = k - e; s_sel[1][0] = c[t]; }
+                e += c[t];
+            }
+        }
+        __syncthreads();
+        const int sel = s_sel[0][0], kk = s_sel[0][1], ncand = s_sel[1][0];
+        if (ncand <= 64) {                                                   // (uniform)
+#pragma unroll
+            for (int r = 0; r < KREG; ++r)
+                if (tid + 1024 * r < n && (int)((kreg[r] - kmin) >> bshift) == sel) s_cand[atomicAdd(&s_ncand, 1)] = kreg[r];
+            for (int i = tid + 1024 * KREG; i < n; i += 1024) {
+                const uint32_t u = s_key[i];
+                if ((int)((u - kmin) >> bshift) == sel) s_cand[atomicAdd(&s_ncand, 1)] = u;
+            }
+            __syncthreads();
+            if (wave == 0) {
+                const uint32_t v = lane < ncand ? s_cand[lane] : 0xFFFFFFFFu;
+                int below = 0, equal = 0;
+                for (int j = 0; j < ncand; ++j) {
+                    const uint32_t u = s_cand[j];
+                    below += u < v;
+                    equal += u == v;
+                }
+                if (lane < ncand && below <= kk && kk < below + equal) s_mm[0][0] = v;   // (the same value from every lane that qualifies)
+            }
+            __syncthreads();
+            prefix = s_mm[0][0];
+            selected = true;
+        }
+        __syncthreads();                   // (s_hist, s_sel and s_wtot are used again below)
+    }
+    if (!selected) {
     // Radix select, 8 bits per pass from the top.  Scores of one image share their leading bits,
     // so a plain histogram would serialise thousands of atomics on a handful of LDS words: every
     // bin has 16 copies (one per lane & 15, in 16 different banks), summed after the pass.
-    uint32_t prefix = 0, mask = 0;
     for (int i = tid; i < 256 * 16; i += 1024) s_hist[i] = 0;
     __syncthreads();
     for (int pass = 0; pass < 4; ++pass) {
@@ -649,6 +736,7 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
         prefix |= (uint32_t)s_sel[pass & 1][0] << shift;
         mask |= 255u << shift;
         k = s_sel[pass & 1][1];
+    }
     }
     const uint32_t tau = prefix;
 
