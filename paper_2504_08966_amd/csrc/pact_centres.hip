@@ -638,6 +638,7 @@ __global__ __launch_bounds__(256) void rho_recheck_mfma_kernel(Batch bt, const c
 // lists: long lists from the front, overflowed from the back) + W * 4 bytes (centres per word)
 // [+ 2 * 8 * n_max bytes of work lists].
 constexpr int RESOLVE_CACHED = 4;
+constexpr int RESOLVE_LOOKS = 2;         // looks at a work-list entry's predecessors per round (7 -> 5 rounds on a 4000-token image; a third look gains nothing, and two looks at the long lists cost more than the round they save)
 typedef uint32_t wl_entry __attribute__((ext_vector_type(2)));      // position | predecessor << 16, two more predecessors (0xFFFF: none)
 typedef __attribute__((address_space(3))) wl_entry lds_wl_entry;
 template <bool WL_LDS> struct WorkList;
@@ -798,28 +799,36 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
                 if (have) e = A[i];
                 const uint32_t p = e.x & 0xFFFFu;
                 uint32_t j[HEAD_PREDS] = {e.x >> 16, e.y & 0xFFFFu, e.y >> 16};
-                bool blocked = false;
+                bool blocked = false, done = !have;
                 uint32_t keep[HEAD_PREDS];
                 int nk = 0;
+                // (RESOLVE_LOOKS looks per round, each followed by what it decides: what the other
+                //  wavefronts decide in their first look is there for the second)
 #pragma unroll
-                for (int t = 0; t < HEAD_PREDS; ++t) keep[t] = 0xFFFFu;
+                for (int look = 0; look < RESOLVE_LOOKS; ++look) {
+                    nk = 0;
 #pragma unroll
-                for (int t = 0; t < HEAD_PREDS; ++t) {
-                    const bool real = j[t] != 0xFFFFu;
-                    const unsigned char sj = s_rd[real ? j[t] : 0u];
-                    blocked |= real && sj == ST_CENTER;
-                    if (real && sj == ST_UNKNOWN) {                    // stays on the entry, moved to the front
-                        if (nk == 0) keep[0] = j[t];
-                        else if (nk == 1) keep[1] = j[t];
-                        else keep[2] = j[t];
-                        ++nk;
+                    for (int t = 0; t < HEAD_PREDS; ++t) keep[t] = 0xFFFFu;
+#pragma unroll
+                    for (int t = 0; t < HEAD_PREDS; ++t) {
+                        const bool real = j[t] != 0xFFFFu;
+                        const unsigned char sj = look == 0 ? s_rd[real ? j[t] : 0u] : s_st[real ? j[t] : 0u];
+                        blocked |= real && sj == ST_CENTER;
+                        if (real && sj == ST_UNKNOWN) {                    // stays on the entry, moved to the front
+                            if (nk == 0) keep[0] = j[t];
+                            else if (nk == 1) keep[1] = j[t];
+                            else keep[2] = j[t];
+                            ++nk;
+                        }
+                    }
+#pragma unroll
+                    for (int t = 0; t < HEAD_PREDS; ++t) j[t] = keep[t];
+                    if (!done) {
+                        if (blocked) { s_st[p] = ST_NOT; done = true; }
+                        else if (nk == 0) { s_st[p] = ST_CENTER; done = true; }
                     }
                 }
-                if (have) {
-                    if (blocked) s_st[p] = ST_NOT;
-                    else if (nk == 0) s_st[p] = ST_CENTER;
-                }
-                const bool stay = have && !blocked && nk != 0;
+                const bool stay = !done;
                 const uint64_t m = __ballot(stay);
                 if (m) {
                     int base = 0;
