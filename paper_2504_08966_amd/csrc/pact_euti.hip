@@ -214,8 +214,42 @@ __host__ __device__ __forceinline__ int hnorm_split(int n, int share) {
 //       supplied the global query ([B, qcols]), its widening to fp64 (1024 columns per block);
 //   the other blocks: |h_i|_2 in fp64, one wavefront per token, 16 tokens per block.
 // grid (nq_blocks + ceil(n_max/16), B), block 1024.
+// Where column c of the global query goes.  The logits kernel for grouped-query heads wants it
+// laid out as its lanes read it (see there): element k of 16-byte chunk cc of query head
+// kvh * rep + r at ((r * epl + k) * n_kv + kvh) * lph + cc; rep == 0: as it is.
+struct QgLayout {
+    int rep, n_kv, d_h, lph, epl;
+    __device__ __forceinline__ int at(int c) const {
+        if (rep == 0) return c;
+        const int j = c / d_h, e = c - j * d_h;
+        return (((j % rep) * epl + (e % epl)) * n_kv + j / rep) * lph + e / epl;
+    }
+};
+
+// Sum over each group of `width` neighbouring lanes (a power of two), left in every lane of the
+// group: lane l adds the value of lane l ^ 1, l ^ 2, ... in turn.  Inside a row of 16 lanes the
+// partner's value comes through the data-parallel lane permutes of the vector unit (for a sum, a
+// mirror image of the group of 8 or 16 serves as well as the exchange of its halves: the partner
+// holds the same partial sum), beyond that through a shuffle; a shuffle of a double is two trips
+// through the LDS crossbar, and 28 of them per wavefront were a quarter of the logits kernel.
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)u, (int)(uint32_t)u, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(u >> 32), (int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double group_sum_f64(double v, int width) {
+    if (width > 1) v += dpp_f64<0xB1>(v);            // quad_perm [1,0,3,2]
+    if (width > 2) v += dpp_f64<0x4E>(v);            // quad_perm [2,3,0,1]
+    if (width > 4) v += dpp_f64<0x141>(v);           // row_half_mirror
+    if (width > 8) v += dpp_f64<0x140>(v);           // row_mirror
+    for (int sft = 16; sft < width; sft <<= 1) v += __shfl_xor(v, sft, 64);
+    return v;
+}
+
 template <int HDT, int QDT>
 __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols, int q_per_token, int nq_blocks,
+                                                             QgLayout lay,
                                                              const double* __restrict__ qg_part,
                                                              const char* __restrict__ q_given,
                                                              double* __restrict__ qg,
@@ -244,7 +278,7 @@ __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols
                 double t = 0.0;
 #pragma unroll
                 for (int k = 0; k < 16; ++k) t += s_p[k][cl];
-                qg[(size_t)b * qcols + c] = t / (double)sg.n;
+                qg[(size_t)b * qcols + lay.at(c)] = t / (double)sg.n;
             }
         } else {
             const int c = blockIdx.x * 1024 + threadIdx.x;
@@ -253,7 +287,7 @@ __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols
                 float f;
                 if (QDT == PACT_BF16) f = __uint_as_float((uint32_t)(*(const uint16_t*)p) << 16);
                 else f = *(const float*)p;
-                qg[(size_t)b * qcols + c] = (double)f;
+                qg[(size_t)b * qcols + lay.at(c)] = (double)f;
             }
         }
         return;
@@ -320,10 +354,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
         // i.e. at (r * EPL + k) * (lanes that hold the key row) + (the lane that needs it).
         constexpr int EPL = Elem<KDT>::EPL;
         const int klanes = n_kv * lph;
-        for (int c = threadIdx.x; c < qcols; c += 1024) {
-            const int j = c / d_h, e = c - j * d_h;
-            s_qg[(((j % rep) * EPL + (e % EPL)) * n_kv + j / rep) * lph + e / EPL] = qgb[c];
-        }
+        for (int c = threadIdx.x; c < qcols; c += 1024) s_qg[c] = qgb[c];      // (left in this order by the kernel before)
         __syncthreads();
         if (i < sg.n) {
             const size_t g = (size_t)sg.base + i;
@@ -345,8 +376,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
             }
 #pragma unroll
             for (int r = 0; r < LOGITS_MAX_REP; ++r)
-                if (r < rep)
-                    for (int sft = 1; sft < lph; sft <<= 1) acc[r] += __shfl_xor(acc[r], sft, 64);
+                if (r < rep) acc[r] = group_sum_f64(acc[r], lph);
             if (klane && (lane & (lph - 1)) == 0) {
 #pragma unroll
                 for (int r = 0; r < LOGITS_MAX_REP; ++r)
@@ -371,7 +401,7 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
 #pragma unroll
                 for (int k = 0; k < Elem<KDT>::EPL; ++k) acc = fma(x[k], qq[k], acc);
             }
-            for (int sft = 1; sft < lph; sft <<= 1) acc += __shfl_xor(acc, sft, 64);
+            acc = group_sum_f64(acc, lph);
             if (klane && (lane & (lph - 1)) == 0) {
                 const int j = lane / lph;
                 logits[g * n_q + j] = acc;
@@ -839,13 +869,16 @@ static int launch_qglobal_hnorm(const Batch& bt, const Ws& w, const ScoreIn& in,
     const int share = hnorm_share(bt);
     const int stream = hidden_streams(bt.total, in.h, Elem<HDT>::BYTES) ? 1 : 0;
     dim3 grid(nq_blocks + (hnorm_split(bt.n_max, share) + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG, bt.B);
+    const int kbytes = in.k_dt == PACT_BF16 ? 2 : 4;
+    QgLayout lay = {0, in.n_kv, in.d_h, in.d_h * kbytes / 16, 16 / kbytes};
+    if (logits_grouped(in.n_kv, in.n_q, in.d_h, kbytes)) lay.rep = in.n_q / in.n_kv;
     if (in.q_dt == PACT_BF16)
         PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_BF16>), grid, dim3(1024), st, bt, qcols,
-                    in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
+                    in.q_per_token ? 1 : 0, nq_blocks, lay, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
                     in.h, w.hnorm, share, stream);
     else
         PACT_LAUNCH("qglobal_hnorm", (qglobal_hnorm_kernel<HDT, PACT_F32>), grid, dim3(1024), st, bt, qcols,
-                    in.q_per_token ? 1 : 0, nq_blocks, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
+                    in.q_per_token ? 1 : 0, nq_blocks, lay, w.qg_part, (const char*)in.q, w.qg, (const char*)in.hidden,
                     in.h, w.hnorm, share, stream);
     return PACT_OK;
 }
