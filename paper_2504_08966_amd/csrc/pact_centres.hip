@@ -89,8 +89,7 @@ __device__ __forceinline__ void nearest_candidate(lds_i32* cand, lds_i32* ctok, 
                 }
             }
         }
-#pragma unroll
-        for (int s = 1; s <= 4; s <<= 1) acc += __shfl_xor(acc, s, 64);
+        acc = group_sum_f32<8>(acc);
         const double den = sqrt(nnp * nnc);
         float cv = den > 0.0 ? (float)((double)acc / den) : 0.0f;
         if (valid && sub == 0) ccos[ci] = cv;
@@ -603,8 +602,8 @@ __global__ __launch_bounds__(256) void rho_recheck_mfma_kernel(Batch bt, const c
             const double term = pk_mine >= q ? 0.0 : (pk_mine == p_t ? 1.0 : exp(-d / d_n));
             double hi = rint(term * 1073741824.0) * (1.0 / 1073741824.0);
             double lo = term - hi;
-#pragma unroll
-            for (int sft = 1; sft <= 8; sft <<= 1) { hi += __shfl_xor(hi, sft, 64); lo += __shfl_xor(lo, sft, 64); }
+            hi = group_sum_f64(hi, 16);
+            lo = group_sum_f64(lo, 16);
             if (i16 == 0) { s_hi[wave][src] = hi; s_lo[wave][src] = lo; }
         }
         __syncthreads();
@@ -1102,9 +1101,7 @@ __device__ __forceinline__ double group_dot64(const char* mine, const char* othe
             }
         }
     }
-#pragma unroll
-    for (int sft = 1; sft <= 8; sft <<= 1) acc += __shfl_xor(acc, sft, 64);
-    return acc;
+    return group_sum_f64(acc, 16);
 }
 
 // Dot product in fp64 of two rows whose 16-byte chunks the 16 lanes of a group already hold (chunks
@@ -1126,10 +1123,8 @@ __device__ __forceinline__ void chunk_dots64(const double (&a)[4][8], const uint
             for (int i = 0; i < EPL; ++i) { acc = fma(a[u][i], x[i], acc); acc2 = fma(x[i], x[i], acc2); }
         }
     }
-#pragma unroll
-    for (int sft = 1; sft <= 8; sft <<= 1) { acc += __shfl_xor(acc, sft, 64); acc2 += __shfl_xor(acc2, sft, 64); }
-    dot = acc;
-    nn_other = acc2;
+    dot = group_sum_f64(acc, 16);
+    nn_other = group_sum_f64(acc2, 16);
 }
 
 // Densities of the listed tokens again, entirely in fp64 (Eq. 5 and Eq. 6 as they are written:
@@ -1244,12 +1239,9 @@ __global__ __launch_bounds__(256) void rho_recheck_kernel(Batch bt, const char* 
                     }
                 }
             }
+            nnp = group_sum_f64(nnp, 16);
 #pragma unroll
-            for (int sft = 1; sft <= 8; sft <<= 1) {
-                nnp += __shfl_xor(nnp, sft, 64);
-#pragma unroll
-                for (int s = 0; s < PER; ++s) { dot[s] += __shfl_xor(dot[s], sft, 64); nnk[s] += __shfl_xor(nnk[s], sft, 64); }
-            }
+            for (int s = 0; s < PER; ++s) { dot[s] = group_sum_f64(dot[s], 16); nnk[s] = group_sum_f64(nnk[s], 16); }
 #pragma unroll
             for (int s = 0; s < PER; ++s) {
                 const int pk = c * RHO_RECHECK_CHUNK + s * 16 + g;
@@ -1330,8 +1322,7 @@ __device__ __forceinline__ void recover_body(const Batch& bt, const NearArgs& a,
             load_batch(0);
             float gm = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
             for (int w = 64 + part; w < Wc; w += 16) gm = fmaxf(gm, cb[(size_t)w * bt.n_max + t]);
-#pragma unroll
-            for (int sft = 1; sft <= 8; sft <<= 1) gm = fmaxf(gm, __shfl_xor(gm, sft, 64));
+            gm = group_max_f32<16>(gm);
             if (gm >= t_lo) {
                 const float floor32 = fmaxf(gm - 2.0f * margin, t_lo);
                 const bool clear = (double)gm - cthr > (double)margin;   // the nearest is certainly within alpha*d_c

@@ -226,27 +226,6 @@ struct QgLayout {
     }
 };
 
-// Sum over each group of `width` neighbouring lanes (a power of two), left in every lane of the
-// group: lane l adds the value of lane l ^ 1, l ^ 2, ... in turn.  Inside a row of 16 lanes the
-// partner's value comes through the data-parallel lane permutes of the vector unit (for a sum, a
-// mirror image of the group of 8 or 16 serves as well as the exchange of its halves: the partner
-// holds the same partial sum), beyond that through a shuffle; a shuffle of a double is two trips
-// through the LDS crossbar, and 28 of them per wavefront were a quarter of the logits kernel.
-template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
-    const uint64_t u = __builtin_bit_cast(uint64_t, v);
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)u, (int)(uint32_t)u, CTRL, 0xF, 0xF, true);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(u >> 32), (int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
-    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
-__device__ __forceinline__ double group_sum_f64(double v, int width) {
-    if (width > 1) v += dpp_f64<0xB1>(v);            // quad_perm [1,0,3,2]
-    if (width > 2) v += dpp_f64<0x4E>(v);            // quad_perm [2,3,0,1]
-    if (width > 4) v += dpp_f64<0x141>(v);           // row_half_mirror
-    if (width > 8) v += dpp_f64<0x140>(v);           // row_mirror
-    for (int sft = 16; sft < width; sft <<= 1) v += __shfl_xor(v, sft, 64);
-    return v;
-}
-
 template <int HDT, int QDT>
 __global__ __launch_bounds__(1024) void qglobal_hnorm_kernel(Batch bt, int qcols, int q_per_token, int nq_blocks,
                                                              QgLayout lay,
@@ -438,11 +417,9 @@ __global__ __launch_bounds__(1024) void score_logits_kernel(Batch bt, const char
         if (j < n_q) {                                             // (whole groups of 16 lanes take the branch)
             const double v = t < cnt ? s_l[t][j] : -INFINITY;
             double m = v;
-#pragma unroll
-            for (int sft = 1; sft <= 8; sft <<= 1) m = fmax(m, __shfl_xor(m, sft, 64));
+            m = group_max_f64<16>(m);
             double e = t < cnt ? exp(v - m) : 0.0;
-#pragma unroll
-            for (int sft = 1; sft <= 8; sft <<= 1) e += __shfl_xor(e, sft, 64);
+            e = group_sum_f64(e, 16);
             if (t == 0) {
                 const int smwg = (bt.n_max + SCORE_TOK_PER_WG - 1) / SCORE_TOK_PER_WG;
                 double* out = sm_part + (((size_t)b * smwg + blockIdx.x) * n_q + j) * 2;

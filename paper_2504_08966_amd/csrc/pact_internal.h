@@ -293,6 +293,57 @@ template <> struct Elem<PACT_F32> {
     }
 };
 
+// Reductions over each group of `width` neighbouring lanes (a power of two), left in every lane
+// of the group: lane l combines with lane l ^ 1, l ^ 2, ... in turn.  Inside a row of 16 lanes the
+// partner's value comes through the data-parallel lane permutes of the vector unit (for a sum or
+// a maximum a mirror image of the group of 8 or 16 serves as well as the exchange of its halves:
+// the partner holds the same partial result, so the values are those of the exchange, bit for bit),
+// beyond that through a shuffle; a shuffle of a double is two trips through the LDS crossbar, and
+// 28 of them per wavefront were a quarter of the logits kernel with 28 query heads.
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v) {
+    const int u = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(u, u, CTRL, 0xF, 0xF, true));
+}
+template <int CTRL> __device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)u, (int)(uint32_t)u, CTRL, 0xF, 0xF, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(u >> 32), (int)(uint32_t)(u >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;   // quad_perm [1,0,3,2], [2,3,0,1], row_half_mirror, row_mirror
+__device__ __forceinline__ double group_sum_f64(double v, int width) {
+    if (width > 1) v += dpp_f64<DPP_XOR1>(v);
+    if (width > 2) v += dpp_f64<DPP_XOR2>(v);
+    if (width > 4) v += dpp_f64<DPP_HALF_MIRROR>(v);
+    if (width > 8) v += dpp_f64<DPP_MIRROR>(v);
+    for (int sft = 16; sft < width; sft <<= 1) v += __shfl_xor(v, sft, 64);
+    return v;
+}
+template <int WIDTH> __device__ __forceinline__ double group_max_f64(double v) {
+    static_assert(WIDTH == 8 || WIDTH == 16, "within a row of 16 lanes");
+    v = fmax(v, dpp_f64<DPP_XOR1>(v));
+    v = fmax(v, dpp_f64<DPP_XOR2>(v));
+    v = fmax(v, dpp_f64<DPP_HALF_MIRROR>(v));
+    if (WIDTH > 8) v = fmax(v, dpp_f64<DPP_MIRROR>(v));
+    return v;
+}
+template <int WIDTH> __device__ __forceinline__ float group_sum_f32(float v) {
+    static_assert(WIDTH == 8 || WIDTH == 16, "within a row of 16 lanes");
+    v += dpp_f32<DPP_XOR1>(v);
+    v += dpp_f32<DPP_XOR2>(v);
+    v += dpp_f32<DPP_HALF_MIRROR>(v);
+    if (WIDTH > 8) v += dpp_f32<DPP_MIRROR>(v);
+    return v;
+}
+template <int WIDTH> __device__ __forceinline__ float group_max_f32(float v) {
+    static_assert(WIDTH == 8 || WIDTH == 16, "within a row of 16 lanes");
+    v = fmaxf(v, dpp_f32<DPP_XOR1>(v));
+    v = fmaxf(v, dpp_f32<DPP_XOR2>(v));
+    v = fmaxf(v, dpp_f32<DPP_HALF_MIRROR>(v));
+    if (WIDTH > 8) v = fmaxf(v, dpp_f32<DPP_MIRROR>(v));
+    return v;
+}
+
 __device__ __forceinline__ double wave_sum_f64(double v) {
 #pragma unroll
     for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
