@@ -133,6 +133,23 @@ template <int L> __device__ __forceinline__ void file_ballots2(uint32_t& lo, uin
 template <int XOR> __device__ __forceinline__ double swizzle_xor(double v) {
     static_assert(XOR >= 1 && XOR < 32, "within 32 lanes");
     const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    if constexpr (XOR < 16) {
+        // inside a row of 16 lanes the vector unit's own lane permutes do it (no trip through the LDS
+        // crossbar): quad permutes for 1 and 2, a rotation by 8 for 8, and for 4 a shift by 4 either
+        // way, each written to the banks of 4 lanes whose partner lies that way
+        auto half = [](int w) __attribute__((always_inline)) {
+            if constexpr (XOR == 1) return __builtin_amdgcn_update_dpp(w, w, 0xB1, 0xF, 0xF, false);
+            else if constexpr (XOR == 2) return __builtin_amdgcn_update_dpp(w, w, 0x4E, 0xF, 0xF, false);
+            else if constexpr (XOR == 8) return __builtin_amdgcn_update_dpp(w, w, 0x128, 0xF, 0xF, false);
+            else {
+                static_assert(XOR == 4, "1, 2, 4 or 8");
+                const int t = __builtin_amdgcn_update_dpp(w, w, 0x104, 0xF, 0x5, false);    // row_shl:4 -> banks 0, 2
+                return __builtin_amdgcn_update_dpp(t, w, 0x114, 0xF, 0xA, false);           // row_shr:4 -> banks 1, 3
+            }
+        };
+        const uint32_t lo = (uint32_t)half((int)(uint32_t)u), hi = (uint32_t)half((int)(uint32_t)(u >> 32));
+        return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+    }
     const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)u, (XOR << 10) | 0x1f);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_swizzle((int)(uint32_t)(u >> 32), (XOR << 10) | 0x1f);
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
