@@ -344,15 +344,16 @@ template <int WIDTH> __device__ __forceinline__ float group_max_f32(float v) {
     return v;
 }
 
+// Over the whole wavefront (all 64 lanes active): neighbours first, inside the rows of 16 lanes through
+// the lane permutes, then the four rows through two shuffles - 4 trips through the LDS crossbar instead
+// of 12, which is half a microsecond in a wavefront that waits for the result.
 __device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, 64);
-    return v;   // butterfly: every lane ends with the bit-identical total
+    return group_sum_f64(v, 64);   // butterfly: every lane ends with the bit-identical total
 }
 __device__ __forceinline__ double wave_max_f64(double v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) v = fmax(v, __shfl_xor(v, s, 64));
-    return v;
+    v = group_max_f64<16>(v);
+    v = fmax(v, __shfl_xor(v, 16, 64));
+    return fmax(v, __shfl_xor(v, 32, 64));
 }
 
 // fp64 dot product of two rows of dk elements, computed by one full wavefront; the partition
