@@ -368,13 +368,8 @@ __device__ __forceinline__ int preds_of_row(int p, int q, const double* r, const
         const int w = w0 + lane;
         uint64_t word = (w < Wq) ? row[w] : 0ull;
         const int cnt = __popcll(word);
-        int inc = cnt;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int t = __shfl_up(inc, d, 64);
-            if (lane >= d) inc += t;
-        }
-        const int nbits = __shfl(inc, 63, 64);
+        const int inc = wave_scan_incl_i32(cnt);
+        const int nbits = lane63_of(inc);
         if (nbits <= PREDS_SPREAD) {
             int at = inc - cnt;
             while (word) {                                   // (no memory access in this loop)
@@ -732,7 +727,7 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         if (ms) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_cnt[1], __popcll(ms));
-            base = __shfl(base, 0, 64);
+            base = lane0_of(base);
             if (sht) {
                 // (slots of the head past its count hold nothing)
                 const uint32_t j1 = c >= 2 ? (hv.y & 0xFFFFu) : 0xFFFFu, j2 = c >= 3 ? (hv.y >> 16) : 0xFFFFu;
@@ -742,13 +737,13 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         if (ml) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_nlong, __popcll(ml));
-            base = __shfl(base, 0, 64);
+            base = lane0_of(base);
             if (lng) s_list[base + lanes_below(ml, lane)] = (uint16_t)p;
         }
         if (mo) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_nover, __popcll(mo));
-            base = __shfl(base, 0, 64);
+            base = lane0_of(base);
             if (ovr) s_list[last - (base + lanes_below(mo, lane))] = (uint16_t)p;
         }
     };
@@ -832,7 +827,7 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
                 if (m) {
                     int base = 0;
                     if (lane == 0) base = atomicAdd(&s_cnt[(rounds + 1) % 3], __popcll(m));
-                    base = __shfl(base, 0, 64);
+                    base = lane0_of(base);
                     if (stay) Bn[base + lanes_below(m, lane)] = wl_entry{p | (keep[0] << 16), keep[1] | (keep[2] << 16)};
                 }
             }
@@ -921,14 +916,9 @@ __global__ __launch_bounds__(1024) void centre_resolve_kernel(Batch bt, pact_rep
         for (int w0 = 0; w0 < Wq; w0 += 64) {
             const int w = w0 + lane;
             const int v = (w < Wq) ? s_wcnt[w] : 0;
-            int inc = v;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int t = __shfl_up(inc, d, 64);
-                if (lane >= d) inc += t;
-            }
+            const int inc = wave_scan_incl_i32(v);
             if (w < Wq) s_wcnt[w] = run + inc - v;
-            run += __shfl(inc, 63, 64);
+            run += lane63_of(inc);
         }
         if (lane == 0) s_wcnt[Wq] = run;
     }

@@ -646,12 +646,7 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
         // exclusive scan over the bins, four per thread
         const int c0 = s_hist[4 * tid], c1 = s_hist[4 * tid + 1], c2 = s_hist[4 * tid + 2], c3 = s_hist[4 * tid + 3];
         const int loc = c0 + c1 + c2 + c3;
-        int inc = loc;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int v = __shfl_up(inc, d, 64);
-            if (lane >= d) inc += v;
-        }
+        const int inc = wave_scan_incl_i32(loc);
         if (lane == 63) s_wtot[wave] = inc;
         __syncthreads();
         int e = inc - loc;
@@ -725,12 +720,7 @@ __global__ __launch_bounds__(1024) void score_prune_kernel(Batch bt, const float
             const int c0 = s_bin[4 * tid], c1 = s_bin[4 * tid + 1];
             const int c2 = s_bin[4 * tid + 2], c3 = s_bin[4 * tid + 3];
             const int loc = c0 + c1 + c2 + c3;
-            int inc = loc;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int v = __shfl_up(inc, d, 64);
-                if (lane >= d) inc += v;
-            }
+            const int inc = wave_scan_incl_i32(loc);
             int e = inc - loc;   // keys with a smaller digit
             const int c[4] = {c0, c1, c2, c3};
 #pragma unroll

@@ -344,6 +344,23 @@ template <int WIDTH> __device__ __forceinline__ float group_max_f32(float v) {
     return v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (all active), on the vector unit's lane
+// permutes: shifts by 1, 2, 4 and 8 inside each row of 16, then lane 15 of rows 0 and 2 to rows 1
+// and 3, then lane 31 to rows 2 and 3.  Six dependent vector instructions instead of six trips
+// through the LDS crossbar.
+__device__ __forceinline__ int wave_scan_incl_i32(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);     // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);     // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);     // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);     // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);     // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);     // row_bcast:31 -> rows 2, 3
+    return v;
+}
+// value of lane 0 / lane 63 of a wavefront-wide register, as a scalar
+__device__ __forceinline__ int lane0_of(int v) { return __builtin_amdgcn_readlane(v, 0); }
+__device__ __forceinline__ int lane63_of(int v) { return __builtin_amdgcn_readlane(v, 63); }
+
 // Over the whole wavefront (all 64 lanes active): neighbours first, inside the rows of 16 lanes through
 // the lane permutes, then the four rows through two shuffles - 4 trips through the LDS crossbar instead
 // of 12, which is half a microsecond in a wavefront that waits for the result.

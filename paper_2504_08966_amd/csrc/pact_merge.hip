@@ -70,12 +70,7 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
     const int c0 = min(C, tid * chunk), c1 = min(C, c0 + chunk);
     int loc = 0;
     for (int c = c0; c < c1; ++c) loc += s_cur[c];
-    int inc = loc;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int v = __shfl_up(inc, d, 64);
-        if (lane >= d) inc += v;
-    }
+    const int inc = wave_scan_incl_i32(loc);
     if (lane == 63) s_wtot[wave] = inc;
     // the large clusters (sizes are still in s_cur), appended a wavefront at a time
     int32_t* bigl = big + sg.base;
@@ -86,7 +81,7 @@ __global__ __launch_bounds__(1024) void scan_fill_kernel(Batch bt, const int32_t
         if (m) {
             int base = 0;
             if (lane == 0) base = atomicAdd(&s_nbig, __popcll(m));
-            base = __shfl(base, 0, 64);
+            base = lane0_of(base);
             if (isbig) bigl[base + __popcll(m & ((1ull << lane) - 1ull))] = c;
         }
     }
