@@ -94,8 +94,10 @@ __device__ __forceinline__ void nearest_candidate(lds_i32* cand, lds_i32* ctok, 
         float cv = den > 0.0 ? (float)((double)acc / den) : 0.0f;
         if (valid && sub == 0) ccos[ci] = cv;
         if (!valid) cv = -INFINITY;
+        // (the eight lanes of a candidate hold the same value: the other candidate of the row of 16 through a rotation)
+        cv = fmaxf(cv, dpp_f32<0x128>(cv));                  // row_ror:8
 #pragma unroll
-        for (int s = 8; s <= 32; s <<= 1) cv = fmaxf(cv, __shfl_xor(cv, s, 64));
+        for (int s = 16; s <= 32; s <<= 1) cv = fmaxf(cv, __shfl_xor(cv, s, 64));
         top = fmaxf(top, cv);
     }
     // 2. the candidates that can still be the nearest, compacted in place (order kept)
@@ -214,10 +216,11 @@ __global__ __launch_bounds__(256) void post_gram_kernel(Batch bt, const char* __
         }
         const int mine = (cnt > gw) ? (cnt - gw + nw - 1) / nw : 0;     // pairs of this wavefront
         for (int k = 0; k < mine; ++k) {
-            const uint32_t pi_raw = (uint32_t)__shfl((int)my_pi, k, 64), pj = (uint32_t)__shfl((int)my_pj, k, 64);
+            // (k is the same in every lane: scalar lane reads)
+            const uint32_t pi_raw = (uint32_t)__builtin_amdgcn_readlane((int)my_pi, k), pj = (uint32_t)__builtin_amdgcn_readlane((int)my_pj, k);
             const uint32_t pi = pi_raw & ~NEAR_MIRROR;
             const bool both = (pi_raw & NEAR_MIRROR) != 0;
-            const int ti = __shfl(my_ti, k, 64), tj = __shfl(my_tj, k, 64);
+            const int ti = __builtin_amdgcn_readlane(my_ti, k), tj = __builtin_amdgcn_readlane(my_tj, k);
             double d = 0.0;
             if (pi != pj) {
                 const double dot = wave_dot64<DT>(kb + (size_t)ti * row_bytes, kb + (size_t)tj * row_bytes, dk, lane);
